@@ -1,0 +1,147 @@
+/*
+ * libsom — batch self-organising-map training epoch on one AMD MI355X (gfx950).
+ *
+ * C ABI, plain pointers and sizes.  Every pointer argument is marked [device] (memory of the context's GPU,
+ * e.g. obtained from hipMalloc or a torch tensor's data_ptr) or [host].  All matrices are row-major.
+ *
+ * Notation (the paper's, Section 3.3.1):
+ *   X      N x D samples, float32, leading dimension ldx >= D (in floats)
+ *   idx    optional list of m presented row numbers into X (Section 3.1, Eq. 2: the iteration subset);
+ *          NULL means rows 0..N-1 are presented and m must equal N
+ *   W      K x D node weights, float32, dense (leading dimension D)
+ *   b(x)   best-matching unit of x: argmin_k |x - w_k|^2 under the weights at the start of the epoch,
+ *          lowest node index among exact float32 minima
+ *   S_k    sum of the presented samples whose BMU is k;  n_k their count
+ *   G      K x K neighbourhood distances between nodes, float32: G[k*K + j] is the distance from BMU node k
+ *          to updated node j (lattice distance for grid / hexagonal maps, graph hop count for the MST and
+ *          RNG topologies of Sections 3.2.1-3.2.2; +inf = no influence)
+ *   sigma  neighbourhood radius of this epoch;  h(g) = exp(-g^2 / (2 sigma^2))
+ *
+ * One epoch (Eq. 3 with learning rate 1 and no momentum, then "U_j / H_j up to numerical safeguards"):
+ *   Num_j = sum_k h(G[k][j]) S_k,   Den_j = sum_k h(G[k][j]) n_k,
+ *   w_j  <- Num_j / Den_j   if Den_j >= eps_h,   otherwise w_j is left unchanged.
+ * Grouping the per-sample sums of Eq. 3 by BMU gives exactly this form.
+ *
+ * Calls return SOM_OK or a negative code; they never abort and never throw.  Arguments are checked first and
+ * a rejected call has no side effects.  Work is enqueued on the context's stream and the call returns without
+ * waiting, unless a [host] output is requested (som_epoch's stats, som_epoch_host).  The caller owns every
+ * buffer it passes and keeps it alive until som_sync (or a synchronising call) returns; the library owns only
+ * its internal workspaces.  A context is bound to one device and is not thread-safe.
+ */
+#ifndef SOM_H
+#define SOM_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct som_ctx som_ctx;
+
+enum {
+    SOM_OK = 0,
+    SOM_EINVAL = -1, /* bad argument (null pointer, non-positive size, ldx < D, m != N without idx, ...) */
+    SOM_ENOMEM = -2, /* a workspace allocation failed */
+    SOM_EHIP = -3,   /* a HIP runtime call or kernel launch failed; see som_last_error */
+    SOM_EIO = -4,    /* reserved for file-backed streaming */
+    SOM_ESTATE = -5  /* context unusable (no gfx950 device, destroyed) */
+};
+
+enum { SOM_KERNEL_GAUSSIAN = 0 /* h(g) = exp(-g^2 / (2 sigma^2)) */ };
+
+/* Create a context on HIP device `device`.  `hip_stream` is a hipStream_t the library enqueues on (e.g. the
+ * caller's torch stream); NULL makes the library create and own a stream.  *out receives the context. */
+int som_create(som_ctx** out, int device, void* hip_stream);
+void som_destroy(som_ctx* ctx);
+/* Static description of a return code. */
+const char* som_strerror(int code);
+/* Detail of the last failure on this context (owned by the context, valid until the next call). */
+const char* som_last_error(const som_ctx* ctx);
+/* Block until everything enqueued on the context's stream has finished. */
+int som_sync(som_ctx* ctx);
+
+/*
+ * Measurement support (not an operation of the paper).  While profiling is enabled the library brackets every
+ * launch of its main BMU kernel with a pair of HIP events on the context's stream; som_profile_read waits for the
+ * stream, writes up to `capacity` kernel durations in milliseconds (launch order) to ms [host], stores the number
+ * of launches recorded since the last read in *count [host], and starts a new record.
+ */
+int som_profile(som_ctx* ctx, int enable);
+int som_profile_read(som_ctx* ctx, float* ms, int32_t capacity, int32_t* count);
+
+/*
+ * Best-matching-unit search (Section 3.3.1, definition of b(x)).
+ *   X [device] N x D, ldx;  idx [device] m row numbers or NULL;  W [device] K x D
+ *   bmu [device] int32[m], required: bmu[i] = b(x_{idx[i]})
+ *   d2  [device] float[m] or NULL: squared distance to the BMU, recomputed by direct differences
+ *   qe  [device] double[2] or NULL, OVERWRITTEN with { sum_i sqrt(d2_i), sum_i d2_i }  (the quantisation
+ *       error of Section 4.2 is qe[0] / m)
+ * The N x K distance matrix is never formed in memory.  m == 0 is allowed (qe becomes {0, 0}).
+ */
+int som_bmu(som_ctx* ctx, const float* X, int64_t N, int32_t D, int64_t ldx,
+            const uint32_t* idx, int64_t m, const float* W, int32_t K,
+            int32_t* bmu, float* d2, double* qe);
+
+/*
+ * Per-BMU sums and counts (the inner sums of Eq. 3 grouped by BMU; adding the results of several calls, or of
+ * several devices, is Eq. 4).
+ *   bmu [device] int32[m], every entry in [0, K)  (entries outside are skipped)
+ *   S [device] double[K*D], n [device] uint64[K]: S_k += x, n_k += 1.  zero_first != 0 clears S and n first;
+ *   otherwise the call accumulates onto their current contents (chunk-wise accumulation).
+ */
+int som_accumulate(som_ctx* ctx, const float* X, int64_t N, int32_t D, int64_t ldx,
+                   const uint32_t* idx, int64_t m, const int32_t* bmu, int32_t K,
+                   double* S, uint64_t* n, int zero_first);
+
+/*
+ * Neighbourhood-weighted update (the normalised update U_j / H_j after Eq. 4).
+ *   S [device] double[K*D], n [device] uint64[K], G [device] float[K*K]
+ *   W [device] K x D float, updated IN PLACE: w_j <- Num_j / Den_j where Den_j >= eps_h, else unchanged
+ *   eps_h <= 0 selects the default 1e-30;  kernel must be SOM_KERNEL_GAUSSIAN;  sigma > 0 and finite
+ *   n_guarded [device] int32 or NULL: OVERWRITTEN with the number of nodes left unchanged
+ * Computed in float64.
+ */
+int som_neighborhood_update(som_ctx* ctx, const double* S, const uint64_t* n, const float* G,
+                            int32_t K, int32_t D, double sigma, int kernel, double eps_h,
+                            float* W, int32_t* n_guarded);
+
+/* [host] statistics of one epoch, filled after the epoch's work has finished. */
+typedef struct {
+    double sum_dist;   /* sum over presented samples of the distance to the BMU (pre-update weights) */
+    double sum_dist2;  /* same with squared distances */
+    int64_t m;         /* samples presented */
+    int64_t n_recheck; /* samples whose best two float32 scores were too close and were re-decided exactly */
+    int32_t n_empty;   /* nodes that were nobody's BMU */
+    int32_t n_guarded; /* nodes left unchanged by the denominator threshold */
+    float ms_bmu_acc;  /* device time of BMU + accumulation (all chunks), milliseconds */
+    float ms_update;   /* device time of the neighbourhood update */
+    float ms_h2d;      /* som_epoch_host: time the copy stream spent on host-to-device transfers */
+} som_stats;
+
+/*
+ * One whole epoch on device-resident samples: BMU search fused with the per-BMU accumulation (the BMU indices
+ * never travel through memory), then the neighbourhood update of W in place.  Arguments as above.  stats is
+ * [host] or NULL; a non-NULL stats makes the call wait for the epoch to finish.  m == 0 leaves W unchanged.
+ */
+int som_epoch(som_ctx* ctx, const float* X, int64_t N, int32_t D, int64_t ldx,
+              const uint32_t* idx, int64_t m, float* W, int32_t K,
+              const float* G, double sigma, int kernel, double eps_h, som_stats* stats);
+
+/*
+ * One whole epoch on samples in HOST memory (Section 3.3.2's chunked loading path: pinned host chunk, copy
+ * to the GPU on a side stream overlapped with compute on the previous chunk, accumulators carried across the
+ * chunks, one update at the end).  Xhost [host] is any readable N x D float32 array, dense (ldx = D), for
+ * instance a memory-mapped file.  chunk_rows > 0 is the chunk length in rows; the library owns two pinned
+ * staging buffers and two device buffers of chunk_rows x D floats, allocated on first use and kept until
+ * som_destroy.  pinned != 0 promises that Xhost itself is pinned (hipHostMalloc) memory, in which case it is
+ * copied from directly.  Always waits for the epoch to finish.
+ */
+int som_epoch_host(som_ctx* ctx, const float* Xhost, int64_t N, int32_t D, int64_t chunk_rows, int pinned,
+                   float* W, int32_t K, const float* G, double sigma, int kernel, double eps_h,
+                   som_stats* stats);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SOM_H */

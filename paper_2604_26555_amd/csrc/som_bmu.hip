@@ -1,0 +1,503 @@
+// Best-matching-unit search for gfx950: fused score contraction + running arg-max, never storing N x K.
+//
+// For sample x and node k the kernel maximises  score(x, k) = x . w_k - |w_k|^2 / 2, which orders the nodes
+// exactly as the squared distance |x - w_k|^2 = |x|^2 - 2 score does (paper Section 3.3.1: b(x) is the
+// best-matching unit under the current weights).  The contraction runs on the float32 matrix cores
+// (v_mfma_f32_32x32x2_f32): one MFMA multiplies a 32-node x 2-feature slab of W by a 2-feature x 32-sample
+// slab of X into a 32 x 32 block of scores, its accumulator pre-loaded with -|w_k|^2 / 2.
+//
+// Work split.  A wavefront owns MS blocks of 32 samples and keeps their features in registers for the whole
+// kernel (lane l holds sample l % 32, features 2 s + l / 32).  The K nodes stream through LDS in stages of 128
+// (double-buffered copies of padded weight rows), shared by the four wavefronts of a workgroup.  After each
+// 32 x 32 block every lane folds its 16 scores into a running (best, runner-up, position) triple, so one lane
+// only ever tracks the nodes of its own half of the rows; the two halves meet once at the end.
+//
+// Exactness.  float32 accumulation leaves an error of a few units in the last place of the score magnitude, so
+// a sample whose best two scores are closer than kRecheckRel * (|x|^2 / 2 + max_k |w_k|^2) is put on a list and
+// re-decided by a second kernel that evaluates sum_d (x_d - w_kd)^2 directly for every node (lowest index wins
+// ties).  For all other samples the winner's squared distance is recomputed by direct differences as well, so
+// the reported distances never carry the cancellation error of the score form.
+#include "som_internal.hpp"
+
+#include <hip/amd_detail/amd_hip_unsafe_atomics.h>
+
+#include <math.h>
+
+namespace som {
+
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+
+constexpr int kWavesPerGroup = 4;
+constexpr int kThreads = kWavesPerGroup * 64;
+
+// floats of one 128-node stage (padded rows + half squared norms), rounded up to one float4 per thread
+constexpr int stage_floats_for(int stride)
+{
+    return ((kNodesPerStage * (stride + 1) + 4 * kThreads - 1) / (4 * kThreads)) * (4 * kThreads);
+}
+
+// ---------------------------------------------------------------------------------------------------------
+// Weight preparation: padded rows + half squared norms per 128-node stage, transposed copy, largest norm.
+// ---------------------------------------------------------------------------------------------------------
+__global__ void __launch_bounds__(128) bmu_prep_kernel(const float* __restrict__ W, int K, int D, int kpad,
+                                                       int stride, int stage_floats, float* __restrict__ stage,
+                                                       float* __restrict__ wt, unsigned int* __restrict__ scal)
+{
+    const int k = blockIdx.x * blockDim.x + threadIdx.x;
+    if (k >= kpad) return;
+    const int st = k / kNodesPerStage, r = k % kNodesPerStage;
+    float* blob = stage + (size_t)st * stage_floats;
+    float* dst = blob + (size_t)r * stride;
+    double nrm = 0.0;
+    for (int f = 0; f < stride; ++f) {
+        const float v = (k < K && f < D) ? W[(size_t)k * D + f] : 0.0f;
+        dst[f] = v;
+        nrm += (double)v * (double)v;
+        if (f < D) wt[(size_t)f * kpad + k] = v;
+    }
+    blob[(size_t)kNodesPerStage * stride + r] = (k < K) ? (float)(-0.5 * nrm) : -INFINITY;
+    if (k < K) {
+        float up = (float)nrm;
+        if ((double)up < nrm) up = nextafterf(up, INFINITY);
+        atomicMax(&scal[0], __float_as_uint(up));
+    }
+}
+
+__global__ void fill_zero_kernel(uint32_t* p, size_t words)
+{
+    for (size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x; i < words; i += (size_t)gridDim.x * blockDim.x)
+        p[i] = 0u;
+}
+
+// ---------------------------------------------------------------------------------------------------------
+// helpers
+// ---------------------------------------------------------------------------------------------------------
+__device__ __forceinline__ double wave_sum(double v)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+    return v;
+}
+
+// adds one sample row into the per-node sums, one feature per lane
+__device__ __forceinline__ void add_row(const float* __restrict__ xr, int D, double* __restrict__ Srow, int lane)
+{
+    for (int f = lane; f < D; f += 64) unsafeAtomicAdd(&Srow[f], (double)xr[f]);
+}
+
+// ---------------------------------------------------------------------------------------------------------
+// main kernel
+// ---------------------------------------------------------------------------------------------------------
+template <int STEPS, int MS, bool FUSE>
+__global__ void __launch_bounds__(kThreads) bmu_kernel(const BmuArgs a)
+{
+    constexpr int STRIDE = 2 * STEPS + 1;
+    constexpr int STAGE_FLOATS = stage_floats_for(STRIDE);   // whole float4s per thread: no tail handling
+    constexpr int STAGE_F4 = STAGE_FLOATS / 4;
+    constexpr int PRE = STAGE_F4 / kThreads;
+    extern __shared__ float4 lds4[];
+    float* lds = reinterpret_cast<float*>(lds4);
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    const int j = lane & 31;
+    const int g = lane >> 5;
+    const int64_t wave0 = ((int64_t)blockIdx.x * kWavesPerGroup + wave) * (MS * 32);
+
+    // ---- this wavefront's samples, kept in registers
+    float x[MS][STEPS];
+    int64_t row[MS];
+    bool valid[MS];
+#pragma unroll
+    for (int mb = 0; mb < MS; ++mb) {
+        const int64_t i = wave0 + mb * 32 + j;
+        valid[mb] = i < a.m;
+        const int64_t ii = valid[mb] ? i : a.m - 1;
+        row[mb] = a.idx ? (int64_t)a.idx[ii] : ii;
+        const float* xr = a.X + row[mb] * a.ldx;
+#pragma unroll
+        for (int s = 0; s < STEPS; ++s) {
+            const int f = 2 * s + g;
+            x[mb][s] = (f < a.D) ? xr[f] : 0.0f;
+        }
+    }
+
+    float best[MS], second[MS];
+    int code[MS];
+#pragma unroll
+    for (int mb = 0; mb < MS; ++mb) {
+        best[mb] = -INFINITY;
+        second[mb] = -INFINITY;
+        code[mb] = 0;
+    }
+
+    // ---- stream the nodes through LDS
+    const int nstages = a.kpad / kNodesPerStage;
+    const float4* src4 = reinterpret_cast<const float4*>(a.stage);
+    {
+#pragma unroll
+        for (int p = 0; p < PRE; ++p) {
+            const int e = tid + p * kThreads;
+            lds4[e] = src4[e];
+        }
+    }
+    __syncthreads();
+
+    for (int st = 0; st < nstages; ++st) {
+        const int buf = st & 1;
+        // the next stage travels global -> registers now and registers -> LDS after this stage's arithmetic
+        // (the last iteration reloads its own stage into the idle buffer, which keeps the loop branch-free)
+        float4 pre[PRE];
+        {
+            const int nxt = (st + 1 < nstages) ? st + 1 : st;
+            const float4* s4 = src4 + (size_t)nxt * STAGE_F4;
+#pragma unroll
+            for (int p = 0; p < PRE; ++p) pre[p] = s4[tid + p * kThreads];
+        }
+        const float* wbuf = lds + buf * STAGE_FLOATS;
+        const float* nbuf = wbuf + kNodesPerStage * STRIDE;
+
+#pragma unroll 1
+        for (int nb = 0; nb < kNodesPerStage / 32; ++nb) {
+            const float* wrow = wbuf + (nb * 32 + j) * STRIDE + g;
+            float wa[STEPS];
+#pragma unroll
+            for (int s = 0; s < STEPS; ++s) wa[s] = wrow[2 * s];
+            const float4* nh = reinterpret_cast<const float4*>(nbuf + nb * 32 + 4 * g);
+            floatx16 c;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const float4 t = nh[2 * q];
+                c[4 * q + 0] = t.x;
+                c[4 * q + 1] = t.y;
+                c[4 * q + 2] = t.z;
+                c[4 * q + 3] = t.w;
+            }
+            floatx16 acc[MS];
+#pragma unroll
+            for (int mb = 0; mb < MS; ++mb) acc[mb] = c;
+#pragma unroll
+            for (int s = 0; s < STEPS; ++s) {
+#pragma unroll
+                for (int mb = 0; mb < MS; ++mb)
+                    acc[mb] = __builtin_amdgcn_mfma_f32_32x32x2f32(wa[s], x[mb][s], acc[mb], 0, 0, 0);
+            }
+            const int codebase = (st * (kNodesPerStage / 32) + nb) * 16;
+#pragma unroll
+            for (int mb = 0; mb < MS; ++mb) {
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const float v = acc[mb][r];
+                    code[mb] = (v > best[mb]) ? codebase + r : code[mb];
+                    second[mb] = __builtin_amdgcn_fmed3f(best[mb], second[mb], v);
+                    best[mb] = fmaxf(best[mb], v);
+                }
+            }
+        }
+
+        {
+            float4* d4 = lds4 + (buf ^ 1) * STAGE_F4;
+#pragma unroll
+            for (int p = 0; p < PRE; ++p) d4[tid + p * kThreads] = pre[p];
+        }
+        __syncthreads();
+    }
+
+    // ---- join the two half-wavefronts, then lane (j, g) finishes block mp + g
+    const float wmax2 = __uint_as_float(a.scal[0]);
+    double qs = 0.0, qs2 = 0.0;
+    int64_t my_row = 0;
+    int my_node = -1;
+#pragma unroll
+    for (int mp = 0; mp < MS; mp += 2) {
+        float r_best = 0.f, r_second = 0.f, r_xn = 0.f, r_part = 0.f;
+        int r_node = 0;
+        bool r_valid = false;
+        int64_t r_row = 0;
+#pragma unroll
+        for (int q = 0; q < 2; ++q) {
+            const int mb = mp + q;
+            if (mb >= MS) break;
+            int node = (code[mb] >> 4) * 32 + 8 * ((code[mb] & 15) >> 2) + 4 * g + (code[mb] & 3);
+            const float ob = __shfl_xor(best[mb], 32);
+            const float os = __shfl_xor(second[mb], 32);
+            const int on = __shfl_xor(node, 32);
+            const float sec = fmaxf(fmaxf(second[mb], os), fminf(best[mb], ob));
+            const bool other = (ob > best[mb]) || (ob == best[mb] && on < node);
+            const float bst = other ? ob : best[mb];
+            node = other ? on : node;
+            node = node < a.K ? node : a.K - 1;
+            // squared norm of the sample and exact squared distance to the winner, half the features per lane
+            float xn = 0.f, part = 0.f;
+            const float* wr = a.W + (size_t)node * a.D;
+#pragma unroll
+            for (int s = 0; s < STEPS; ++s) {
+                const int f = 2 * s + g;
+                const float wv = (f < a.D) ? wr[f] : 0.0f;
+                const float df = x[mb][s] - wv;
+                xn = fmaf(x[mb][s], x[mb][s], xn);
+                part = fmaf(df, df, part);
+            }
+            xn += __shfl_xor(xn, 32);
+            part += __shfl_xor(part, 32);
+            if (q == g) {
+                r_best = bst;
+                r_second = sec;
+                r_node = node;
+                r_xn = xn;
+                r_part = part;
+                r_valid = valid[mb];
+                r_row = row[mb];
+            }
+        }
+        bool done = false;
+        if (r_valid) {
+            const int64_t i = wave0 + (mp + g) * 32 + j;
+            const float bound = (0.5f * r_xn + wmax2) * kRecheckRel;
+            const bool close = !((r_best - r_second) > bound);
+            if (close && a.K > 1) {
+                const unsigned int pos = atomicAdd(&a.scal[1], 1u);
+                a.recheck[pos] = (uint32_t)i;
+            } else {
+                done = true;
+                if (a.bmu) a.bmu[i] = r_node;
+                if (a.d2) a.d2[i] = r_part;
+                qs += sqrt((double)r_part);
+                qs2 += (double)r_part;
+            }
+        }
+        if (FUSE) {
+            my_row = r_row;
+            my_node = done ? r_node : -1;
+            if (done) atomicAdd(&a.n[r_node], 1ull);
+            // every lane's finished sample is added to its node's sum, one sample at a time, features across lanes
+            for (int t = 0; t < 64; ++t) {
+                const int node = __builtin_amdgcn_readlane(my_node, t);
+                if (node < 0) continue;
+                const uint32_t lo = __builtin_amdgcn_readlane((uint32_t)my_row, t);
+                const uint32_t hi = __builtin_amdgcn_readlane((uint32_t)((uint64_t)my_row >> 32), t);
+                const int64_t r = (int64_t)(((uint64_t)hi << 32) | lo);
+                add_row(a.X + r * a.ldx, a.D, a.S + (size_t)node * a.D, lane);
+            }
+        }
+    }
+    if (a.qe) {
+        qs = wave_sum(qs);
+        qs2 = wave_sum(qs2);
+        if (lane == 0 && (qs != 0.0 || qs2 != 0.0)) {
+            unsafeAtomicAdd(&a.qe[0], qs);
+            unsafeAtomicAdd(&a.qe[1], qs2);
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------------------
+// exact re-decision of the listed samples: one wavefront per sample, nodes across lanes
+// ---------------------------------------------------------------------------------------------------------
+template <bool FUSE>
+__global__ void __launch_bounds__(256) bmu_recheck_kernel(const BmuArgs a)
+{
+    const int lane = threadIdx.x & 63;
+    const unsigned int count = a.scal[1];
+    const unsigned int nwaves = gridDim.x * (blockDim.x >> 6);
+    if (blockIdx.x == 0 && threadIdx.x == 0) atomicAdd(&a.scal[2], count); // running total over the calls of an epoch
+    double qs = 0.0, qs2 = 0.0;
+    for (unsigned int e = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6); e < count; e += nwaves) {
+        const int64_t i = (int64_t)a.recheck[e];
+        int64_t r = a.idx ? (int64_t)a.idx[i] : i;
+        r = (int64_t)(((uint64_t)__builtin_amdgcn_readfirstlane((uint32_t)((uint64_t)r >> 32)) << 32) |
+                      __builtin_amdgcn_readfirstlane((uint32_t)r));
+        const float* xr = a.X + r * a.ldx;
+        float bd = INFINITY;
+        int bk = 0x7fffffff;
+        for (int kb = 0; kb < a.kpad; kb += 1024) {
+            float dist[16];
+#pragma unroll
+            for (int q = 0; q < 16; ++q) dist[q] = 0.f;
+            for (int d = 0; d < a.D; ++d) {
+                const float xd = xr[d];
+                const float* wcol = a.wt + (size_t)d * a.kpad + kb + lane;
+#pragma unroll
+                for (int q = 0; q < 16; ++q) {
+                    if (kb + q * 64 < a.kpad) {
+                        const float df = xd - wcol[q * 64];
+                        dist[q] = fmaf(df, df, dist[q]);
+                    }
+                }
+            }
+#pragma unroll
+            for (int q = 0; q < 16; ++q) {
+                const int k = kb + q * 64 + lane;
+                if (k < a.K && dist[q] < bd) {
+                    bd = dist[q];
+                    bk = k;
+                }
+            }
+        }
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) {
+            const float od = __shfl_xor(bd, o);
+            const int ok = __shfl_xor(bk, o);
+            if (od < bd || (od == bd && ok < bk)) {
+                bd = od;
+                bk = ok;
+            }
+        }
+        if (bk >= a.K) bk = 0; // only reachable with non-finite input
+        if (lane == 0) {
+            if (a.bmu) a.bmu[i] = bk;
+            if (a.d2) a.d2[i] = bd;
+            qs += sqrt((double)bd);
+            qs2 += (double)bd;
+            if (FUSE) atomicAdd(&a.n[bk], 1ull);
+        }
+        if (FUSE) add_row(xr, a.D, a.S + (size_t)bk * a.D, lane);
+    }
+    if (a.qe && lane == 0 && (qs != 0.0 || qs2 != 0.0)) {
+        unsafeAtomicAdd(&a.qe[0], qs);
+        unsafeAtomicAdd(&a.qe[1], qs2);
+    }
+}
+
+// ---------------------------------------------------------------------------------------------------------
+// host side
+// ---------------------------------------------------------------------------------------------------------
+static int steps_for(int D)
+{
+    const int need = (D + 1) / 2;
+    const int avail[] = {4, 8, 16, 25, 32};
+    for (int s : avail)
+        if (need <= s) return s;
+    return 0;
+}
+
+int launch_fill_zero(som_ctx* ctx, void* p, size_t bytes)
+{
+    if (bytes == 0) return SOM_OK;
+    const size_t words = bytes / 4;
+    int blocks = (int)((words + 255) / 256);
+    if (blocks > 2048) blocks = 2048;
+    hipLaunchKernelGGL(fill_zero_kernel, dim3(blocks), dim3(256), 0, ctx->stream, (uint32_t*)p, words);
+    return check_hip(ctx, hipGetLastError(), "fill_zero launch");
+}
+
+int bmu_prepare(som_ctx* ctx, const float* W, int32_t K, int32_t D, BmuPrep* out)
+{
+    const int steps = steps_for(D);
+    if (steps == 0) return fail(ctx, SOM_EINVAL, "D = %d is above the supported maximum of %d", D, 2 * kMaxStepsResident);
+    const int stride = 2 * steps + 1;
+    const int kpad = ((K + kNodesPerStage - 1) / kNodesPerStage) * kNodesPerStage;
+    const size_t stage_bytes = (size_t)(kpad / kNodesPerStage) * stage_floats_for(stride) * sizeof(float);
+    const size_t wt_bytes = (size_t)D * kpad * sizeof(float);
+    const size_t need = stage_bytes + wt_bytes + 256;
+    if (need > ctx->prep_bytes) {
+        if (ctx->prep_blob) {
+            if (int rc = check_hip(ctx, hipStreamSynchronize(ctx->stream), "sync before workspace growth")) return rc;
+            (void)hipFree(ctx->prep_blob);
+            ctx->prep_blob = nullptr;
+            ctx->prep_bytes = 0;
+        }
+        if (hipMalloc(&ctx->prep_blob, need) != hipSuccess) {
+            (void)hipGetLastError();
+            return fail(ctx, SOM_ENOMEM, "cannot allocate %zu bytes for the weight workspace", need);
+        }
+        ctx->prep_bytes = need;
+    }
+    char* base = (char*)ctx->prep_blob;
+    out->scal = (unsigned int*)base;
+    out->stage = (float*)(base + 256);
+    out->wt = (float*)(base + 256 + stage_bytes);
+    out->kpad = kpad;
+    out->steps = steps;
+    out->stride = stride;
+    if (int rc = launch_fill_zero(ctx, out->scal, 256)) return rc;
+    hipLaunchKernelGGL(bmu_prep_kernel, dim3((kpad + 127) / 128), dim3(128), 0, ctx->stream, W, K, D, kpad, stride,
+                       stage_floats_for(stride), out->stage, out->wt, out->scal);
+    return check_hip(ctx, hipGetLastError(), "bmu_prep launch");
+}
+
+template <int STEPS, int MS, bool FUSE>
+static int launch_bmu(som_ctx* ctx, const BmuArgs& a)
+{
+    constexpr int STRIDE = 2 * STEPS + 1;
+    constexpr size_t lds_bytes = 2 * (size_t)stage_floats_for(STRIDE) * sizeof(float);
+    static bool attr_set = false;
+    auto kern = bmu_kernel<STEPS, MS, FUSE>;
+    if (!attr_set) {
+        if (int rc = check_hip(ctx,
+                               hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes),
+                               "raising the dynamic LDS limit"))
+            return rc;
+        attr_set = true;
+    }
+    const int64_t per_group = (int64_t)kWavesPerGroup * MS * 32;
+    const int64_t groups = (a.m + per_group - 1) / per_group;
+    hipLaunchKernelGGL(kern, dim3((unsigned)groups), dim3(kThreads), lds_bytes, ctx->stream, a);
+    return check_hip(ctx, hipGetLastError(), "bmu kernel launch");
+}
+
+template <bool FUSE>
+static int dispatch_bmu(som_ctx* ctx, int steps, const BmuArgs& a)
+{
+    switch (steps) {
+    case 4: return launch_bmu<4, 2, FUSE>(ctx, a);
+    case 8: return launch_bmu<8, 2, FUSE>(ctx, a);
+    case 16: return launch_bmu<16, 2, FUSE>(ctx, a);
+    case 25: return launch_bmu<25, 2, FUSE>(ctx, a);
+    case 32: return launch_bmu<32, 2, FUSE>(ctx, a);
+    }
+    return fail(ctx, SOM_EINVAL, "no BMU kernel for %d steps", steps);
+}
+
+int bmu_run(som_ctx* ctx, const BmuPrep& prep, BmuArgs a)
+{
+    if (a.m <= 0) return SOM_OK;
+    if ((size_t)a.m > ctx->recheck_cap) {
+        if (ctx->recheck) {
+            if (int rc = check_hip(ctx, hipStreamSynchronize(ctx->stream), "sync before workspace growth")) return rc;
+            (void)hipFree(ctx->recheck);
+            ctx->recheck = nullptr;
+            ctx->recheck_cap = 0;
+        }
+        if (hipMalloc((void**)&ctx->recheck, (size_t)a.m * sizeof(uint32_t)) != hipSuccess) {
+            (void)hipGetLastError();
+            return fail(ctx, SOM_ENOMEM, "cannot allocate the %lld-entry recheck list", (long long)a.m);
+        }
+        ctx->recheck_cap = (size_t)a.m;
+    }
+    a.kpad = prep.kpad;
+    a.stage = prep.stage;
+    a.wt = prep.wt;
+    a.scal = prep.scal;
+    a.recheck = ctx->recheck;
+    const bool fuse = a.S != nullptr;
+    // the list length restarts for every call; the prepared weights may serve several calls (chunks)
+    if (int rc = launch_fill_zero(ctx, prep.scal + 1, 4)) return rc;
+    hipEvent_t stop = nullptr;
+    if (ctx->profiling) {
+        if (ctx->prof_used == ctx->prof_events.size()) {
+            hipEvent_t e0, e1;
+            if (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess)
+                return fail(ctx, SOM_EHIP, "event creation failed");
+            ctx->prof_events.emplace_back(e0, e1);
+        }
+        (void)hipEventRecord(ctx->prof_events[ctx->prof_used].first, ctx->stream);
+        stop = ctx->prof_events[ctx->prof_used].second;
+        ++ctx->prof_used;
+    }
+    int rc = fuse ? dispatch_bmu<true>(ctx, prep.steps, a) : dispatch_bmu<false>(ctx, prep.steps, a);
+    if (stop) (void)hipEventRecord(stop, ctx->stream);
+    if (rc) return rc;
+    if (a.K > 1) {
+        if (fuse)
+            hipLaunchKernelGGL(bmu_recheck_kernel<true>, dim3(512), dim3(256), 0, ctx->stream, a);
+        else
+            hipLaunchKernelGGL(bmu_recheck_kernel<false>, dim3(512), dim3(256), 0, ctx->stream, a);
+        rc = check_hip(ctx, hipGetLastError(), "bmu recheck launch");
+    }
+    return rc;
+}
+
+} // namespace som

@@ -1,0 +1,95 @@
+// Internal declarations shared by the translation units of libsom (not part of the public ABI).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include <utility>
+#include <vector>
+
+#include "som.h"
+
+namespace som {
+
+constexpr int kNodesPerStage = 128;   // nodes of W staged through LDS at a time by the BMU kernel
+constexpr int kMaxStepsResident = 32; // BMU kernel keeps a sample's features in registers up to D = 64
+
+// Score-gap threshold, relative to the magnitude bound 0.5|x|^2 + max_k |w_k|^2 of the float32 dot-product
+// accumulation: a sample whose best two scores are closer than this is re-decided by direct differences.
+constexpr float kRecheckRel = 1.0f / 262144.0f; // 2^-18, about 64 float32 roundings of that magnitude
+
+struct BmuPrep {
+    float* stage = nullptr;        // [Kpad / 128][128 * (stride + 1)]: padded weight rows, then -|w|^2 / 2
+    float* wt = nullptr;           // [D][Kpad] transposed weights
+    unsigned int* scal = nullptr;  // [0] = bits of max_k |w_k|^2, [1] = recheck-list length, [2] = its total since prepare
+    int kpad = 0, steps = 0, stride = 0;
+};
+
+struct BmuArgs {
+    const float* X;
+    int64_t ldx;
+    const uint32_t* idx;
+    int64_t m;
+    int32_t D, K, kpad;
+    const float* W;          // caller's dense K x D weights (exact distances)
+    const float* stage;      // BmuPrep::stage
+    const float* wt;         // BmuPrep::wt
+    unsigned int* scal;      // BmuPrep::scal
+    uint32_t* recheck;       // [m] sample positions to re-decide
+    int32_t* bmu;            // may be null in the fused epoch
+    float* d2;               // may be null
+    double* qe;              // [2], accumulated (caller zeroes)
+    double* S;               // fused accumulation targets, null when not fused
+    unsigned long long* n;
+};
+
+} // namespace som
+
+struct som_ctx {
+    int device = 0;
+    hipStream_t stream = nullptr;
+    bool own_stream = false;
+    hipStream_t copy_stream = nullptr;
+    char err[512] = {0};
+
+    // BMU workspaces (grown on demand)
+    void* prep_blob = nullptr;
+    size_t prep_bytes = 0;
+    uint32_t* recheck = nullptr;
+    size_t recheck_cap = 0;
+    // epoch-internal accumulators
+    double* S = nullptr;
+    size_t S_elems = 0;
+    unsigned long long* n = nullptr;
+    size_t n_elems = 0;
+    double* qe = nullptr;          // double[2]
+    int32_t* small = nullptr;      // int32[4]: n_guarded, n_empty, spare
+    void* host_small = nullptr;    // pinned mirror for reading results back
+    // streaming
+    float* pinned[2] = {nullptr, nullptr};
+    float* dchunk[2] = {nullptr, nullptr};
+    size_t chunk_elems = 0;
+    hipEvent_t ev_copied[2] = {nullptr, nullptr};
+    hipEvent_t ev_consumed[2] = {nullptr, nullptr};
+    hipEvent_t ev_t[4] = {nullptr, nullptr, nullptr, nullptr};
+    // measurement support: event pairs around every launch of the main BMU kernel while profiling is on
+    bool profiling = false;
+    std::vector<std::pair<hipEvent_t, hipEvent_t>> prof_events;
+    size_t prof_used = 0;
+};
+
+namespace som {
+
+int fail(som_ctx* ctx, int code, const char* fmt, ...);
+int check_hip(som_ctx* ctx, hipError_t e, const char* what);
+
+// kernels' host launchers (each returns SOM_OK or an error code after recording detail in ctx)
+int launch_fill_zero(som_ctx* ctx, void* p, size_t bytes);
+int bmu_prepare(som_ctx* ctx, const float* W, int32_t K, int32_t D, BmuPrep* out);
+int bmu_run(som_ctx* ctx, const BmuPrep& prep, BmuArgs args);
+int accumulate_run(som_ctx* ctx, const float* X, int32_t D, int64_t ldx, const uint32_t* idx, int64_t m,
+                   const int32_t* bmu, int32_t K, double* S, unsigned long long* n);
+int update_run(som_ctx* ctx, const double* S, const unsigned long long* n, const float* G, int32_t K,
+               int32_t D, double sigma, double eps_h, float* W, int32_t* small);
+
+} // namespace som

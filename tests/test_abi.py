@@ -1,0 +1,60 @@
+"""CPU-side checks of the boundary: the library loads, exports what include/som.h declares, fails loudly."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2604_26555_amd as pkg
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared():
+    text = open(os.path.join(ROOT, "include", "som.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(som_[a-z_]+)\s*\(", text)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(pkg.LIB_PATH):
+        from paper_2604_26555_amd.build import build
+        build(verbose=False)
+    return pkg.load_library()
+
+
+def test_header_and_binding_agree():
+    assert _declared() == sorted(pkg.EXPORTS)
+
+
+def test_library_exports_every_declared_symbol(lib):
+    for name in _declared():
+        assert hasattr(lib, name), name
+
+
+def test_strerror_without_gpu(lib):
+    assert lib.som_strerror(0) == b"ok"
+    assert lib.som_strerror(pkg.SOM_EINVAL) == b"invalid argument"
+    assert lib.som_strerror(-99) == b"unknown error code"
+    assert lib.som_last_error(None) == b"null context"
+
+
+def test_no_cpu_fallback(lib):
+    import torch
+    if torch.cuda.is_available():
+        pytest.skip("a GPU is present")
+    handle = ctypes.c_void_p()
+    assert lib.som_create(ctypes.byref(handle), 0, None) == pkg.SOM_ESTATE
+    assert not handle.value
+    with pytest.raises(RuntimeError):
+        pkg.Som(0)
+    assert lib.som_sync(None) == pkg.SOM_EINVAL
+
+
+def test_product_never_imports_the_oracle():
+    for dirpath, _, files in os.walk(os.path.join(ROOT, "paper_2604_26555_amd")):
+        for f in files:
+            if f.endswith((".py", ".hip", ".hpp", ".h")):
+                src = open(os.path.join(dirpath, f)).read()
+                assert "oracle" not in src, os.path.join(dirpath, f)

@@ -1,0 +1,345 @@
+"""GPU parity: every entry point of libsom against the CPU oracle on the same seeded inputs.
+
+Bars (stated here, derived in the design doc):
+  * BMU indices identical to the oracle's, except samples whose two best oracle distances differ by less than
+    1e-5 relative (more than one answer is acceptable there);
+  * squared distances, quantisation error and weights within 1e-4 relative;
+  * counts bit-exact, per-node sums within 1e-6 relative (float32 partial sums of float32 data, then float64).
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from synth import GaussianMixture, draw_initial_rows, draw_subset, linear_sigma, make_workload
+
+pytestmark = pytest.mark.gpu
+
+REL = 1e-4
+
+
+@pytest.fixture(scope="module")
+def som():
+    from paper_2604_26555_amd import Som
+    s = Som(0)
+    yield s
+    s.close()
+
+
+def dev(a, dtype=None):
+    t = torch.from_numpy(np.ascontiguousarray(a))
+    if dtype is not None:
+        t = t.to(dtype)
+    return t.cuda()
+
+
+def problem(seed, m, K, D, n_comp=6):
+    gm = GaussianMixture(seed, D, n_comp)
+    X = gm.rows(0, m)
+    rows = draw_initial_rows(seed, m, K) if K <= m else None
+    if rows is not None:
+        W = X[rows].copy()
+    else:
+        W = GaussianMixture(seed + 1, D, n_comp).rows(0, K)
+    return X, W
+
+
+def check_bmu(b_gpu, d2_gpu, X, W, idx=None):
+    Xp = X if idx is None else X[idx.astype(np.int64)]
+    b, best, second = oracle.bmu(Xp, W)
+    mask = oracle.near_tie_mask(best, second)
+    bad = (b_gpu != b) & ~mask
+    assert not bad.any(), f"{bad.sum()} BMU mismatches outside the near-tie mask, first at {np.flatnonzero(bad)[:5]}"
+    # where the index differs inside the mask the GPU's choice must still be a (near-)minimiser
+    diff = np.flatnonzero(b_gpu != b)
+    if len(diff):
+        alt = ((Xp[diff].astype(np.float64) - W[b_gpu[diff]].astype(np.float64)) ** 2).sum(1)
+        assert (alt <= best[diff] * (1 + 1e-5) + 1e-30).all()
+    if d2_gpu is not None:
+        same = b_gpu == b
+        np.testing.assert_allclose(d2_gpu[same], best[same], rtol=REL, atol=1e-12)
+    return b, best, mask
+
+
+# ------------------------------------------------------------------------------------------- stage 1
+@pytest.mark.parametrize("m,K,D", [
+    (1, 1, 1), (5, 3, 2), (257, 5, 3), (1000, 100, 8), (10_000, 100, 8), (777, 130, 17), (3000, 128, 16),
+    (4099, 1024, 50), (600, 300, 64), (2048, 257, 33),
+])
+def test_bmu_matches_oracle(som, m, K, D):
+    X, W = problem(100 + m + K + D, m, K, D)
+    d2 = torch.empty(m, dtype=torch.float32, device="cuda")
+    qe = torch.full((2,), -1.0, dtype=torch.float64, device="cuda")
+    b_gpu, _, _ = som.som_bmu(dev(X), dev(W), d2=d2, qe=qe)
+    som.som_sync()
+    b, best, _ = check_bmu(b_gpu.cpu().numpy(), d2.cpu().numpy(), X, W)
+    q = qe.cpu().numpy()
+    assert abs(q[0] - np.sqrt(best).sum()) <= REL * max(np.sqrt(best).sum(), 1e-30)
+    assert abs(q[1] - best.sum()) <= REL * max(best.sum(), 1e-30)
+
+
+def test_bmu_exact_ties_and_duplicates(som):
+    W = np.array([[1.0, 0.0], [-1.0, 0.0], [0.0, 1.0], [0.0, -1.0], [0.0, 1.0]], dtype=np.float32)
+    X = np.array([[0.0, 0.0], [0.0, 0.5], [0.25, 0.25], [-3.0, 0.0]], dtype=np.float32)
+    b_gpu, _, _ = som.som_bmu(dev(X), dev(W))
+    assert b_gpu.cpu().tolist() == oracle.bmu(X, W)[0].tolist() == [0, 2, 0, 1]
+
+
+def test_bmu_index_list_and_leading_dimension(som):
+    X, W = problem(7, 5000, 64, 10)
+    pad = np.full((5000, 13), 1e9, dtype=np.float32)       # garbage beyond D must never be read as features
+    pad[:, :10] = X
+    idx = draw_subset(7, 0, 5000, 1234)
+    d2 = torch.empty(1234, dtype=torch.float32, device="cuda")
+    Xd = dev(pad)[:, :10]
+    b_gpu, _, _ = som.som_bmu(Xd, dev(W), idx=dev(idx.astype(np.int32)), d2=d2)
+    check_bmu(b_gpu.cpu().numpy(), d2.cpu().numpy(), X, W, idx)
+
+
+def test_bmu_large_norm_small_gap(som):
+    # clusters far from the origin: |x|^2 ~ 1e5 while neighbouring nodes differ by ~1e-2 in squared distance,
+    # so the float32 score form alone could not decide; the direct re-decision has to
+    rng = np.random.default_rng(3)
+    centre = np.full(50, 45.0)
+    X = (centre + rng.normal(size=(4000, 50)) * 0.05).astype(np.float32)
+    W = (centre + rng.normal(size=(256, 50)) * 0.05).astype(np.float32)
+    b_gpu, _, _ = som.som_bmu(dev(X), dev(W))
+    check_bmu(b_gpu.cpu().numpy(), None, X, W)
+
+
+# ------------------------------------------------------------------------------------------- stage 2
+@pytest.mark.parametrize("m,K,D", [(1, 1, 1), (1000, 100, 8), (50_000, 1024, 50), (30_001, 37, 64), (4096, 2000, 5)])
+def test_accumulate_matches_oracle(som, m, K, D):
+    X, W = problem(200 + m + K, m, min(K, m), D)
+    b = np.random.default_rng(m).integers(0, K, size=m).astype(np.int32)
+    S = torch.full((K, D), 7.0, dtype=torch.float64, device="cuda")
+    n = torch.full((K,), 7, dtype=torch.int64, device="cuda")
+    som.som_accumulate(dev(X), dev(b), K, S, n, zero_first=True)
+    S_or, n_or = oracle.accumulate(X, None, b, K)
+    assert (n.cpu().numpy() == n_or).all()
+    scale = np.abs(X).max() * np.maximum(n_or, 1)[:, None]
+    assert (np.abs(S.cpu().numpy() - S_or) <= 1e-6 * scale).all()
+    # a second call without clearing adds on top (chunk-wise accumulation of Eq. 3)
+    som.som_accumulate(dev(X), dev(b), K, S, n, zero_first=False)
+    assert (n.cpu().numpy() == 2 * n_or).all()
+    assert (np.abs(S.cpu().numpy() - 2 * S_or) <= 2e-6 * scale).all()
+
+
+def test_accumulate_shards_add_up(som):
+    X, _ = problem(11, 20_000, 50, 12)
+    b = np.random.default_rng(11).integers(0, 50, size=20_000).astype(np.int32)
+    idx = draw_subset(11, 0, 20_000, 9000)
+    S = torch.zeros((50, 12), dtype=torch.float64, device="cuda")
+    n = torch.zeros((50,), dtype=torch.int64, device="cuda")
+    Xd = dev(X)
+    for lo, hi in ((0, 1), (1, 4000), (4000, 9000)):
+        som.som_accumulate(Xd, dev(b[lo:hi]), 50, S, n, idx=dev(idx[lo:hi].astype(np.int32)), zero_first=(lo == 0))
+    S_or, n_or = oracle.accumulate(X, idx, b[:9000], 50)
+    assert (n.cpu().numpy() == n_or).all() and int(n.sum()) == 9000
+    np.testing.assert_allclose(S.cpu().numpy(), S_or, rtol=1e-6, atol=1e-6 * np.abs(X).max() * n_or.max())
+
+
+# ------------------------------------------------------------------------------------------- stage 3
+def weights_close(W_gpu, W_or, den=None, eps_h=oracle.DEFAULT_EPS_H):
+    keep = np.ones(len(W_or), dtype=bool)
+    if den is not None:
+        keep = ~((den > eps_h / 4) & (den < eps_h * 4))      # the threshold itself is decided in float64 on both sides
+    scale = np.maximum(np.abs(W_or).max(axis=1, keepdims=True), 1e-30)
+    err = np.abs(W_gpu.astype(np.float64) - W_or) / scale
+    assert (err[keep] <= REL).all(), f"max relative weight error {err[keep].max():.3e}"
+    return int((~keep).sum())
+
+
+@pytest.mark.parametrize("K,D,sigma,kind", [
+    (1, 3, 1.0, "rect"), (100, 8, 5.0, "rect"), (100, 8, 0.5, "rect"), (1024, 50, 16.0, "hex"), (1024, 50, 1.0, "hex"),
+    (130, 70, 2.0, "mst"), (64, 5, 0.3, "rng"), (30, 4, 0.05, "rect"),
+])
+def test_update_matches_oracle(som, K, D, sigma, kind):
+    rng = np.random.default_rng(K + D)
+    W = rng.normal(size=(K, D)).astype(np.float32)
+    n = rng.integers(0, 50, size=K).astype(np.int64)
+    n[rng.random(K) < 0.3] = 0
+    S = rng.normal(size=(K, D)) * n[:, None]
+    shape = {1: (1, 1), 100: (10, 10), 1024: (32, 32), 30: (5, 6)}.get(K)
+    G = oracle.graph_distances(kind, W=W, lattice=shape).astype(np.float32)
+    Wd = dev(W)
+    ng = torch.full((1,), -5, dtype=torch.int32, device="cuda")
+    som.som_neighborhood_update(dev(S), dev(n), dev(G), sigma, Wd, n_guarded=ng)
+    W_or, guarded, den = oracle.neighborhood_update(S, n, G.astype(np.float64), sigma, W)
+    skipped = weights_close(Wd.cpu().numpy(), W_or, den)
+    assert abs(int(ng.item()) - int(guarded.sum())) <= skipped
+    # guarded nodes are bit-identical to their old weights
+    assert (Wd.cpu().numpy()[guarded & (den < oracle.DEFAULT_EPS_H / 4)] == W[guarded & (den < oracle.DEFAULT_EPS_H / 4)]).all()
+
+
+def test_update_with_unreachable_nodes(som):
+    K, D = 6, 3
+    G = oracle.hop_distances(K, np.array([[0, 1], [1, 2], [3, 4]])).astype(np.float32)   # node 5 isolated
+    rng = np.random.default_rng(0)
+    W = rng.normal(size=(K, D)).astype(np.float32)
+    n = np.array([3, 0, 2, 0, 1, 0], dtype=np.int64)
+    S = rng.normal(size=(K, D)) * n[:, None]
+    Wd = dev(W)
+    som.som_neighborhood_update(dev(S), dev(n), dev(G), 1.5, Wd)
+    W_or, guarded, den = oracle.neighborhood_update(S, n, G.astype(np.float64), 1.5, W)
+    assert guarded.tolist() == [False, False, False, False, False, True]
+    weights_close(Wd.cpu().numpy(), W_or, den)
+    assert (Wd.cpu().numpy()[5] == W[5]).all()
+
+
+# ------------------------------------------------------------------------------------------- whole epochs
+def run_teacher_forced(som, wl, n_rows, epochs, idx_fn=None):
+    """Each epoch starts from the oracle's weights; compares BMUs, weights, QE and counters of that epoch."""
+    X = wl.data().rows(0, n_rows)
+    W = X[draw_initial_rows(wl.seed, n_rows, wl.k)].astype(np.float64)
+    sig = linear_sigma(wl.sigma[0], wl.sigma[1], wl.epochs)
+    Xd = dev(X)
+    for e in epochs:
+        W32 = W.astype(np.float32)
+        G = oracle.graph_distances(wl.topology, W=W32, lattice=wl.lattice).astype(np.float32)
+        idx = idx_fn(e) if idx_fn else None
+        idx_d = dev(idx.astype(np.int32)) if idx is not None else None
+        b_gpu, _, _ = som.som_bmu(Xd, dev(W32), idx=idx_d)
+        b_gpu = b_gpu.cpu().numpy()
+        b, best, mask = check_bmu(b_gpu, None, X, W32, idx)
+        # inside the near-tie mask either index is a valid BMU: the oracle's update follows the GPU's choice there
+        b_use = np.where(mask, b_gpu, b)
+        ref = oracle.epoch_grouped(X, idx, W32, G.astype(np.float64), sig[e], b=b_use)
+        Wd = dev(W32)
+        st = som.som_epoch(Xd, Wd, dev(G), sig[e], idx=idx_d)
+        weights_close(Wd.cpu().numpy(), ref["W"], ref["den"])
+        m = len(b)
+        assert st.m == m
+        assert abs(st.qe - oracle.quantization_error(best)) <= REL * oracle.quantization_error(best)
+        assert abs(st.sum_dist2 - best.sum()) <= REL * best.sum()
+        assert st.n_empty == int((ref["n"] == 0).sum())
+        assert abs(st.n_guarded - int(ref["guarded"].sum())) <= int(((ref["den"] > 2.5e-31) & (ref["den"] < 4e-30)).sum())
+        W = ref["W"]
+    return W
+
+
+def test_epochs_cfg0_teacher_forced(som):
+    wl = make_workload("cfg0")
+    run_teacher_forced(som, wl, wl.n, range(wl.epochs))
+
+
+def test_epochs_cfg1_shape_teacher_forced(som):
+    wl = make_workload("cfg1", n=40_000)
+    run_teacher_forced(som, wl, wl.n, [0, 1, 10, 19])
+
+
+def test_epochs_mst_and_rng_teacher_forced(som):
+    wl = make_workload("cfg2", n=30_000, k=256)
+    run_teacher_forced(som, wl, wl.n, [0, 1, 19])
+    wl = make_workload("cfg3", n=60_000, k=200)
+    m = oracle.sampling_budget(wl.n, rho=wl.rho)
+    run_teacher_forced(som, wl, wl.n, [0, 29], idx_fn=lambda e: draw_subset(wl.seed, e, wl.n, m))
+
+
+def test_epochs_cfg0_free_running(som):
+    wl = make_workload("cfg0")
+    X = wl.data().rows(0, wl.n)
+    W0 = X[draw_initial_rows(wl.seed, wl.n, wl.k)]
+    G = oracle.graph_distances(wl.topology, lattice=wl.lattice)
+    sig = linear_sigma(*wl.sigma, wl.epochs)
+    Wd, Gd, Xd = dev(W0), dev(G.astype(np.float32)), dev(X)
+    W = W0.astype(np.float64)
+    for e in range(wl.epochs):
+        st = som.som_epoch(Xd, Wd, Gd, sig[e])
+        ref = oracle.epoch_grouped(X, None, W, G, sig[e])
+        W = ref["W"].astype(np.float32).astype(np.float64)   # the oracle carries float32 weights between epochs too
+        assert abs(st.qe - ref["qe"]) <= 1e-3 * ref["qe"]
+    weights_close(Wd.cpu().numpy(), W)
+    qe = torch.zeros(2, dtype=torch.float64, device="cuda")
+    som.som_bmu(Xd, Wd, qe=qe)
+    final = oracle.quantization_error(oracle.bmu(X, W)[1])
+    assert abs(qe[0].item() / wl.n - final) <= 1e-3 * final
+
+
+def test_empty_and_degenerate_epochs(som):
+    X, W = problem(5, 100, 4, 3)
+    G = dev(oracle.rect_lattice_distances(2, 2).astype(np.float32))
+    Wd = dev(W)
+    st = som.som_epoch(dev(X)[:0], Wd, G, 1.0)
+    assert st.m == 0 and st.n_guarded == 4 and (Wd.cpu().numpy() == W).all()
+    b, _, _ = som.som_bmu(dev(X)[:0], Wd)
+    assert b.numel() == 0
+    # K = 1: every sample maps to node 0 and the update is the data mean
+    W1 = dev(np.zeros((1, 3), dtype=np.float32))
+    st = som.som_epoch(dev(X), W1, dev(np.zeros((1, 1), dtype=np.float32)), 2.0)
+    np.testing.assert_allclose(W1.cpu().numpy()[0], X.astype(np.float64).mean(0), rtol=1e-6, atol=1e-7)
+    assert st.n_empty == 0 and st.n_guarded == 0
+    # all samples identical
+    Xs = np.tile(np.array([[1.5, -2.0, 0.25]], dtype=np.float32), (300, 1))
+    Wd = dev(W)
+    som.som_epoch(dev(Xs), Wd, G, 0.01)
+    ref = oracle.epoch_definition(Xs, None, W, oracle.rect_lattice_distances(2, 2), 0.01)
+    weights_close(Wd.cpu().numpy(), ref["W"], ref["den"])
+
+
+def test_run_to_run_determinism_of_counts(som):
+    wl = make_workload("cfg1", n=30_000)
+    X = wl.data().rows(0, wl.n)
+    W0 = X[draw_initial_rows(wl.seed, wl.n, wl.k)]
+    G = dev(oracle.graph_distances("hex", lattice=(32, 32)).astype(np.float32))
+    outs = []
+    for _ in range(2):
+        Wd = dev(W0)
+        b, _, _ = som.som_bmu(dev(X), Wd)
+        st = som.som_epoch(dev(X), Wd, G, 3.0)
+        outs.append((b.cpu().numpy(), Wd.cpu().numpy(), st))
+    assert (outs[0][0] == outs[1][0]).all()
+    np.testing.assert_allclose(outs[0][1], outs[1][1], rtol=1e-6, atol=1e-7)
+    assert outs[0][2].n_empty == outs[1][2].n_empty and outs[0][2].n_recheck == outs[1][2].n_recheck
+
+
+# ------------------------------------------------------------------------------------------- streaming
+@pytest.mark.parametrize("chunk", [1000, 4096, 7001, 50_000])
+def test_streamed_epoch_equals_resident_epoch(som, chunk):
+    wl = make_workload("cfg4", n=20_000, k=100, lattice=(10, 10))
+    X = wl.data().rows(0, wl.n)
+    W0 = X[draw_initial_rows(wl.seed, wl.n, wl.k)]
+    G = dev(oracle.graph_distances("rect", lattice=(10, 10)).astype(np.float32))
+    Wa, Wb = dev(W0), dev(W0)
+    sa = som.som_epoch(dev(X), Wa, G, 2.0)
+    sb = som.som_epoch_host(X, Wb, G, 2.0, chunk_rows=chunk)
+    np.testing.assert_allclose(Wb.cpu().numpy(), Wa.cpu().numpy(), rtol=1e-6, atol=1e-7)
+    assert sa.m == sb.m == wl.n and abs(sa.sum_dist - sb.sum_dist) <= 1e-9 * sa.sum_dist
+    assert sa.n_empty == sb.n_empty
+    ref = oracle.epoch_grouped(X, None, W0, oracle.rect_lattice_distances(10, 10), 2.0)
+    weights_close(Wb.cpu().numpy(), ref["W"], ref["den"])
+    # pinned source: copied from directly
+    Xp = torch.from_numpy(X).pin_memory()
+    Wc = dev(W0)
+    som.som_epoch_host(Xp, Wc, G, 2.0, chunk_rows=chunk)
+    np.testing.assert_allclose(Wc.cpu().numpy(), Wa.cpu().numpy(), rtol=1e-6, atol=1e-7)
+
+
+# ------------------------------------------------------------------------------------------- error paths
+def test_argument_errors_are_reported_not_fatal(som):
+    from paper_2604_26555_amd import SomError, SOM_EINVAL
+    X, W = problem(9, 64, 4, 3)
+    Xd, Wd = dev(X), dev(W)
+    G = dev(oracle.rect_lattice_distances(2, 2).astype(np.float32))
+    lib, h = som.lib, som._h
+    bmu = torch.empty(64, dtype=torch.int32, device="cuda")
+    p = lambda t: t.data_ptr()
+    assert lib.som_bmu(h, None, 64, 3, 3, None, 64, p(Wd), 4, p(bmu), None, None) == SOM_EINVAL
+    assert lib.som_bmu(h, p(Xd), 64, 3, 2, None, 64, p(Wd), 4, p(bmu), None, None) == SOM_EINVAL      # ldx < D
+    assert lib.som_bmu(h, p(Xd), 64, 3, 3, None, 10, p(Wd), 4, p(bmu), None, None) == SOM_EINVAL      # m != N, no idx
+    assert lib.som_bmu(h, p(Xd), 64, 3, 3, None, 64, p(Wd), 0, p(bmu), None, None) == SOM_EINVAL      # K < 1
+    assert lib.som_bmu(h, p(Xd), -1, 3, 3, None, -1, p(Wd), 4, p(bmu), None, None) == SOM_EINVAL
+    assert lib.som_bmu(h, p(Xd), 64, 3, 3, None, 64, p(Wd), 4, None, None, None) == SOM_EINVAL
+    host = torch.from_numpy(X)                                                                         # pageable host memory
+    assert lib.som_bmu(h, host.data_ptr(), 64, 3, 3, None, 64, p(Wd), 4, p(bmu), None, None) == SOM_EINVAL
+    assert b"device" in lib.som_last_error(h)
+    for bad_sigma in (0.0, -1.0, float("nan"), float("inf")):
+        with pytest.raises(SomError):
+            som.som_epoch(Xd, Wd, G, bad_sigma)
+    assert lib.som_epoch(h, p(Xd), 64, 3, 3, None, 64, p(Wd), 4, p(G), 1.0, 5, 0.0, None) == SOM_EINVAL   # unknown kernel
+    with pytest.raises(SomError):
+        som.som_epoch_host(X, Wd, G, 1.0, chunk_rows=0)
+    assert (Wd.cpu().numpy() == W).all()            # rejected calls leave W alone
+    # the context is still usable
+    st = som.som_epoch(Xd, Wd, G, 1.0)
+    assert st.m == 64
