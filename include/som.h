@@ -5,7 +5,7 @@
  * e.g. obtained from hipMalloc or a torch tensor's data_ptr) or [host].  All matrices are row-major.
  *
  * Notation (the paper's, Section 3.3.1):
- *   X      N x D samples, float32, leading dimension ldx >= D (in floats)
+ *   X      N x D samples, float32, leading dimension ldx >= D (in floats); may be NULL when N == 0
  *   idx    optional list of m presented row numbers into X (Section 3.1, Eq. 2: the iteration subset);
  *          NULL means rows 0..N-1 are presented and m must equal N
  *   W      K x D node weights, float32, dense (leading dimension D)
@@ -50,8 +50,9 @@ enum {
 
 enum { SOM_KERNEL_GAUSSIAN = 0 /* h(g) = exp(-g^2 / (2 sigma^2)) */ };
 
-/* Create a context on HIP device `device`.  `hip_stream` is a hipStream_t the library enqueues on (e.g. the
- * caller's torch stream); NULL makes the library create and own a stream.  *out receives the context. */
+/* Create a context on HIP device `device`.  `hip_stream` is the hipStream_t the library enqueues all compute on
+ * (e.g. the caller's torch stream); NULL is HIP's default stream.  The stream stays the caller's.  The library
+ * creates one further stream of its own for host-to-device copies.  *out receives the context. */
 int som_create(som_ctx** out, int device, void* hip_stream);
 void som_destroy(som_ctx* ctx);
 /* Static description of a return code. */

@@ -89,8 +89,11 @@ def near_tie_mask(d2_best: np.ndarray, d2_second: np.ndarray, rel: float = 1e-5)
 
     For such samples more than one BMU is an acceptable answer in float32 arithmetic.
     """
-    denom = np.maximum(d2_second, np.finfo(np.float64).tiny)
-    return (d2_second - d2_best) / denom < rel
+    d2_second = np.asarray(d2_second, dtype=np.float64)
+    finite = np.isfinite(d2_second)                      # K = 1 has no runner-up, hence no tie
+    denom = np.where(finite, np.maximum(d2_second, np.finfo(np.float64).tiny), 1.0)
+    gap = np.where(finite, d2_second - d2_best, np.inf)
+    return gap / denom < rel
 
 
 def quantization_error(d2_best: np.ndarray) -> float:

@@ -62,7 +62,7 @@ static int common_checks(som_ctx* ctx, const void* X, int64_t N, int32_t D, int6
                          const void* W, int32_t K)
 {
     if (!ctx) return SOM_EINVAL;
-    if (!X || !W) return fail(ctx, SOM_EINVAL, "null X or W");
+    if (!W || (!X && N != 0)) return fail(ctx, SOM_EINVAL, "null X or W");
     if (K < 1 || D < 1) return fail(ctx, SOM_EINVAL, "K and D must be positive (K=%d, D=%d)", K, D);
     if (N < 0 || m < 0) return fail(ctx, SOM_EINVAL, "negative N or m");
     if (ldx < D) return fail(ctx, SOM_EINVAL, "ldx (%lld) is smaller than D (%d)", (long long)ldx, D);
@@ -111,15 +111,7 @@ int som_create(som_ctx** out, int device, void* hip_stream)
     som_ctx* c = new (std::nothrow) som_ctx;
     if (!c) return SOM_ENOMEM;
     c->device = device;
-    if (hip_stream) {
-        c->stream = (hipStream_t)hip_stream;
-    } else {
-        if (hipStreamCreateWithFlags(&c->stream, hipStreamNonBlocking) != hipSuccess) {
-            delete c;
-            return SOM_EHIP;
-        }
-        c->own_stream = true;
-    }
+    c->stream = (hipStream_t)hip_stream; // NULL is HIP's default stream, which is what torch uses by default
     bool ok = hipStreamCreateWithFlags(&c->copy_stream, hipStreamNonBlocking) == hipSuccess;
     ok = ok && hipMalloc((void**)&c->qe, 2 * sizeof(double)) == hipSuccess;
     ok = ok && hipMalloc((void**)&c->small, 64) == hipSuccess;
@@ -166,7 +158,6 @@ void som_destroy(som_ctx* c)
         (void)hipEventDestroy(pr.first);
         (void)hipEventDestroy(pr.second);
     }
-    if (c->own_stream && c->stream) (void)hipStreamDestroy(c->stream);
     delete c;
 }
 
@@ -201,7 +192,7 @@ int som_bmu(som_ctx* ctx, const float* X, int64_t N, int32_t D, int64_t ldx, con
 {
     if (int rc = common_checks(ctx, X, N, D, ldx, idx, m, W, K)) return rc;
     if (!bmu && m > 0) return fail(ctx, SOM_EINVAL, "null bmu output");
-    if (!device_readable(X) || !device_readable(W) || (m > 0 && !device_readable(bmu)))
+    if ((N > 0 && !device_readable(X)) || !device_readable(W) || (m > 0 && !device_readable(bmu)))
         return fail(ctx, SOM_EINVAL, "X, W and bmu must be device-accessible memory");
     if (int rc = check_hip(ctx, hipSetDevice(ctx->device), "hipSetDevice")) return rc;
     if (qe)
@@ -228,7 +219,7 @@ int som_accumulate(som_ctx* ctx, const float* X, int64_t N, int32_t D, int64_t l
 {
     if (int rc = common_checks(ctx, X, N, D, ldx, idx, m, S, K)) return rc;
     if (!S || !n || (!bmu && m > 0)) return fail(ctx, SOM_EINVAL, "null S, n or bmu");
-    if (!device_readable(X) || !device_readable(S) || !device_readable(n) || (m > 0 && !device_readable(bmu)))
+    if ((N > 0 && !device_readable(X)) || !device_readable(S) || !device_readable(n) || (m > 0 && !device_readable(bmu)))
         return fail(ctx, SOM_EINVAL, "X, bmu, S and n must be device-accessible memory");
     if (int rc = check_hip(ctx, hipSetDevice(ctx->device), "hipSetDevice")) return rc;
     if (zero_first) {
@@ -308,7 +299,7 @@ int som_epoch(som_ctx* ctx, const float* X, int64_t N, int32_t D, int64_t ldx, c
 {
     if (int rc = common_checks(ctx, X, N, D, ldx, idx, m, W, K)) return rc;
     if (int rc = update_checks(ctx, G, K, D, sigma, kernel)) return rc;
-    if (!device_readable(X) || !device_readable(W) || !device_readable(G))
+    if ((N > 0 && !device_readable(X)) || !device_readable(W) || !device_readable(G))
         return fail(ctx, SOM_EINVAL, "X, W and G must be device-accessible memory");
     if (int rc = check_hip(ctx, hipSetDevice(ctx->device), "hipSetDevice")) return rc;
     if (eps_h <= 0.0) eps_h = 1e-30;

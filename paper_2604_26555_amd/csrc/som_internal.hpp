@@ -48,7 +48,6 @@ struct BmuArgs {
 struct som_ctx {
     int device = 0;
     hipStream_t stream = nullptr;
-    bool own_stream = false;
     hipStream_t copy_stream = nullptr;
     char err[512] = {0};
 
