@@ -17,6 +17,8 @@ FLAGS = [
     # packed float32 VALU forms are kept off for this target
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-munsafe-fp-atomics",
+    # MFMA results land in ordinary VGPRs so the arg-max fold reads them without accumulator-register copies
+    "-mllvm", "-amdgpu-mfma-vgpr-form",
     "-Wall", "-Wno-unused-result",
     "-I", os.path.join(ROOT, "include"), "-I", CSRC,
 ]

@@ -149,6 +149,8 @@ void som_destroy(som_ctx* c)
         if (c->ev_t[i]) (void)hipEventDestroy(c->ev_t[i]);
     if (c->prep_blob) (void)hipFree(c->prep_blob);
     if (c->recheck) (void)hipFree(c->recheck);
+    if (c->bmu_ws) (void)hipFree(c->bmu_ws);
+    if (c->acc_blob) (void)hipFree(c->acc_blob);
     if (c->S) (void)hipFree(c->S);
     if (c->n) (void)hipFree(c->n);
     if (c->qe) (void)hipFree(c->qe);
@@ -222,11 +224,7 @@ int som_accumulate(som_ctx* ctx, const float* X, int64_t N, int32_t D, int64_t l
     if ((N > 0 && !device_readable(X)) || !device_readable(S) || !device_readable(n) || (m > 0 && !device_readable(bmu)))
         return fail(ctx, SOM_EINVAL, "X, bmu, S and n must be device-accessible memory");
     if (int rc = check_hip(ctx, hipSetDevice(ctx->device), "hipSetDevice")) return rc;
-    if (zero_first) {
-        if (int rc = launch_fill_zero(ctx, S, (size_t)K * D * sizeof(double))) return rc;
-        if (int rc = launch_fill_zero(ctx, n, (size_t)K * sizeof(uint64_t))) return rc;
-    }
-    return accumulate_run(ctx, X, D, ldx, idx, m, bmu, K, S, (unsigned long long*)n);
+    return accumulate_run(ctx, X, D, ldx, idx, m, bmu, K, S, (unsigned long long*)n, zero_first != 0);
 }
 
 static int update_checks(som_ctx* ctx, const void* G, int32_t K, int32_t D, double sigma, int kernel)
@@ -263,12 +261,11 @@ struct HostSmall {
     unsigned int scal[4];
 };
 
-static int begin_epoch(som_ctx* ctx, int32_t K, int32_t D)
+static int begin_epoch(som_ctx* ctx, int32_t K, int32_t D, int64_t chunk_rows)
 {
+    if (int rc = grow(ctx, &ctx->bmu_ws, &ctx->bmu_elems, (size_t)chunk_rows, "the BMU indices")) return rc;
     if (int rc = grow(ctx, &ctx->S, &ctx->S_elems, (size_t)K * D, "the per-node sums")) return rc;
     if (int rc = grow(ctx, &ctx->n, &ctx->n_elems, (size_t)K, "the per-node counts")) return rc;
-    if (int rc = launch_fill_zero(ctx, ctx->S, (size_t)K * D * sizeof(double))) return rc;
-    if (int rc = launch_fill_zero(ctx, ctx->n, (size_t)K * sizeof(unsigned long long))) return rc;
     if (int rc = launch_fill_zero(ctx, ctx->qe, 2 * sizeof(double))) return rc;
     return launch_fill_zero(ctx, ctx->small, 64);
 }
@@ -311,7 +308,7 @@ int som_epoch(som_ctx* ctx, const float* X, int64_t N, int32_t D, int64_t ldx, c
         }
         return SOM_OK;
     }
-    if (int rc = begin_epoch(ctx, K, D)) return rc;
+    if (int rc = begin_epoch(ctx, K, D, m)) return rc;
     BmuPrep prep;
     if (stats) (void)hipEventRecord(ctx->ev_t[0], ctx->stream);
     if (int rc = bmu_prepare(ctx, W, K, D, &prep)) return rc;
@@ -324,9 +321,9 @@ int som_epoch(som_ctx* ctx, const float* X, int64_t N, int32_t D, int64_t ldx, c
     a.K = K;
     a.W = W;
     a.qe = ctx->qe;
-    a.S = ctx->S;
-    a.n = ctx->n;
+    a.bmu = ctx->bmu_ws;
     if (int rc = bmu_run(ctx, prep, a)) return rc;
+    if (int rc = accumulate_run(ctx, X, D, ldx, idx, m, ctx->bmu_ws, K, ctx->S, ctx->n, true)) return rc;
     HostSmall* h = (HostSmall*)ctx->host_small;
     if (stats) {
         (void)hipEventRecord(ctx->ev_t[1], ctx->stream);
@@ -400,7 +397,7 @@ int som_epoch_host(som_ctx* ctx, const float* Xhost, int64_t N, int32_t D, int64
         }
         ctx->chunk_elems = want;
     }
-    if (int rc = begin_epoch(ctx, K, D)) return rc;
+    if (int rc = begin_epoch(ctx, K, D, chunk_rows)) return rc;
     BmuPrep prep;
     (void)hipEventRecord(ctx->ev_t[0], ctx->stream);
     if (int rc = bmu_prepare(ctx, W, K, D, &prep)) return rc;
@@ -443,9 +440,9 @@ int som_epoch_host(som_ctx* ctx, const float* Xhost, int64_t N, int32_t D, int64
         a.K = K;
         a.W = W;
         a.qe = ctx->qe;
-        a.S = ctx->S;
-        a.n = ctx->n;
+        a.bmu = ctx->bmu_ws;
         if (int rc = bmu_run(ctx, prep, a)) return rc;
+        if (int rc = accumulate_run(ctx, ctx->dchunk[b], D, D, nullptr, rows, ctx->bmu_ws, K, ctx->S, ctx->n, c == 0)) return rc;
         (void)hipEventRecord(ctx->ev_consumed[b], ctx->stream);
     }
     (void)hipEventRecord(ctx->ev_t[1], ctx->stream);

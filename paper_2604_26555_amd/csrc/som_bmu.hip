@@ -2,21 +2,23 @@
 //
 // For sample x and node k the kernel maximises  score(x, k) = x . w_k - |w_k|^2 / 2, which orders the nodes
 // exactly as the squared distance |x - w_k|^2 = |x|^2 - 2 score does (paper Section 3.3.1: b(x) is the
-// best-matching unit under the current weights).  The contraction runs on the float32 matrix cores
-// (v_mfma_f32_32x32x2_f32): one MFMA multiplies a 32-node x 2-feature slab of W by a 2-feature x 32-sample
+// best-matching unit under the current weights).  The contraction runs as float32 MFMA
+// (v_mfma_f32_32x32x2_f32): one instruction multiplies a 32-node x 2-feature slab of W by a 2-feature x 32-sample
 // slab of X into a 32 x 32 block of scores, its accumulator pre-loaded with -|w_k|^2 / 2.
 //
 // Work split.  A wavefront owns MS blocks of 32 samples and keeps their features in registers for the whole
 // kernel (lane l holds sample l % 32, features 2 s + l / 32).  The K nodes stream through LDS in stages of 128
 // (double-buffered copies of padded weight rows), shared by the four wavefronts of a workgroup.  After each
 // 32 x 32 block every lane folds its 16 scores into a running (best, runner-up, position) triple, so one lane
-// only ever tracks the nodes of its own half of the rows; the two halves meet once at the end.
+// only ever tracks the nodes of its own half of the rows; the two halves meet once at the end.  On this chip
+// float32 MFMA and ordinary vector instructions occupy the same lanes (they do not overlap, not even across
+// wavefronts), so the fold is held to four vector instructions per score.
 //
 // Exactness.  float32 accumulation leaves an error of a few units in the last place of the score magnitude, so
-// a sample whose best two scores are closer than kRecheckRel * (|x|^2 / 2 + max_k |w_k|^2) is put on a list and
-// re-decided by a second kernel that evaluates sum_d (x_d - w_kd)^2 directly for every node (lowest index wins
-// ties).  For all other samples the winner's squared distance is recomputed by direct differences as well, so
-// the reported distances never carry the cancellation error of the score form.
+// a sample whose best two scores are closer than a rigorous bound of that error is put on a list and re-decided
+// by a second kernel that evaluates sum_d (x_d - w_kd)^2 directly for every node (lowest index wins ties).  For
+// all other samples the winner's squared distance is recomputed by direct differences as well, so the reported
+// distances never carry the cancellation error of the score form.
 #include "som_internal.hpp"
 
 #include <hip/amd_detail/amd_hip_unsafe_atomics.h>
@@ -79,16 +81,19 @@ __device__ __forceinline__ double wave_sum(double v)
     return v;
 }
 
-// adds one sample row into the per-node sums, one feature per lane
-__device__ __forceinline__ void add_row(const float* __restrict__ xr, int D, double* __restrict__ Srow, int lane)
+// plain v_max_f32: the scores are never signalling NaNs worth quieting, and every VALU instruction here is paid
+// for in matrix time (float32 MFMA and the vector ALU share the same lanes)
+__device__ __forceinline__ float vmax(float a, float b)
 {
-    for (int f = lane; f < D; f += 64) unsafeAtomicAdd(&Srow[f], (double)xr[f]);
+    float r;
+    asm("v_max_f32 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
+    return r;
 }
 
 // ---------------------------------------------------------------------------------------------------------
 // main kernel
 // ---------------------------------------------------------------------------------------------------------
-template <int STEPS, int MS, bool FUSE>
+template <int STEPS, int MS>
 __global__ void __launch_bounds__(kThreads) bmu_kernel(const BmuArgs a)
 {
     constexpr int STRIDE = 2 * STEPS + 1;
@@ -107,15 +112,14 @@ __global__ void __launch_bounds__(kThreads) bmu_kernel(const BmuArgs a)
 
     // ---- this wavefront's samples, kept in registers
     float x[MS][STEPS];
-    int64_t row[MS];
     bool valid[MS];
 #pragma unroll
     for (int mb = 0; mb < MS; ++mb) {
         const int64_t i = wave0 + mb * 32 + j;
         valid[mb] = i < a.m;
         const int64_t ii = valid[mb] ? i : a.m - 1;
-        row[mb] = a.idx ? (int64_t)a.idx[ii] : ii;
-        const float* xr = a.X + row[mb] * a.ldx;
+        const int64_t row = a.idx ? (int64_t)a.idx[ii] : ii;
+        const float* xr = a.X + row * a.ldx;
 #pragma unroll
         for (int s = 0; s < STEPS; ++s) {
             const int f = 2 * s + g;
@@ -123,13 +127,15 @@ __global__ void __launch_bounds__(kThreads) bmu_kernel(const BmuArgs a)
         }
     }
 
+    // running best / runner-up scores of this lane's half of the rows, and where the best one sits
     float best[MS], second[MS];
-    int code[MS];
+    int rsel[MS], tsel[MS];
 #pragma unroll
     for (int mb = 0; mb < MS; ++mb) {
         best[mb] = -INFINITY;
         second[mb] = -INFINITY;
-        code[mb] = 0;
+        rsel[mb] = 0;
+        tsel[mb] = 0;
     }
 
     // ---- stream the nodes through LDS
@@ -183,16 +189,19 @@ __global__ void __launch_bounds__(kThreads) bmu_kernel(const BmuArgs a)
                 for (int mb = 0; mb < MS; ++mb)
                     acc[mb] = __builtin_amdgcn_mfma_f32_32x32x2f32(wa[s], x[mb][s], acc[mb], 0, 0, 0);
             }
-            const int codebase = (st * (kNodesPerStage / 32) + nb) * 16;
+            // fold the 16 scores of each block into the running triple: four VALU instructions per score
+            const int tile = st * (kNodesPerStage / 32) + nb;
 #pragma unroll
             for (int mb = 0; mb < MS; ++mb) {
+                const float before = best[mb];
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
                     const float v = acc[mb][r];
-                    code[mb] = (v > best[mb]) ? codebase + r : code[mb];
+                    rsel[mb] = (v > best[mb]) ? r : rsel[mb];
                     second[mb] = __builtin_amdgcn_fmed3f(best[mb], second[mb], v);
-                    best[mb] = fmaxf(best[mb], v);
+                    best[mb] = vmax(best[mb], v);
                 }
+                tsel[mb] = (best[mb] > before) ? tile : tsel[mb];
             }
         }
 
@@ -206,20 +215,18 @@ __global__ void __launch_bounds__(kThreads) bmu_kernel(const BmuArgs a)
 
     // ---- join the two half-wavefronts, then lane (j, g) finishes block mp + g
     const float wmax2 = __uint_as_float(a.scal[0]);
+    const float rel = (float)(2 * STEPS + 8) * 5.9604645e-08f;    // (roundings per score + slack) * 2^-24
     double qs = 0.0, qs2 = 0.0;
-    int64_t my_row = 0;
-    int my_node = -1;
 #pragma unroll
     for (int mp = 0; mp < MS; mp += 2) {
         float r_best = 0.f, r_second = 0.f, r_xn = 0.f, r_part = 0.f;
         int r_node = 0;
         bool r_valid = false;
-        int64_t r_row = 0;
 #pragma unroll
         for (int q = 0; q < 2; ++q) {
             const int mb = mp + q;
             if (mb >= MS) break;
-            int node = (code[mb] >> 4) * 32 + 8 * ((code[mb] & 15) >> 2) + 4 * g + (code[mb] & 3);
+            int node = tsel[mb] * 32 + 8 * (rsel[mb] >> 2) + 4 * g + (rsel[mb] & 3);
             const float ob = __shfl_xor(best[mb], 32);
             const float os = __shfl_xor(second[mb], 32);
             const int on = __shfl_xor(node, 32);
@@ -248,37 +255,21 @@ __global__ void __launch_bounds__(kThreads) bmu_kernel(const BmuArgs a)
                 r_xn = xn;
                 r_part = part;
                 r_valid = valid[mb];
-                r_row = row[mb];
             }
         }
-        bool done = false;
         if (r_valid) {
             const int64_t i = wave0 + (mp + g) * 32 + j;
-            const float bound = (0.5f * r_xn + wmax2) * kRecheckRel;
+            // magnitude bound of every partial sum of the score: |w|^2/2 + sum |x_d w_d| <= |x|^2/2 + |w|^2
+            const float bound = (0.5f * r_xn + wmax2) * rel;
             const bool close = !((r_best - r_second) > bound);
+            a.bmu[i] = r_node;
+            if (a.d2) a.d2[i] = r_part;
             if (close && a.K > 1) {
                 const unsigned int pos = atomicAdd(&a.scal[1], 1u);
                 a.recheck[pos] = (uint32_t)i;
             } else {
-                done = true;
-                if (a.bmu) a.bmu[i] = r_node;
-                if (a.d2) a.d2[i] = r_part;
                 qs += sqrt((double)r_part);
                 qs2 += (double)r_part;
-            }
-        }
-        if (FUSE) {
-            my_row = r_row;
-            my_node = done ? r_node : -1;
-            if (done) atomicAdd(&a.n[r_node], 1ull);
-            // every lane's finished sample is added to its node's sum, one sample at a time, features across lanes
-            for (int t = 0; t < 64; ++t) {
-                const int node = __builtin_amdgcn_readlane(my_node, t);
-                if (node < 0) continue;
-                const uint32_t lo = __builtin_amdgcn_readlane((uint32_t)my_row, t);
-                const uint32_t hi = __builtin_amdgcn_readlane((uint32_t)((uint64_t)my_row >> 32), t);
-                const int64_t r = (int64_t)(((uint64_t)hi << 32) | lo);
-                add_row(a.X + r * a.ldx, a.D, a.S + (size_t)node * a.D, lane);
             }
         }
     }
@@ -293,68 +284,125 @@ __global__ void __launch_bounds__(kThreads) bmu_kernel(const BmuArgs a)
 }
 
 // ---------------------------------------------------------------------------------------------------------
-// exact re-decision of the listed samples: one wavefront per sample, nodes across lanes
+// exact re-decision of the listed samples by direct differences, sum_d (x_d - w_kd)^2 for every node.
+// A workgroup takes kExactGroup samples at a time; thread t owns nodes t, t + 256, ... so one coalesced read of
+// the transposed weights serves all samples of the group, and the samples' features are broadcast from LDS.
 // ---------------------------------------------------------------------------------------------------------
-template <bool FUSE>
-__global__ void __launch_bounds__(256) bmu_recheck_kernel(const BmuArgs a)
+constexpr int kExactGroup = 8;
+constexpr int kExactNodesPerThread = 4;
+
+__global__ void __launch_bounds__(256) bmu_exact_kernel(const BmuArgs a)
 {
-    const int lane = threadIdx.x & 63;
+    __shared__ float4 xs4[64][kExactGroup / 4];   // [feature within a 64-wide slab][sample]
+    __shared__ float red_d[4][kExactGroup];
+    __shared__ int red_k[4][kExactGroup];
+    float* xs = reinterpret_cast<float*>(xs4);
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
     const unsigned int count = a.scal[1];
-    const unsigned int nwaves = gridDim.x * (blockDim.x >> 6);
-    if (blockIdx.x == 0 && threadIdx.x == 0) atomicAdd(&a.scal[2], count); // running total over the calls of an epoch
+    if (blockIdx.x == 0 && tid == 0) atomicAdd(&a.scal[2], count); // running total over the calls of an epoch
     double qs = 0.0, qs2 = 0.0;
-    for (unsigned int e = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6); e < count; e += nwaves) {
-        const int64_t i = (int64_t)a.recheck[e];
-        int64_t r = a.idx ? (int64_t)a.idx[i] : i;
-        r = (int64_t)(((uint64_t)__builtin_amdgcn_readfirstlane((uint32_t)((uint64_t)r >> 32)) << 32) |
-                      __builtin_amdgcn_readfirstlane((uint32_t)r));
-        const float* xr = a.X + r * a.ldx;
-        float bd = INFINITY;
-        int bk = 0x7fffffff;
-        for (int kb = 0; kb < a.kpad; kb += 1024) {
-            float dist[16];
+    for (unsigned int g0 = blockIdx.x * kExactGroup; g0 < count; g0 += gridDim.x * kExactGroup) {
+        float bestd[kExactGroup];
+        int bestk[kExactGroup];
 #pragma unroll
-            for (int q = 0; q < 16; ++q) dist[q] = 0.f;
-            for (int d = 0; d < a.D; ++d) {
-                const float xd = xr[d];
-                const float* wcol = a.wt + (size_t)d * a.kpad + kb + lane;
+        for (int s = 0; s < kExactGroup; ++s) {
+            bestd[s] = INFINITY;
+            bestk[s] = 0x7fffffff;
+        }
+        for (int kb = 0; kb < a.kpad; kb += 256 * kExactNodesPerThread) {
+            float dist[kExactGroup][kExactNodesPerThread];
 #pragma unroll
-                for (int q = 0; q < 16; ++q) {
-                    if (kb + q * 64 < a.kpad) {
-                        const float df = xd - wcol[q * 64];
-                        dist[q] = fmaf(df, df, dist[q]);
+            for (int s = 0; s < kExactGroup; ++s)
+#pragma unroll
+                for (int u = 0; u < kExactNodesPerThread; ++u) dist[s][u] = 0.f;
+            for (int d0 = 0; d0 < a.D; d0 += 64) {
+                const int dn = (a.D - d0 < 64) ? a.D - d0 : 64;
+                __syncthreads();
+                for (int e = tid; e < kExactGroup * dn; e += 256) {
+                    const int s = e / dn, d = e % dn;
+                    const unsigned int ge = (g0 + s < count) ? g0 + s : count - 1;
+                    const int64_t i = (int64_t)a.recheck[ge];
+                    const int64_t r = a.idx ? (int64_t)a.idx[i] : i;
+                    xs[d * kExactGroup + s] = a.X[r * a.ldx + d0 + d];
+                }
+                __syncthreads();
+                for (int d = 0; d < dn; ++d) {
+                    float w[kExactNodesPerThread];
+#pragma unroll
+                    for (int u = 0; u < kExactNodesPerThread; ++u) {
+                        const int k = kb + u * 256 + tid;
+                        w[u] = (k < a.kpad) ? a.wt[(size_t)(d0 + d) * a.kpad + k] : 0.f;
                     }
+                    float xv[kExactGroup];
+#pragma unroll
+                    for (int q = 0; q < kExactGroup / 4; ++q) {
+                        const float4 t = xs4[d][q];
+                        xv[4 * q + 0] = t.x;
+                        xv[4 * q + 1] = t.y;
+                        xv[4 * q + 2] = t.z;
+                        xv[4 * q + 3] = t.w;
+                    }
+#pragma unroll
+                    for (int s = 0; s < kExactGroup; ++s)
+#pragma unroll
+                        for (int u = 0; u < kExactNodesPerThread; ++u) {
+                            const float df = xv[s] - w[u];
+                            dist[s][u] = fmaf(df, df, dist[s][u]);
+                        }
                 }
             }
 #pragma unroll
-            for (int q = 0; q < 16; ++q) {
-                const int k = kb + q * 64 + lane;
-                if (k < a.K && dist[q] < bd) {
-                    bd = dist[q];
-                    bk = k;
+            for (int u = 0; u < kExactNodesPerThread; ++u) {
+                const int k = kb + u * 256 + tid;
+#pragma unroll
+                for (int s = 0; s < kExactGroup; ++s)
+                    if (k < a.K && dist[s][u] < bestd[s]) {
+                        bestd[s] = dist[s][u];
+                        bestk[s] = k;
+                    }
+            }
+        }
+        // lowest distance, then lowest node index, across the workgroup
+#pragma unroll
+        for (int s = 0; s < kExactGroup; ++s) {
+            float bd = bestd[s];
+            int bk = bestk[s];
+#pragma unroll
+            for (int o = 32; o > 0; o >>= 1) {
+                const float od = __shfl_xor(bd, o);
+                const int ok = __shfl_xor(bk, o);
+                if (od < bd || (od == bd && ok < bk)) {
+                    bd = od;
+                    bk = ok;
                 }
             }
-        }
-#pragma unroll
-        for (int o = 32; o > 0; o >>= 1) {
-            const float od = __shfl_xor(bd, o);
-            const int ok = __shfl_xor(bk, o);
-            if (od < bd || (od == bd && ok < bk)) {
-                bd = od;
-                bk = ok;
+            if (lane == 0) {
+                red_d[wave][s] = bd;
+                red_k[wave][s] = bk;
             }
         }
-        if (bk >= a.K) bk = 0; // only reachable with non-finite input
-        if (lane == 0) {
-            if (a.bmu) a.bmu[i] = bk;
+        __syncthreads();
+        if (tid < kExactGroup && g0 + tid < count) {
+            float bd = red_d[0][tid];
+            int bk = red_k[0][tid];
+            for (int w = 1; w < 4; ++w) {
+                const float od = red_d[w][tid];
+                const int ok = red_k[w][tid];
+                if (od < bd || (od == bd && ok < bk)) {
+                    bd = od;
+                    bk = ok;
+                }
+            }
+            if (bk >= a.K) bk = 0; // only reachable with non-finite input
+            const int64_t i = (int64_t)a.recheck[g0 + tid];
+            a.bmu[i] = bk;
             if (a.d2) a.d2[i] = bd;
             qs += sqrt((double)bd);
             qs2 += (double)bd;
-            if (FUSE) atomicAdd(&a.n[bk], 1ull);
         }
-        if (FUSE) add_row(xr, a.D, a.S + (size_t)bk * a.D, lane);
     }
-    if (a.qe && lane == 0 && (qs != 0.0 || qs2 != 0.0)) {
+    if (a.qe && tid < kExactGroup && (qs != 0.0 || qs2 != 0.0)) {
         unsafeAtomicAdd(&a.qe[0], qs);
         unsafeAtomicAdd(&a.qe[1], qs2);
     }
@@ -417,13 +465,13 @@ int bmu_prepare(som_ctx* ctx, const float* W, int32_t K, int32_t D, BmuPrep* out
     return check_hip(ctx, hipGetLastError(), "bmu_prep launch");
 }
 
-template <int STEPS, int MS, bool FUSE>
+template <int STEPS, int MS>
 static int launch_bmu(som_ctx* ctx, const BmuArgs& a)
 {
     constexpr int STRIDE = 2 * STEPS + 1;
     constexpr size_t lds_bytes = 2 * (size_t)stage_floats_for(STRIDE) * sizeof(float);
     static bool attr_set = false;
-    auto kern = bmu_kernel<STEPS, MS, FUSE>;
+    auto kern = bmu_kernel<STEPS, MS>;
     if (!attr_set) {
         if (int rc = check_hip(ctx,
                                hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -438,15 +486,14 @@ static int launch_bmu(som_ctx* ctx, const BmuArgs& a)
     return check_hip(ctx, hipGetLastError(), "bmu kernel launch");
 }
 
-template <bool FUSE>
 static int dispatch_bmu(som_ctx* ctx, int steps, const BmuArgs& a)
 {
     switch (steps) {
-    case 4: return launch_bmu<4, 2, FUSE>(ctx, a);
-    case 8: return launch_bmu<8, 2, FUSE>(ctx, a);
-    case 16: return launch_bmu<16, 2, FUSE>(ctx, a);
-    case 25: return launch_bmu<25, 2, FUSE>(ctx, a);
-    case 32: return launch_bmu<32, 2, FUSE>(ctx, a);
+    case 4: return launch_bmu<4, 2>(ctx, a);
+    case 8: return launch_bmu<8, 2>(ctx, a);
+    case 16: return launch_bmu<16, 2>(ctx, a);
+    case 25: return launch_bmu<25, 2>(ctx, a);
+    case 32: return launch_bmu<32, 2>(ctx, a);
     }
     return fail(ctx, SOM_EINVAL, "no BMU kernel for %d steps", steps);
 }
@@ -472,7 +519,6 @@ int bmu_run(som_ctx* ctx, const BmuPrep& prep, BmuArgs a)
     a.wt = prep.wt;
     a.scal = prep.scal;
     a.recheck = ctx->recheck;
-    const bool fuse = a.S != nullptr;
     // the list length restarts for every call; the prepared weights may serve several calls (chunks)
     if (int rc = launch_fill_zero(ctx, prep.scal + 1, 4)) return rc;
     hipEvent_t stop = nullptr;
@@ -487,15 +533,12 @@ int bmu_run(som_ctx* ctx, const BmuPrep& prep, BmuArgs a)
         stop = ctx->prof_events[ctx->prof_used].second;
         ++ctx->prof_used;
     }
-    int rc = fuse ? dispatch_bmu<true>(ctx, prep.steps, a) : dispatch_bmu<false>(ctx, prep.steps, a);
+    int rc = dispatch_bmu(ctx, prep.steps, a);
     if (stop) (void)hipEventRecord(stop, ctx->stream);
     if (rc) return rc;
     if (a.K > 1) {
-        if (fuse)
-            hipLaunchKernelGGL(bmu_recheck_kernel<true>, dim3(512), dim3(256), 0, ctx->stream, a);
-        else
-            hipLaunchKernelGGL(bmu_recheck_kernel<false>, dim3(512), dim3(256), 0, ctx->stream, a);
-        rc = check_hip(ctx, hipGetLastError(), "bmu recheck launch");
+        hipLaunchKernelGGL(bmu_exact_kernel, dim3(1024), dim3(256), 0, ctx->stream, a);
+        rc = check_hip(ctx, hipGetLastError(), "bmu exact-pass launch");
     }
     return rc;
 }

@@ -14,10 +14,6 @@ namespace som {
 constexpr int kNodesPerStage = 128;   // nodes of W staged through LDS at a time by the BMU kernel
 constexpr int kMaxStepsResident = 32; // BMU kernel keeps a sample's features in registers up to D = 64
 
-// Score-gap threshold, relative to the magnitude bound 0.5|x|^2 + max_k |w_k|^2 of the float32 dot-product
-// accumulation: a sample whose best two scores are closer than this is re-decided by direct differences.
-constexpr float kRecheckRel = 1.0f / 262144.0f; // 2^-18, about 64 float32 roundings of that magnitude
-
 struct BmuPrep {
     float* stage = nullptr;        // [Kpad / 128][128 * (stride + 1)]: padded weight rows, then -|w|^2 / 2
     float* wt = nullptr;           // [D][Kpad] transposed weights
@@ -36,11 +32,9 @@ struct BmuArgs {
     const float* wt;         // BmuPrep::wt
     unsigned int* scal;      // BmuPrep::scal
     uint32_t* recheck;       // [m] sample positions to re-decide
-    int32_t* bmu;            // may be null in the fused epoch
+    int32_t* bmu;            // [m], always written
     float* d2;               // may be null
-    double* qe;              // [2], accumulated (caller zeroes)
-    double* S;               // fused accumulation targets, null when not fused
-    unsigned long long* n;
+    double* qe;              // [2], accumulated (caller zeroes); may be null
 };
 
 } // namespace som
@@ -56,6 +50,10 @@ struct som_ctx {
     size_t prep_bytes = 0;
     uint32_t* recheck = nullptr;
     size_t recheck_cap = 0;
+    int32_t* bmu_ws = nullptr;     // BMU indices of the epoch drivers (one chunk's worth)
+    size_t bmu_elems = 0;
+    void* acc_blob = nullptr;      // per-workgroup float64 slices + counts of the accumulation pass
+    size_t acc_bytes = 0;
     // epoch-internal accumulators
     double* S = nullptr;
     size_t S_elems = 0;
@@ -87,7 +85,7 @@ int launch_fill_zero(som_ctx* ctx, void* p, size_t bytes);
 int bmu_prepare(som_ctx* ctx, const float* W, int32_t K, int32_t D, BmuPrep* out);
 int bmu_run(som_ctx* ctx, const BmuPrep& prep, BmuArgs args);
 int accumulate_run(som_ctx* ctx, const float* X, int32_t D, int64_t ldx, const uint32_t* idx, int64_t m,
-                   const int32_t* bmu, int32_t K, double* S, unsigned long long* n);
+                   const int32_t* bmu, int32_t K, double* S, unsigned long long* n, bool zero_first);
 int update_run(som_ctx* ctx, const double* S, const unsigned long long* n, const float* G, int32_t K,
                int32_t D, double sigma, double eps_h, float* W, int32_t* small);
 
