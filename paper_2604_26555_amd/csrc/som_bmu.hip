@@ -297,6 +297,7 @@ __global__ void __launch_bounds__(256) bmu_exact_kernel(const BmuArgs a)
     __shared__ float red_d[4][kExactGroup];
     __shared__ int red_k[4][kExactGroup];
     float* xs = reinterpret_cast<float*>(xs4);
+    const float* __restrict__ wt = a.wt;
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
     const unsigned int count = a.scal[1];
@@ -327,29 +328,37 @@ __global__ void __launch_bounds__(256) bmu_exact_kernel(const BmuArgs a)
                     xs[d * kExactGroup + s] = a.X[r * a.ldx + d0 + d];
                 }
                 __syncthreads();
-                for (int d = 0; d < dn; ++d) {
-                    float w[kExactNodesPerThread];
+                // four features at a time: their sixteen weight loads are in flight together
+                for (int d = 0; d < dn; d += 4) {
+                    float w[4][kExactNodesPerThread];
 #pragma unroll
-                    for (int u = 0; u < kExactNodesPerThread; ++u) {
-                        const int k = kb + u * 256 + tid;
-                        w[u] = (k < a.kpad) ? a.wt[(size_t)(d0 + d) * a.kpad + k] : 0.f;
-                    }
-                    float xv[kExactGroup];
-#pragma unroll
-                    for (int q = 0; q < kExactGroup / 4; ++q) {
-                        const float4 t = xs4[d][q];
-                        xv[4 * q + 0] = t.x;
-                        xv[4 * q + 1] = t.y;
-                        xv[4 * q + 2] = t.z;
-                        xv[4 * q + 3] = t.w;
-                    }
-#pragma unroll
-                    for (int s = 0; s < kExactGroup; ++s)
+                    for (int t = 0; t < 4; ++t)
 #pragma unroll
                         for (int u = 0; u < kExactNodesPerThread; ++u) {
-                            const float df = xv[s] - w[u];
-                            dist[s][u] = fmaf(df, df, dist[s][u]);
+                            const int k = kb + u * 256 + tid;
+                            w[t][u] = (k < a.kpad && d + t < dn) ? wt[(size_t)(d0 + d + t) * a.kpad + k] : 0.f;
                         }
+#pragma unroll
+                    for (int t = 0; t < 4; ++t) {
+                        if (d + t < dn) {
+                            float xv[kExactGroup];
+#pragma unroll
+                            for (int q = 0; q < kExactGroup / 4; ++q) {
+                                const float4 v4 = xs4[d + t][q];
+                                xv[4 * q + 0] = v4.x;
+                                xv[4 * q + 1] = v4.y;
+                                xv[4 * q + 2] = v4.z;
+                                xv[4 * q + 3] = v4.w;
+                            }
+#pragma unroll
+                            for (int s = 0; s < kExactGroup; ++s)
+#pragma unroll
+                                for (int u = 0; u < kExactNodesPerThread; ++u) {
+                                    const float df = xv[s] - w[t][u];
+                                    dist[s][u] = fmaf(df, df, dist[s][u]);
+                                }
+                        }
+                    }
                 }
             }
 #pragma unroll

@@ -54,6 +54,8 @@ struct som_ctx {
     size_t bmu_elems = 0;
     void* acc_blob = nullptr;      // per-workgroup float64 slices + counts of the accumulation pass
     size_t acc_bytes = 0;
+    void* upd_blob = nullptr;      // influence matrix + split-k partials of the update
+    size_t upd_bytes = 0;
     // epoch-internal accumulators
     double* S = nullptr;
     size_t S_elems = 0;

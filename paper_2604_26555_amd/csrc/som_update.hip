@@ -2,79 +2,154 @@
 // per-sample sums of Eq. 3 grouped by best-matching unit):
 //     Num_j = sum_k h(G[k][j]) S_k,   Den_j = sum_k h(G[k][j]) n_k,   h(g) = exp(-g^2 / (2 sigma^2)),
 //     w_j <- Num_j / Den_j  where Den_j >= eps_h, otherwise w_j stays.
-// One workgroup owns kTJ updated nodes and 64 features; it walks the K contributing nodes in chunks of 64,
-// evaluating the influences of the chunk once (one exp per thread) and staging the chunk's rows of S in LDS.
+// Three small launches, all latency-bound at K ~ 1000, so each is shaped for many independent workgroups:
+//   1. influence_kernel    h[k][j] for all K x K pairs, one exp per thread (K^2 threads);
+//   2. contract_kernel     partial Num / Den over a quarter of the k range per workgroup (split-k keeps four
+//                          workgroups per compute unit in flight; partials are stored, not atomically added);
+//   3. finish_kernel       adds the partials in a fixed order, applies the threshold, writes W, counts.
+// The contraction is 2 K^2 (D + 1) float64 flops (0.1 GFLOP at K = 1024, D = 50): microseconds on the vector
+// ALUs, so it stays a plain FMA loop.
 #include "som_internal.hpp"
 
 #include <math.h>
 
 namespace som {
 
-constexpr int kTJ = 4;   // updated nodes per workgroup (one wavefront each)
-constexpr int kKC = 64;  // contributing nodes per chunk
+constexpr int kTJ = 4;       // updated nodes per workgroup (one wavefront each)
+constexpr int kKC = 32;      // contributing nodes staged per step (two LDS buffers of kKC x 64 doubles)
+constexpr int kSplitK = 4;   // workgroups sharing one block of updated nodes
 
-__global__ void __launch_bounds__(kTJ * 64) update_kernel(const double* __restrict__ S,
-                                                          const unsigned long long* __restrict__ n,
-                                                          const float* __restrict__ G, int K, int D, double inv2s2,
-                                                          double eps_h, float* __restrict__ W,
-                                                          int32_t* __restrict__ small)
+__global__ void __launch_bounds__(256) influence_kernel(const float* __restrict__ G, int K, double inv2s2,
+                                                        double* __restrict__ H)
 {
-    __shared__ double hs[kKC][kTJ];
-    __shared__ double ns[kKC];
-    __shared__ double Ss[kKC][64];
+    const size_t e = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (e >= (size_t)K * K) return;
+    const double gd = (double)G[e];
+    H[e] = isinf(gd) ? 0.0 : exp(-(gd * gd) * inv2s2);
+}
+
+// grid (K / kTJ, ceil(D / 64), kSplitK); thread = (node jj = tid / 64, feature dl = tid % 64)
+__global__ void __launch_bounds__(kTJ * 64) contract_kernel(const double* __restrict__ H, const double* __restrict__ S,
+                                                            const unsigned long long* __restrict__ n, int K, int D,
+                                                            double* __restrict__ part)
+{
+    __shared__ double hs[2][kKC][kTJ];
+    __shared__ double ns[2][kKC];
+    __shared__ double Ss[2][kKC][64];
     const int tid = threadIdx.x;
-    const int jj = tid >> 6;          // which of the workgroup's nodes
-    const int dl = tid & 63;          // feature within the 64-wide slab
+    const int jj = tid >> 6, dl = tid & 63;
     const int j0 = blockIdx.x * kTJ;
     const int d0 = blockIdx.y * 64;
-    const int j = j0 + jj;
-    const int d = d0 + dl;
+    const int kper = ((K + kSplitK * kKC - 1) / (kSplitK * kKC)) * kKC;
+    const int k_lo = blockIdx.z * kper;
+    const int k_hi = (k_lo + kper < K) ? k_lo + kper : K;
+    constexpr int SLOADS = kKC * 64 / (kTJ * 64);
     double num = 0.0, den = 0.0;
-    for (int kc = 0; kc < K; kc += kKC) {
-        // influences of this chunk on the workgroup's nodes: thread -> (k = tid / kTJ, node tid % kTJ)
-        {
-            const int kk = tid / kTJ, q = tid % kTJ;
-            const int k = kc + kk;
-            double h = 0.0;
-            if (k < K && j0 + q < K) {
-                const double gd = (double)G[(size_t)k * K + j0 + q];
-                h = isinf(gd) ? 0.0 : exp(-(gd * gd) * inv2s2);
-            }
-            hs[kk][q] = h;
-            if (q == 0) ns[kk] = (k < K) ? (double)n[k] : 0.0;
-        }
-        for (int e = tid; e < kKC * 64; e += kTJ * 64) {
+    double pre_s[SLOADS], pre_h = 0.0, pre_n = 0.0;
+
+    auto fetch = [&](int kc) {
+#pragma unroll
+        for (int p = 0; p < SLOADS; ++p) {
+            const int e = tid + p * kTJ * 64;
             const int kk = e >> 6, f = e & 63;
             const int k = kc + kk;
-            Ss[kk][f] = (k < K && d0 + f < D) ? S[(size_t)k * D + d0 + f] : 0.0;
+            pre_s[p] = (k < k_hi && d0 + f < D) ? S[(size_t)k * D + d0 + f] : 0.0;
         }
-        __syncthreads();
+        const int kk = tid / kTJ, q = tid % kTJ;      // the first kKC * kTJ threads bring the influences
+        const int k = kc + kk;
+        const bool mine = kk < kKC && k < k_hi;
+        pre_h = (mine && j0 + q < K) ? H[(size_t)k * K + j0 + q] : 0.0;
+        pre_n = (mine && q == 0) ? (double)n[k] : 0.0;
+    };
+    auto stash = [&](int buf) {
+#pragma unroll
+        for (int p = 0; p < SLOADS; ++p) {
+            const int e = tid + p * kTJ * 64;
+            Ss[buf][e >> 6][e & 63] = pre_s[p];
+        }
+        if (tid < kKC * kTJ) {
+            hs[buf][tid / kTJ][tid % kTJ] = pre_h;
+            if (tid % kTJ == 0) ns[buf][tid / kTJ] = pre_n;
+        }
+    };
+
+    if (k_lo < k_hi) {
+        fetch(k_lo);
+        stash(0);
+    }
+    __syncthreads();
+    int buf = 0;
+    for (int kc = k_lo; kc < k_hi; kc += kKC, buf ^= 1) {
+        const bool more = kc + kKC < k_hi;
+        if (more) fetch(kc + kKC);
 #pragma unroll 8
         for (int kk = 0; kk < kKC; ++kk) {
-            const double h = hs[kk][jj];
-            num = fma(h, Ss[kk][dl], num);
-            den = fma(h, ns[kk], den);
+            const double h = hs[buf][kk][jj];
+            num = fma(h, Ss[buf][kk][dl], num);
+            den = fma(h, ns[buf][kk], den);
         }
+        if (more) stash(buf ^ 1);
         __syncthreads();
     }
+    const int j = j0 + jj, d = d0 + dl;
     if (j < K) {
-        const bool ok = den >= eps_h;
-        if (ok && d < D) W[(size_t)j * D + d] = (float)(num / den);
-        if (dl == 0 && blockIdx.y == 0 && small) {
-            if (!ok) atomicAdd(&small[0], 1);
-            if (n[j] == 0ull) atomicAdd(&small[1], 1);
-        }
+        double* row = part + ((size_t)blockIdx.z * K + j) * (D + 1);
+        if (d < D) row[d] = num;
+        if (dl == 0 && blockIdx.y == 0) row[D] = den;
+    }
+}
+
+__global__ void __launch_bounds__(256) finish_kernel(const double* __restrict__ part,
+                                                     const unsigned long long* __restrict__ n, int K, int D,
+                                                     double eps_h, float* __restrict__ W, int32_t* __restrict__ small)
+{
+    const int e = blockIdx.x * 256 + threadIdx.x;
+    if (e >= K * D) return;
+    const int j = e / D, d = e % D;
+    const size_t stride = (size_t)K * (D + 1);
+    const double* row = part + (size_t)j * (D + 1);
+    double num = 0.0, den = 0.0;
+#pragma unroll
+    for (int z = 0; z < kSplitK; ++z) {
+        num += row[z * stride + d];
+        den += row[z * stride + D];
+    }
+    const bool ok = den >= eps_h;
+    if (ok) W[e] = (float)(num / den);
+    if (d == 0 && small) {
+        if (!ok) atomicAdd(&small[0], 1);
+        if (n[j] == 0ull) atomicAdd(&small[1], 1);
     }
 }
 
 int update_run(som_ctx* ctx, const double* S, const unsigned long long* n, const float* G, int32_t K, int32_t D,
                double sigma, double eps_h, float* W, int32_t* small)
 {
-    const double s = sigma;
-    const double inv2s2 = 1.0 / (2.0 * s * s);
-    dim3 grid((K + kTJ - 1) / kTJ, (D + 63) / 64);
-    hipLaunchKernelGGL(update_kernel, grid, dim3(kTJ * 64), 0, ctx->stream, S, n, G, K, D, inv2s2, eps_h, W, small);
-    return check_hip(ctx, hipGetLastError(), "update kernel launch");
+    const size_t h_elems = (size_t)K * K;
+    const size_t need = (h_elems + (size_t)kSplitK * K * (D + 1)) * sizeof(double);
+    if (need > ctx->upd_bytes) {
+        if (ctx->upd_blob) {
+            if (int rc = check_hip(ctx, hipStreamSynchronize(ctx->stream), "sync before workspace growth")) return rc;
+            (void)hipFree(ctx->upd_blob);
+            ctx->upd_blob = nullptr;
+            ctx->upd_bytes = 0;
+        }
+        if (hipMalloc(&ctx->upd_blob, need) != hipSuccess) {
+            (void)hipGetLastError();
+            return fail(ctx, SOM_ENOMEM, "cannot allocate %zu bytes for the update workspace", need);
+        }
+        ctx->upd_bytes = need;
+    }
+    double* H = (double*)ctx->upd_blob;
+    double* part = H + h_elems;
+    const double inv2s2 = 1.0 / (2.0 * sigma * sigma);
+    hipLaunchKernelGGL(influence_kernel, dim3((unsigned)((h_elems + 255) / 256)), dim3(256), 0, ctx->stream, G, K, inv2s2, H);
+    if (int rc = check_hip(ctx, hipGetLastError(), "influence kernel launch")) return rc;
+    dim3 grid((K + kTJ - 1) / kTJ, (D + 63) / 64, kSplitK);
+    hipLaunchKernelGGL(contract_kernel, grid, dim3(kTJ * 64), 0, ctx->stream, H, S, n, K, D, part);
+    if (int rc = check_hip(ctx, hipGetLastError(), "contraction kernel launch")) return rc;
+    hipLaunchKernelGGL(finish_kernel, dim3((K * D + 255) / 256), dim3(256), 0, ctx->stream, part, n, K, D, eps_h, W, small);
+    return check_hip(ctx, hipGetLastError(), "update finish launch");
 }
 
 } // namespace som
