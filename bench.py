@@ -29,6 +29,8 @@ def main() -> int:
     ap.add_argument("--rows", type=int, default=None, help="override the workload's sample count")
     ap.add_argument("--cpu-rows", type=int, default=1_000_000, help="rows of the workload the CPU oracle is timed on")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run one plain device-to-device copy of X (known size) for scaling hardware counters")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
@@ -100,10 +102,18 @@ def main() -> int:
     flops = 2.0 * m * wl.k * wl.d                          # algorithmic: 2 K D per presented sample
     achieved = flops / (avg_kernel_ms * 1e-3) / 1e12 if kernel_ms else float("nan")
     traffic = None
-    pmc = os.path.join(ROOT, "profiles", f"bmu_kernel_{wl.name}_hbm_traffic.json")
-    if os.path.exists(pmc):
-        traffic = json.load(open(pmc)).get("traffic_bytes_per_launch")
+    # measured off-line with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (scaled by a plain copy); see profiles/
+    pmc = os.path.join(ROOT, "profiles", f"epoch_{wl.name}_hbm_traffic.md")
+    if os.path.exists(pmc) and args.rows is None:
+        for line in open(pmc):
+            if line.startswith("traffic_bytes_per_launch_bmu_kernel:"):
+                traffic = float(line.split(":")[1])
 
+    if args.copy_calibration:
+        Xcopy = torch.empty_like(Xd)
+        Xcopy.copy_(Xd)                      # reads and writes X.numel() * 4 bytes
+        torch.cuda.synchronize()
+        del Xcopy
     qe = torch.zeros(2, dtype=torch.float64, device="cuda")
     som.som_bmu(Xd, Wd, qe=qe)
     final_qe = float(qe[0].item()) / m
