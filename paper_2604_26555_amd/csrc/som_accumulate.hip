@@ -181,6 +181,11 @@ __global__ void __launch_bounds__(256) accumulate_direct_kernel(const float* __r
 int accumulate_run(som_ctx* ctx, const float* X, int32_t D, int64_t ldx, const uint32_t* idx, int64_t m,
                    const int32_t* bmu, int32_t K, double* S, unsigned long long* n, bool zero_first)
 {
+    // maps whose K x (D + 1) partial fits one workgroup's MFMA accumulators take the atomic-free path
+    {
+        const int rc = accumulate_mfma_run(ctx, X, D, ldx, idx, m, bmu, K, S, n, zero_first);
+        if (rc != 1) return rc;
+    }
     // widest feature slab whose LDS footprint fits
     int ws = D < 256 ? D : 256;   // the kernel's multiply-high division is exact for slabs up to 512 wide
     while (ws >= 1 && acc_lds_bytes(K, ws) > kAccLdsBytes) --ws;
