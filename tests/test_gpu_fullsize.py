@@ -1,0 +1,101 @@
+"""Parity at the benchmark's own size and launch configuration: cfg1, 1,000,000 x 50 samples, 1024 nodes.
+
+The brute-force oracle checks a seeded sample of rows one by one; properties that hold at any size cover the rest
+(counts add up to m, the per-node sums add up to the column sums of X, BMU distances reproduce the QE), and one
+teacher-forced epoch is compared against the oracle's grouped form on all rows.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from synth import draw_initial_rows, linear_sigma, make_workload
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def som():
+    from paper_2604_26555_amd import Som
+    s = Som(0)
+    yield s
+    s.close()
+
+
+@pytest.fixture(scope="module")
+def cfg1():
+    wl = make_workload("cfg1")
+    X = wl.data().rows(0, wl.n)
+    W0 = X[draw_initial_rows(wl.seed, wl.n, wl.k)].copy()
+    return wl, X, W0
+
+
+def trained(som, wl, Xd, W0, epochs):
+    """Weights after a few GPU epochs (a spread-out map rather than the initial sample rows)."""
+    from paper_2604_26555_amd import topology
+    G = torch.from_numpy(topology.graph_distances(wl.topology, lattice=wl.lattice)).cuda()
+    Wd = torch.from_numpy(W0).cuda()
+    sig = linear_sigma(*wl.sigma, wl.epochs)
+    for e in range(epochs):
+        som.som_epoch(Xd, Wd, G, float(sig[e]), want_stats=False)
+    som.som_sync()
+    return Wd, G, sig
+
+
+@pytest.mark.parametrize("epochs", [0, 3, 12])
+def test_full_size_bmu_sampled_against_brute_force(som, cfg1, epochs):
+    wl, X, W0 = cfg1
+    Xd = torch.from_numpy(X).cuda()
+    Wd, _, _ = trained(som, wl, Xd, W0, epochs)
+    W = Wd.cpu().numpy()
+    d2 = torch.empty(wl.n, dtype=torch.float32, device="cuda")
+    qe = torch.zeros(2, dtype=torch.float64, device="cuda")
+    b_gpu, _, _ = som.som_bmu(Xd, Wd, d2=d2, qe=qe)
+    b_gpu, d2 = b_gpu.cpu().numpy(), d2.cpu().numpy()
+    rows = np.sort(np.random.default_rng(77 + epochs).choice(wl.n, 4000, replace=False))
+    rows = np.unique(np.concatenate([rows, [0, 255, 256, wl.n - 65, wl.n - 1]]))      # tile edges and the ragged tail
+    b, best, second = oracle.bmu(X[rows], W)
+    mask = oracle.near_tie_mask(best, second)
+    assert ((b_gpu[rows] == b) | mask).all()
+    same = b_gpu[rows] == b
+    np.testing.assert_allclose(d2[rows][same], best[same], rtol=1e-4, atol=1e-12)
+    # properties at full size
+    assert b_gpu.min() >= 0 and b_gpu.max() < wl.k
+    q = qe.cpu().numpy()
+    assert abs(q[1] - d2.astype(np.float64).sum()) <= 1e-6 * q[1]
+    assert abs(q[0] - np.sqrt(d2.astype(np.float64)).sum()) <= 1e-6 * q[0]
+    # every reported distance is the distance to the reported node
+    chk = np.random.default_rng(5).choice(wl.n, 20000, replace=False)
+    direct = ((X[chk].astype(np.float64) - W[b_gpu[chk]].astype(np.float64)) ** 2).sum(1)
+    np.testing.assert_allclose(d2[chk], direct, rtol=1e-4, atol=1e-12)
+
+
+def test_full_size_accumulate_properties_and_epoch(som, cfg1):
+    wl, X, W0 = cfg1
+    Xd = torch.from_numpy(X).cuda()
+    Wd, G, sig = trained(som, wl, Xd, W0, 5)
+    W = Wd.cpu().numpy()
+    b_gpu, _, _ = som.som_bmu(Xd, Wd)
+    S = torch.zeros((wl.k, wl.d), dtype=torch.float64, device="cuda")
+    n = torch.zeros(wl.k, dtype=torch.int64, device="cuda")
+    som.som_accumulate(Xd, b_gpu, wl.k, S, n)
+    S, n = S.cpu().numpy(), n.cpu().numpy()
+    b_np = b_gpu.cpu().numpy()
+    assert n.sum() == wl.n and (n == np.bincount(b_np, minlength=wl.k)).all()
+    col = X.astype(np.float64).sum(0)
+    # every sample enters one float32 addition whose result is below a few max|x|: at most n * 2^-24 * max|x| in total
+    np.testing.assert_allclose(S.sum(0), col, rtol=0, atol=wl.n * 2.0 ** -24 * np.abs(X).max())
+    S_or, _ = oracle.accumulate(X, None, b_np, wl.k)
+    assert (np.abs(S - S_or) <= 1e-6 * np.abs(X).max() * np.maximum(n, 1)[:, None]).all()
+    # one teacher-forced epoch on all rows against the oracle's grouped form
+    ref_b, best, second = oracle.bmu_gram(X, W)
+    mask = oracle.near_tie_mask(best, second)
+    assert ((b_np == ref_b) | mask).all(), f"{((b_np != ref_b) & ~mask).sum()} BMU mismatches outside the near-tie mask"
+    b_use = np.where(mask, b_np, ref_b)
+    G_or = oracle.graph_distances(wl.topology, lattice=wl.lattice)
+    ref = oracle.epoch_grouped(X, None, W, G_or, float(sig[5]), b=b_use)
+    st = som.som_epoch(Xd, Wd, G, float(sig[5]))
+    scale = np.abs(ref["W"]).max(axis=1, keepdims=True)
+    assert (np.abs(Wd.cpu().numpy() - ref["W"]) <= 1e-4 * scale).all()
+    assert abs(st.qe - oracle.quantization_error(best)) <= 1e-4 * oracle.quantization_error(best)
+    assert st.n_empty == int((ref["n"] == 0).sum()) and st.m == wl.n
