@@ -93,8 +93,9 @@ __device__ __forceinline__ float vmax(float a, float b)
 // ---------------------------------------------------------------------------------------------------------
 // main kernel
 // ---------------------------------------------------------------------------------------------------------
+// two workgroups per compute unit (LDS-bound), i.e. two wavefronts per SIMD: the register budget is 256 VGPRs
 template <int STEPS, int MS>
-__global__ void __launch_bounds__(kThreads) bmu_kernel(const BmuArgs a)
+__global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 2))) bmu_kernel(const BmuArgs a)
 {
     constexpr int STRIDE = 2 * STEPS + 1;
     constexpr int STAGE_FLOATS = stage_floats_for(STRIDE);   // whole float4s per thread: no tail handling
@@ -142,29 +143,36 @@ __global__ void __launch_bounds__(kThreads) bmu_kernel(const BmuArgs a)
     const int nstages = a.kpad / kNodesPerStage;
     const float4* src4 = reinterpret_cast<const float4*>(a.stage);
     {
+        float4 first[PRE];
 #pragma unroll
-        for (int p = 0; p < PRE; ++p) {
-            const int e = tid + p * kThreads;
-            lds4[e] = src4[e];
-        }
+        for (int p = 0; p < PRE; ++p) first[p] = src4[tid + p * kThreads];
+#pragma unroll
+        for (int p = 0; p < PRE; ++p) lds4[tid + p * kThreads] = first[p];
     }
     __syncthreads();
 
     for (int st = 0; st < nstages; ++st) {
         const int buf = st & 1;
         // the next stage travels global -> registers now and registers -> LDS after this stage's arithmetic
-        // (the last iteration reloads its own stage into the idle buffer, which keeps the loop branch-free)
-        float4 pre[PRE];
+        // (the last iteration reloads its own stage into the idle buffer, which keeps the loop branch-free).
+        // Named scalars rather than an array, and a scheduling fence behind the loads: otherwise the compiler
+        // sinks every load to its use after the MFMAs and the copy is no longer hidden.
+        float4 pre0, pre1, pre2, pre3, pre4, pre5, pre6, pre7, pre8;
+        static_assert(PRE <= 9, "stage copy holds at most nine float4 per thread");
         {
             const int nxt = (st + 1 < nstages) ? st + 1 : st;
-            const float4* s4 = src4 + (size_t)nxt * STAGE_F4;
-#pragma unroll
-            for (int p = 0; p < PRE; ++p) pre[p] = s4[tid + p * kThreads];
+            const float4* s4 = src4 + (size_t)nxt * STAGE_F4 + tid;
+#define SOM_PRE_LOAD(i) if constexpr (PRE > i) pre##i = s4[i * kThreads];
+            SOM_PRE_LOAD(0) SOM_PRE_LOAD(1) SOM_PRE_LOAD(2) SOM_PRE_LOAD(3) SOM_PRE_LOAD(4)
+            SOM_PRE_LOAD(5) SOM_PRE_LOAD(6) SOM_PRE_LOAD(7) SOM_PRE_LOAD(8)
+#undef SOM_PRE_LOAD
         }
+        __builtin_amdgcn_sched_barrier(0);
         const float* wbuf = lds + buf * STAGE_FLOATS;
         const float* nbuf = wbuf + kNodesPerStage * STRIDE;
 
-#pragma unroll 1
+        // fully unrolled: with the stage body in one basic block the prefetch loads above stay ahead of the MFMAs
+#pragma unroll
         for (int nb = 0; nb < kNodesPerStage / 32; ++nb) {
             const float* wrow = wbuf + (nb * 32 + j) * STRIDE + g;
             float wa[STEPS];
@@ -206,9 +214,11 @@ __global__ void __launch_bounds__(kThreads) bmu_kernel(const BmuArgs a)
         }
 
         {
-            float4* d4 = lds4 + (buf ^ 1) * STAGE_F4;
-#pragma unroll
-            for (int p = 0; p < PRE; ++p) d4[tid + p * kThreads] = pre[p];
+            float4* d4 = lds4 + (buf ^ 1) * STAGE_F4 + tid;
+#define SOM_PRE_STORE(i) if constexpr (PRE > i) d4[i * kThreads] = pre##i;
+            SOM_PRE_STORE(0) SOM_PRE_STORE(1) SOM_PRE_STORE(2) SOM_PRE_STORE(3) SOM_PRE_STORE(4)
+            SOM_PRE_STORE(5) SOM_PRE_STORE(6) SOM_PRE_STORE(7) SOM_PRE_STORE(8)
+#undef SOM_PRE_STORE
         }
         __syncthreads();
     }
