@@ -198,11 +198,9 @@ int som_bmu(som_ctx* ctx, const float* X, int64_t N, int32_t D, int64_t ldx, con
     if ((N > 0 && !device_readable(X)) || !device_readable(W) || (m > 0 && !device_readable(bmu)))
         return fail(ctx, SOM_EINVAL, "X, W and bmu must be device-accessible memory");
     if (int rc = check_hip(ctx, hipSetDevice(ctx->device), "hipSetDevice")) return rc;
-    if (qe)
-        if (int rc = launch_fill_zero(ctx, qe, 2 * sizeof(double))) return rc;
-    if (m == 0) return SOM_OK;
+    if (m == 0) return qe ? launch_fill_zero(ctx, qe, 2 * sizeof(double)) : SOM_OK;
     BmuPrep prep;
-    if (int rc = bmu_prepare(ctx, W, K, D, &prep)) return rc;
+    if (int rc = bmu_prepare(ctx, W, K, D, &prep, qe, nullptr)) return rc;
     BmuArgs a{};
     a.X = X;
     a.ldx = ldx;
@@ -267,8 +265,7 @@ static int begin_epoch(som_ctx* ctx, int32_t K, int32_t D, int64_t chunk_rows)
     if (int rc = grow(ctx, &ctx->bmu_ws, &ctx->bmu_elems, (size_t)chunk_rows, "the BMU indices")) return rc;
     if (int rc = grow(ctx, &ctx->S, &ctx->S_elems, (size_t)K * D, "the per-node sums")) return rc;
     if (int rc = grow(ctx, &ctx->n, &ctx->n_elems, (size_t)K, "the per-node counts")) return rc;
-    if (int rc = launch_fill_zero(ctx, ctx->qe, 2 * sizeof(double))) return rc;
-    return launch_fill_zero(ctx, ctx->small, 64);
+    return SOM_OK;   // qe and the small counters are cleared by the weight-preparation kernel
 }
 
 static int finish_stats(som_ctx* ctx, int64_t m, int64_t n_recheck, som_stats* stats, bool timed, float ms_h2d)
@@ -312,7 +309,7 @@ int som_epoch(som_ctx* ctx, const float* X, int64_t N, int32_t D, int64_t ldx, c
     if (int rc = begin_epoch(ctx, K, D, m)) return rc;
     BmuPrep prep;
     if (stats) (void)hipEventRecord(ctx->ev_t[0], ctx->stream);
-    if (int rc = bmu_prepare(ctx, W, K, D, &prep)) return rc;
+    if (int rc = bmu_prepare(ctx, W, K, D, &prep, ctx->qe, ctx->small)) return rc;
     BmuArgs a{};
     a.X = X;
     a.ldx = ldx;
@@ -334,7 +331,7 @@ int som_epoch(som_ctx* ctx, const float* X, int64_t N, int32_t D, int64_t ldx, c
     if (stats) {
         (void)hipEventRecord(ctx->ev_t[2], ctx->stream);
         if (int rc = finish_stats(ctx, m, 0, stats, true, 0.f)) return rc;
-        stats->n_recheck = h->scal[2];
+        stats->n_recheck = h->scal[3];
     }
     return SOM_OK;
 }
@@ -401,7 +398,7 @@ int som_epoch_host(som_ctx* ctx, const float* Xhost, int64_t N, int32_t D, int64
     if (int rc = begin_epoch(ctx, K, D, chunk_rows)) return rc;
     BmuPrep prep;
     (void)hipEventRecord(ctx->ev_t[0], ctx->stream);
-    if (int rc = bmu_prepare(ctx, W, K, D, &prep)) return rc;
+    if (int rc = bmu_prepare(ctx, W, K, D, &prep, ctx->qe, ctx->small)) return rc;
 
     const int64_t nchunks = (N + chunk_rows - 1) / chunk_rows;
     HostSmall* h = (HostSmall*)ctx->host_small;
@@ -458,7 +455,7 @@ int som_epoch_host(som_ctx* ctx, const float* Xhost, int64_t N, int32_t D, int64
     }
     for (hipEvent_t e : h2d_marks) (void)hipEventDestroy(e);
     if (rc) return rc;
-    if (stats) return finish_stats(ctx, N, (int64_t)h->scal[2], stats, true, ms_h2d);
+    if (stats) return finish_stats(ctx, N, (int64_t)h->scal[3], stats, true, ms_h2d);
     return SOM_OK;
 }
 

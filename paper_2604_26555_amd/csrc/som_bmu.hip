@@ -39,29 +39,41 @@ constexpr int stage_floats_for(int stride)
 }
 
 // ---------------------------------------------------------------------------------------------------------
-// Weight preparation: padded rows + half squared norms per 128-node stage, transposed copy, largest norm.
+// Weight preparation: padded rows + half squared norms per 128-node stage, transposed copy, largest squared
+// norm (scal[0], cleared beforehand), and the zeroing of the result words the later kernels count into.
+// One thread per element of the padded K x stride matrix (coalesced reads of W); the first kpad threads also
+// compute their node's norm in float64.
 // ---------------------------------------------------------------------------------------------------------
-__global__ void __launch_bounds__(128) bmu_prep_kernel(const float* __restrict__ W, int K, int D, int kpad,
-                                                       int stride, int stage_floats, float* __restrict__ stage,
-                                                       float* __restrict__ wt, unsigned int* __restrict__ scal)
+__global__ void __launch_bounds__(256) bmu_prep_kernel(const float* __restrict__ W, int K, int D, int kpad, int stride,
+                                                       int stage_floats, float* __restrict__ stage,
+                                                       float* __restrict__ wt, unsigned int* __restrict__ scal,
+                                                       double* __restrict__ qe, int32_t* __restrict__ small)
 {
-    const int k = blockIdx.x * blockDim.x + threadIdx.x;
-    if (k >= kpad) return;
-    const int st = k / kNodesPerStage, r = k % kNodesPerStage;
-    float* blob = stage + (size_t)st * stage_floats;
-    float* dst = blob + (size_t)r * stride;
-    double nrm = 0.0;
-    for (int f = 0; f < stride; ++f) {
+    const int e = blockIdx.x * 256 + threadIdx.x;
+    if (e < 2 && qe) qe[e] = 0.0;
+    if (e < 4 && small) small[e] = 0;
+    if (e < kpad * stride) {
+        const int k = e / stride, f = e - k * stride;
         const float v = (k < K && f < D) ? W[(size_t)k * D + f] : 0.0f;
-        dst[f] = v;
-        nrm += (double)v * (double)v;
+        const int st = k / kNodesPerStage, r = k % kNodesPerStage;
+        stage[(size_t)st * stage_floats + (size_t)r * stride + f] = v;
         if (f < D) wt[(size_t)f * kpad + k] = v;
     }
-    blob[(size_t)kNodesPerStage * stride + r] = (k < K) ? (float)(-0.5 * nrm) : -INFINITY;
-    if (k < K) {
-        float up = (float)nrm;
-        if ((double)up < nrm) up = nextafterf(up, INFINITY);
-        atomicMax(&scal[0], __float_as_uint(up));
+    if (e < kpad) {
+        const int k = e;
+        double nrm = 0.0;
+        if (k < K)
+            for (int f = 0; f < D; ++f) {
+                const double v = (double)W[(size_t)k * D + f];
+                nrm += v * v;
+            }
+        const int st = k / kNodesPerStage, r = k % kNodesPerStage;
+        stage[(size_t)st * stage_floats + (size_t)kNodesPerStage * stride + r] = (k < K) ? (float)(-0.5 * nrm) : -INFINITY;
+        if (k < K) {
+            float up = (float)nrm;
+            if ((double)up < nrm) up = nextafterf(up, INFINITY);
+            atomicMax(&scal[0], __float_as_uint(up));
+        }
     }
 }
 
@@ -275,7 +287,7 @@ __global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2
             a.bmu[i] = r_node;
             if (a.d2) a.d2[i] = r_part;
             if (close && a.K > 1) {
-                const unsigned int pos = atomicAdd(&a.scal[1], 1u);
+                const unsigned int pos = atomicAdd(&a.scal[a.slot], 1u);
                 a.recheck[pos] = (uint32_t)i;
             } else {
                 qs += sqrt((double)r_part);
@@ -310,8 +322,11 @@ __global__ void __launch_bounds__(256) bmu_exact_kernel(const BmuArgs a)
     const float* __restrict__ wt = a.wt;
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
-    const unsigned int count = a.scal[1];
-    if (blockIdx.x == 0 && tid == 0) atomicAdd(&a.scal[2], count); // running total over the calls of an epoch
+    const unsigned int count = a.scal[a.slot];
+    if (blockIdx.x == 0 && tid == 0) {
+        atomicAdd(&a.scal[3], count);   // running total over the calls that share one weight preparation
+        a.scal[3 - a.slot] = 0u;        // the next call counts into the other slot (slots are 1 and 2)
+    }
     double qs = 0.0, qs2 = 0.0;
     for (unsigned int g0 = blockIdx.x * kExactGroup; g0 < count; g0 += gridDim.x * kExactGroup) {
         float bestd[kExactGroup];
@@ -449,7 +464,7 @@ int launch_fill_zero(som_ctx* ctx, void* p, size_t bytes)
     return check_hip(ctx, hipGetLastError(), "fill_zero launch");
 }
 
-int bmu_prepare(som_ctx* ctx, const float* W, int32_t K, int32_t D, BmuPrep* out)
+int bmu_prepare(som_ctx* ctx, const float* W, int32_t K, int32_t D, BmuPrep* out, double* qe, int32_t* small)
 {
     const int steps = steps_for(D);
     if (steps == 0) return fail(ctx, SOM_EINVAL, "D = %d is above the supported maximum of %d", D, 2 * kMaxStepsResident);
@@ -478,9 +493,10 @@ int bmu_prepare(som_ctx* ctx, const float* W, int32_t K, int32_t D, BmuPrep* out
     out->kpad = kpad;
     out->steps = steps;
     out->stride = stride;
-    if (int rc = launch_fill_zero(ctx, out->scal, 256)) return rc;
-    hipLaunchKernelGGL(bmu_prep_kernel, dim3((kpad + 127) / 128), dim3(128), 0, ctx->stream, W, K, D, kpad, stride,
-                       stage_floats_for(stride), out->stage, out->wt, out->scal);
+    out->calls = 0;
+    if (int rc = launch_fill_zero(ctx, out->scal, 32)) return rc;
+    hipLaunchKernelGGL(bmu_prep_kernel, dim3((kpad * stride + 255) / 256), dim3(256), 0, ctx->stream, W, K, D, kpad,
+                       stride, stage_floats_for(stride), out->stage, out->wt, out->scal, qe, small);
     return check_hip(ctx, hipGetLastError(), "bmu_prep launch");
 }
 
@@ -517,7 +533,7 @@ static int dispatch_bmu(som_ctx* ctx, int steps, const BmuArgs& a)
     return fail(ctx, SOM_EINVAL, "no BMU kernel for %d steps", steps);
 }
 
-int bmu_run(som_ctx* ctx, const BmuPrep& prep, BmuArgs a)
+int bmu_run(som_ctx* ctx, BmuPrep& prep, BmuArgs a)
 {
     if (a.m <= 0) return SOM_OK;
     if ((size_t)a.m > ctx->recheck_cap) {
@@ -538,8 +554,10 @@ int bmu_run(som_ctx* ctx, const BmuPrep& prep, BmuArgs a)
     a.wt = prep.wt;
     a.scal = prep.scal;
     a.recheck = ctx->recheck;
-    // the list length restarts for every call; the prepared weights may serve several calls (chunks)
-    if (int rc = launch_fill_zero(ctx, prep.scal + 1, 4)) return rc;
+    // the list length restarts for every call (chunk): calls alternate between two counters, and each call's
+    // exact pass clears the counter of the next one
+    a.slot = 1 + (prep.calls & 1);
+    ++prep.calls;
     hipEvent_t stop = nullptr;
     if (ctx->profiling) {
         if (ctx->prof_used == ctx->prof_events.size()) {

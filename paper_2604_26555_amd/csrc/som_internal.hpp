@@ -17,8 +17,9 @@ constexpr int kMaxStepsResident = 32; // BMU kernel keeps a sample's features in
 struct BmuPrep {
     float* stage = nullptr;        // [Kpad / 128][128 * (stride + 1)]: padded weight rows, then -|w|^2 / 2
     float* wt = nullptr;           // [D][Kpad] transposed weights
-    unsigned int* scal = nullptr;  // [0] = bits of max_k |w_k|^2, [1] = recheck-list length, [2] = its total since prepare
+    unsigned int* scal = nullptr;  // [0] = bits of max_k |w_k|^2, [1], [2] = recheck-list length (alternating calls), [3] = total
     int kpad = 0, steps = 0, stride = 0;
+    int calls = 0;                 // bmu_run calls served by this preparation (selects the list counter)
 };
 
 struct BmuArgs {
@@ -31,6 +32,7 @@ struct BmuArgs {
     const float* stage;      // BmuPrep::stage
     const float* wt;         // BmuPrep::wt
     unsigned int* scal;      // BmuPrep::scal
+    int32_t slot;            // which of scal[1], scal[2] this call counts into
     uint32_t* recheck;       // [m] sample positions to re-decide
     int32_t* bmu;            // [m], always written
     float* d2;               // may be null
@@ -84,8 +86,9 @@ int check_hip(som_ctx* ctx, hipError_t e, const char* what);
 
 // kernels' host launchers (each returns SOM_OK or an error code after recording detail in ctx)
 int launch_fill_zero(som_ctx* ctx, void* p, size_t bytes);
-int bmu_prepare(som_ctx* ctx, const float* W, int32_t K, int32_t D, BmuPrep* out);
-int bmu_run(som_ctx* ctx, const BmuPrep& prep, BmuArgs args);
+// qe (double[2]) and small (int32[4]) are zeroed by the preparation kernel when given
+int bmu_prepare(som_ctx* ctx, const float* W, int32_t K, int32_t D, BmuPrep* out, double* qe, int32_t* small);
+int bmu_run(som_ctx* ctx, BmuPrep& prep, BmuArgs args);
 int accumulate_run(som_ctx* ctx, const float* X, int32_t D, int64_t ldx, const uint32_t* idx, int64_t m,
                    const int32_t* bmu, int32_t K, double* S, unsigned long long* n, bool zero_first);
 // 1 = shape not served by the MFMA path (caller falls back), otherwise SOM_OK or an error code

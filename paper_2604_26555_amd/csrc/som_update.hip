@@ -4,7 +4,7 @@
 //     w_j <- Num_j / Den_j  where Den_j >= eps_h, otherwise w_j stays.
 // Three small launches, all latency-bound at K ~ 1000, so each is shaped for many independent workgroups:
 //   1. influence_kernel    h[k][j] for all K x K pairs, one exp per thread (K^2 threads);
-//   2. contract_kernel     partial Num / Den over a quarter of the k range per workgroup (split-k keeps four
+//   2. contract_kernel     partial Num / Den over an eighth of the k range per workgroup (split-k keeps several
 //                          workgroups per compute unit in flight; partials are stored, not atomically added);
 //   3. finish_kernel       adds the partials in a fixed order, applies the threshold, writes W, counts.
 // The contraction is 2 K^2 (D + 1) float64 flops (0.1 GFLOP at K = 1024, D = 50): microseconds on the vector
@@ -17,7 +17,7 @@ namespace som {
 
 constexpr int kTJ = 4;       // updated nodes per workgroup (one wavefront each)
 constexpr int kKC = 32;      // contributing nodes staged per step (two LDS buffers of kKC x 64 doubles)
-constexpr int kSplitK = 4;   // workgroups sharing one block of updated nodes
+constexpr int kSplitK = 8;   // workgroups sharing one block of updated nodes
 
 __global__ void __launch_bounds__(256) influence_kernel(const float* __restrict__ G, int K, double inv2s2,
                                                         double* __restrict__ H)
