@@ -39,25 +39,30 @@ constexpr int stage_floats_for(int stride)
 }
 
 // ---------------------------------------------------------------------------------------------------------
-// Weight preparation: padded rows + half squared norms per 128-node stage, transposed copy, largest squared
-// norm (scal[0], cleared beforehand), and the zeroing of the result words the later kernels count into.
-// One thread per element of the padded K x stride matrix (coalesced reads of W); the first kpad threads also
-// compute their node's norm in float64.
+// Weight preparation: padded rows + half squared norms per (128-node stage, feature chunk), transposed copy,
+// largest squared norm (scal[0], cleared beforehand), and the zeroing of the result words the later kernels count
+// into.  A chunk holds stride - 1 features and one zero column (odd row stride); maps with D <= 64 have a single
+// chunk.  One thread per element of the padded matrix (coalesced reads of W); the first kpad threads also compute
+// their node's norm in float64.
 // ---------------------------------------------------------------------------------------------------------
 __global__ void __launch_bounds__(256) bmu_prep_kernel(const float* __restrict__ W, int K, int D, int kpad, int stride,
-                                                       int stage_floats, float* __restrict__ stage,
+                                                       int nch, int stage_floats, float* __restrict__ stage,
                                                        float* __restrict__ wt, unsigned int* __restrict__ scal,
                                                        double* __restrict__ qe, int32_t* __restrict__ small)
 {
     const int e = blockIdx.x * 256 + threadIdx.x;
+    const int cols = nch * stride;
     if (e < 2 && qe) qe[e] = 0.0;
     if (e < 4 && small) small[e] = 0;
-    if (e < kpad * stride) {
-        const int k = e / stride, f = e - k * stride;
-        const float v = (k < K && f < D) ? W[(size_t)k * D + f] : 0.0f;
+    if (e < kpad * cols) {
+        const int k = e / cols, c = e - k * cols;
+        const int ch = c / stride, fl = c - ch * stride;
+        const int f = ch * (stride - 1) + fl;
+        const bool real = k < K && fl < stride - 1 && f < D;
+        const float v = real ? W[(size_t)k * D + f] : 0.0f;
         const int st = k / kNodesPerStage, r = k % kNodesPerStage;
-        stage[(size_t)st * stage_floats + (size_t)r * stride + f] = v;
-        if (f < D) wt[(size_t)f * kpad + k] = v;
+        stage[((size_t)st * nch + ch) * stage_floats + (size_t)r * stride + fl] = v;
+        if (fl < stride - 1 && f < D) wt[(size_t)f * kpad + k] = v;
     }
     if (e < kpad) {
         const int k = e;
@@ -68,7 +73,9 @@ __global__ void __launch_bounds__(256) bmu_prep_kernel(const float* __restrict__
                 nrm += v * v;
             }
         const int st = k / kNodesPerStage, r = k % kNodesPerStage;
-        stage[(size_t)st * stage_floats + (size_t)kNodesPerStage * stride + r] = (k < K) ? (float)(-0.5 * nrm) : -INFINITY;
+        const float nh = (k < K) ? (float)(-0.5 * nrm) : -INFINITY;
+        for (int ch = 0; ch < nch; ++ch)
+            stage[((size_t)st * nch + ch) * stage_floats + (size_t)kNodesPerStage * stride + r] = nh;
         if (k < K) {
             float up = (float)nrm;
             if ((double)up < nrm) up = nextafterf(up, INFINITY);
@@ -306,6 +313,152 @@ __global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2
 }
 
 // ---------------------------------------------------------------------------------------------------------
+// the same search for D > 64: features go through in chunks of 64.  A wavefront owns one block of 32 samples;
+// the accumulators of a stage's four node blocks stay live across the chunks, the samples' features of the
+// current chunk are re-read from memory (they stay cache-resident: one workgroup touches 128 rows).
+// ---------------------------------------------------------------------------------------------------------
+__global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 2))) bmu_wide_kernel(const BmuArgs a)
+{
+    constexpr int STEPS = 32, STRIDE = 2 * STEPS + 1, NBS = kNodesPerStage / 32;
+    constexpr int STAGE_FLOATS = stage_floats_for(STRIDE);
+    constexpr int STAGE_F4 = STAGE_FLOATS / 4;
+    constexpr int PRE = STAGE_F4 / kThreads;
+    static_assert(PRE == 9, "stage copy of the wide kernel holds nine float4 per thread");
+    extern __shared__ float4 lds4[];
+    float* lds = reinterpret_cast<float*>(lds4);
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int j = lane & 31, g = lane >> 5;
+    const int64_t i = ((int64_t)blockIdx.x * kWavesPerGroup + wave) * 32 + j;
+    const bool valid = i < a.m;
+    const int64_t ii = valid ? i : a.m - 1;
+    const int64_t row = a.idx ? (int64_t)a.idx[ii] : ii;
+    const float* xr = a.X + row * a.ldx;
+
+    float best = -INFINITY, second = -INFINITY;
+    int rsel = 0, tsel = 0;
+    const int nstages = a.kpad / kNodesPerStage;
+    const int nch = (a.D + 63) / 64;
+    const int nq = nstages * nch;
+    const float4* src4 = reinterpret_cast<const float4*>(a.stage);
+    {
+        float4 first[PRE];
+#pragma unroll
+        for (int p = 0; p < PRE; ++p) first[p] = src4[tid + p * kThreads];
+#pragma unroll
+        for (int p = 0; p < PRE; ++p) lds4[tid + p * kThreads] = first[p];
+    }
+    __syncthreads();
+
+    floatx16 acc[NBS];
+    int st = 0, ch = 0;
+    for (int q = 0; q < nq; ++q) {
+        const int buf = q & 1;
+        float4 pre0, pre1, pre2, pre3, pre4, pre5, pre6, pre7, pre8;
+        {
+            const int nxt = (q + 1 < nq) ? q + 1 : q;
+            const float4* s4 = src4 + (size_t)nxt * STAGE_F4 + tid;
+            pre0 = s4[0 * kThreads]; pre1 = s4[1 * kThreads]; pre2 = s4[2 * kThreads];
+            pre3 = s4[3 * kThreads]; pre4 = s4[4 * kThreads]; pre5 = s4[5 * kThreads];
+            pre6 = s4[6 * kThreads]; pre7 = s4[7 * kThreads]; pre8 = s4[8 * kThreads];
+        }
+        float x[STEPS];
+#pragma unroll
+        for (int s = 0; s < STEPS; ++s) {
+            const int f = 64 * ch + 2 * s + g;
+            x[s] = (f < a.D) ? xr[f] : 0.0f;
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        const float* wbuf = lds + buf * STAGE_FLOATS;
+        const float* nbuf = wbuf + kNodesPerStage * STRIDE;
+#pragma unroll
+        for (int nb = 0; nb < NBS; ++nb) {
+            if (ch == 0) {
+                const float4* nh = reinterpret_cast<const float4*>(nbuf + nb * 32 + 4 * g);
+#pragma unroll
+                for (int t = 0; t < 4; ++t) {
+                    const float4 v = nh[2 * t];
+                    acc[nb][4 * t + 0] = v.x;
+                    acc[nb][4 * t + 1] = v.y;
+                    acc[nb][4 * t + 2] = v.z;
+                    acc[nb][4 * t + 3] = v.w;
+                }
+            }
+            const float* wrow = wbuf + (nb * 32 + j) * STRIDE + g;
+#pragma unroll
+            for (int s = 0; s < STEPS; ++s)
+                acc[nb] = __builtin_amdgcn_mfma_f32_32x32x2f32(wrow[2 * s], x[s], acc[nb], 0, 0, 0);
+            if (ch == nch - 1) {
+                const int tile = st * NBS + nb;
+                const float before = best;
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const float v = acc[nb][r];
+                    rsel = (v > best) ? r : rsel;
+                    second = __builtin_amdgcn_fmed3f(best, second, v);
+                    best = vmax(best, v);
+                }
+                tsel = (best > before) ? tile : tsel;
+            }
+        }
+        {
+            float4* d4 = lds4 + (buf ^ 1) * STAGE_F4 + tid;
+            d4[0 * kThreads] = pre0; d4[1 * kThreads] = pre1; d4[2 * kThreads] = pre2;
+            d4[3 * kThreads] = pre3; d4[4 * kThreads] = pre4; d4[5 * kThreads] = pre5;
+            d4[6 * kThreads] = pre6; d4[7 * kThreads] = pre7; d4[8 * kThreads] = pre8;
+        }
+        __syncthreads();
+        if (++ch == nch) {
+            ch = 0;
+            ++st;
+        }
+    }
+
+    // ---- join the two half-wavefronts; squared norm and exact winner distance from memory, half the features each
+    int node = tsel * 32 + 8 * (rsel >> 2) + 4 * g + (rsel & 3);
+    const float ob = __shfl_xor(best, 32), os = __shfl_xor(second, 32);
+    const int on = __shfl_xor(node, 32);
+    const float sec = fmaxf(fmaxf(second, os), fminf(best, ob));
+    const bool other = (ob > best) || (ob == best && on < node);
+    const float bst = other ? ob : best;
+    node = other ? on : node;
+    node = node < a.K ? node : a.K - 1;
+    float xn = 0.f, part = 0.f;
+    const float* wr = a.W + (size_t)node * a.D;
+    for (int f = g; f < a.D; f += 2) {
+        const float xv = xr[f];
+        const float df = xv - wr[f];
+        xn = fmaf(xv, xv, xn);
+        part = fmaf(df, df, part);
+    }
+    xn += __shfl_xor(xn, 32);
+    part += __shfl_xor(part, 32);
+    double qs = 0.0, qs2 = 0.0;
+    if (valid && g == 0) {
+        const float wmax2 = __uint_as_float(a.scal[0]);
+        const float rel = (float)(2 * STEPS * nch + 8) * 5.9604645e-08f;    // (roundings per score + slack) * 2^-24
+        const float bound = (0.5f * xn + wmax2) * rel;
+        const bool close = !((bst - sec) > bound);
+        a.bmu[i] = node;
+        if (a.d2) a.d2[i] = part;
+        if (close && a.K > 1) {
+            const unsigned int pos = atomicAdd(&a.scal[a.slot], 1u);
+            a.recheck[pos] = (uint32_t)i;
+        } else {
+            qs = sqrt((double)part);
+            qs2 = (double)part;
+        }
+    }
+    if (a.qe) {
+        qs = wave_sum(qs);
+        qs2 = wave_sum(qs2);
+        if (lane == 0 && (qs != 0.0 || qs2 != 0.0)) {
+            unsafeAtomicAdd(&a.qe[0], qs);
+            unsafeAtomicAdd(&a.qe[1], qs2);
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------------------
 // exact re-decision of the listed samples by direct differences, sum_d (x_d - w_kd)^2 for every node.
 // A workgroup takes kExactGroup samples at a time; thread t owns nodes t, t + 256, ... so one coalesced read of
 // the transposed weights serves all samples of the group, and the samples' features are broadcast from LDS.
@@ -466,11 +619,11 @@ int launch_fill_zero(som_ctx* ctx, void* p, size_t bytes)
 
 int bmu_prepare(som_ctx* ctx, const float* W, int32_t K, int32_t D, BmuPrep* out, double* qe, int32_t* small)
 {
-    const int steps = steps_for(D);
-    if (steps == 0) return fail(ctx, SOM_EINVAL, "D = %d is above the supported maximum of %d", D, 2 * kMaxStepsResident);
+    const int steps = (D <= 2 * kMaxStepsResident) ? steps_for(D) : kMaxStepsResident;
+    const int nch = (D <= 2 * kMaxStepsResident) ? 1 : (D + 2 * kMaxStepsResident - 1) / (2 * kMaxStepsResident);
     const int stride = 2 * steps + 1;
     const int kpad = ((K + kNodesPerStage - 1) / kNodesPerStage) * kNodesPerStage;
-    const size_t stage_bytes = (size_t)(kpad / kNodesPerStage) * stage_floats_for(stride) * sizeof(float);
+    const size_t stage_bytes = (size_t)(kpad / kNodesPerStage) * nch * stage_floats_for(stride) * sizeof(float);
     const size_t wt_bytes = (size_t)D * kpad * sizeof(float);
     const size_t need = stage_bytes + wt_bytes + 256;
     if (need > ctx->prep_bytes) {
@@ -493,11 +646,31 @@ int bmu_prepare(som_ctx* ctx, const float* W, int32_t K, int32_t D, BmuPrep* out
     out->kpad = kpad;
     out->steps = steps;
     out->stride = stride;
+    out->nch = nch;
     out->calls = 0;
     if (int rc = launch_fill_zero(ctx, out->scal, 32)) return rc;
-    hipLaunchKernelGGL(bmu_prep_kernel, dim3((kpad * stride + 255) / 256), dim3(256), 0, ctx->stream, W, K, D, kpad,
-                       stride, stage_floats_for(stride), out->stage, out->wt, out->scal, qe, small);
+    const long long elems = (long long)kpad * nch * stride;
+    hipLaunchKernelGGL(bmu_prep_kernel, dim3((unsigned)((elems + 255) / 256)), dim3(256), 0, ctx->stream, W, K, D, kpad,
+                       stride, nch, stage_floats_for(stride), out->stage, out->wt, out->scal, qe, small);
     return check_hip(ctx, hipGetLastError(), "bmu_prep launch");
+}
+
+static int launch_bmu_wide(som_ctx* ctx, const BmuArgs& a)
+{
+    constexpr size_t lds_bytes = 2 * (size_t)stage_floats_for(2 * kMaxStepsResident + 1) * sizeof(float);
+    static bool attr_set = false;
+    if (!attr_set) {
+        if (int rc = check_hip(ctx,
+                               hipFuncSetAttribute(reinterpret_cast<const void*>(bmu_wide_kernel),
+                                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes),
+                               "raising the dynamic LDS limit"))
+            return rc;
+        attr_set = true;
+    }
+    const int64_t per_group = (int64_t)kWavesPerGroup * 32;
+    const int64_t groups = (a.m + per_group - 1) / per_group;
+    hipLaunchKernelGGL(bmu_wide_kernel, dim3((unsigned)groups), dim3(kThreads), lds_bytes, ctx->stream, a);
+    return check_hip(ctx, hipGetLastError(), "bmu (wide) kernel launch");
 }
 
 template <int STEPS, int MS>
@@ -570,7 +743,7 @@ int bmu_run(som_ctx* ctx, BmuPrep& prep, BmuArgs a)
         stop = ctx->prof_events[ctx->prof_used].second;
         ++ctx->prof_used;
     }
-    int rc = dispatch_bmu(ctx, prep.steps, a);
+    int rc = prep.nch > 1 ? launch_bmu_wide(ctx, a) : dispatch_bmu(ctx, prep.steps, a);
     if (stop) (void)hipEventRecord(stop, ctx->stream);
     if (rc) return rc;
     if (a.K > 1) {

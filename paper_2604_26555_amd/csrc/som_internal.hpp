@@ -15,10 +15,11 @@ constexpr int kNodesPerStage = 128;   // nodes of W staged through LDS at a time
 constexpr int kMaxStepsResident = 32; // BMU kernel keeps a sample's features in registers up to D = 64
 
 struct BmuPrep {
-    float* stage = nullptr;        // [Kpad / 128][128 * (stride + 1)]: padded weight rows, then -|w|^2 / 2
+    float* stage = nullptr;        // [Kpad / 128][nch] blobs: 128 padded weight rows of a chunk, then -|w|^2 / 2
     float* wt = nullptr;           // [D][Kpad] transposed weights
     unsigned int* scal = nullptr;  // [0] = bits of max_k |w_k|^2, [1], [2] = recheck-list length (alternating calls), [3] = total
     int kpad = 0, steps = 0, stride = 0;
+    int nch = 1;                   // feature chunks of 2 * steps features (1 unless D > 64)
     int calls = 0;                 // bmu_run calls served by this preparation (selects the list counter)
 };
 

@@ -65,6 +65,7 @@ def check_bmu(b_gpu, d2_gpu, X, W, idx=None):
 @pytest.mark.parametrize("m,K,D", [
     (1, 1, 1), (5, 3, 2), (257, 5, 3), (1000, 100, 8), (10_000, 100, 8), (777, 130, 17), (3000, 128, 16),
     (4099, 1024, 50), (600, 300, 64), (2048, 257, 33),
+    (1000, 200, 65), (3000, 1024, 130), (500, 64, 300), (300, 130, 1000),      # feature-chunked kernel (D > 64)
 ])
 def test_bmu_matches_oracle(som, m, K, D):
     X, W = problem(100 + m + K + D, m, K, D)
@@ -108,7 +109,8 @@ def test_bmu_large_norm_small_gap(som):
 
 
 # ------------------------------------------------------------------------------------------- stage 2
-@pytest.mark.parametrize("m,K,D", [(1, 1, 1), (1000, 100, 8), (50_000, 1024, 50), (30_001, 37, 64), (4096, 2000, 5)])
+@pytest.mark.parametrize("m,K,D", [(1, 1, 1), (1000, 100, 8), (50_000, 1024, 50), (30_001, 37, 64), (4096, 2000, 5),
+                                   (20_000, 500, 63), (9000, 100, 200), (5000, 3000, 40), (40_000, 2048, 31)])
 def test_accumulate_matches_oracle(som, m, K, D):
     X, W = problem(200 + m + K, m, min(K, m), D)
     b = np.random.default_rng(m).integers(0, K, size=m).astype(np.int32)
@@ -234,6 +236,12 @@ def test_epochs_mst_and_rng_teacher_forced(som):
     wl = make_workload("cfg3", n=60_000, k=200)
     m = oracle.sampling_budget(wl.n, rho=wl.rho)
     run_teacher_forced(som, wl, wl.n, [0, 29], idx_fn=lambda e: draw_subset(wl.seed, e, wl.n, m))
+
+
+def test_epochs_wide_features_teacher_forced(som):
+    # D > 64: feature-chunked BMU kernel, LDS-atomic accumulation, two feature slabs in the update
+    wl = make_workload("cfg1", n=6000, d=100, k=64, lattice=(8, 8), mixture=dict(n_comp=6, std=(0.2, 3.0)))
+    run_teacher_forced(som, wl, wl.n, [0, 5, 19])
 
 
 def test_epochs_cfg0_free_running(som):
