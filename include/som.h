@@ -107,6 +107,17 @@ int som_neighborhood_update(som_ctx* ctx, const double* S, const uint64_t* n, co
                             int32_t K, int32_t D, double sigma, int kernel, double eps_h,
                             float* W, int32_t* n_guarded);
 
+/*
+ * General update rule of the paragraph after Eq. 4: learning rate eta (the eta_t inside U_j of Eq. 3) and
+ * optional momentum.  With   u_j = eta (Num_j / Den_j - w_j)   (= U_j / H_j; 0 where Den_j < eps_h)   every
+ * later update on this context (som_neighborhood_update, som_epoch, som_epoch_host) applies
+ *     delta_j = u_j + mu * velocity_j,    w_j <- w_j + delta_j,    velocity_j <- delta_j.
+ * velocity [device] float[K*D], caller-owned, read and written by every update; required when mu != 0, may be
+ * NULL otherwise.  eta = 1, mu = 0 (the default of a new context) is the plain rule w_j <- Num_j / Den_j.
+ * eta must be in (0, 1], mu in [0, 1).
+ */
+int som_set_update_rule(som_ctx* ctx, double eta, double mu, float* velocity);
+
 /* [host] statistics of one epoch, filled after the epoch's work has finished. */
 typedef struct {
     double sum_dist;   /* sum over presented samples of the distance to the BMU (pre-update weights) */

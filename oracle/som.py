@@ -195,6 +195,28 @@ def neighborhood_update(S, n, G, sigma, W, eps_h: float = DEFAULT_EPS_H):
     return Wn, guarded, den
 
 
+def neighborhood_update_momentum(S, n, G, sigma, W, V, eta: float = 1.0, mu: float = 0.0,
+                                 eps_h: float = DEFAULT_EPS_H):
+    """General update of the paragraph after Eq. 4: learning rate inside U, optional momentum on the normalised update.
+
+    u_j = eta * (Num_j / Den_j - w_j)  (= U_j / H_j of Eq. 3), or 0 where the denominator is below the threshold;
+    delta_j = u_j + mu * V_j;  w_j <- w_j + delta_j;  the new velocity is delta_j.  Returns (W_new, V_new, guarded).
+    """
+    S = np.asarray(S, dtype=np.float64)
+    nn = np.asarray(n, dtype=np.float64)
+    W0 = np.asarray(W, dtype=np.float64)
+    V0 = np.zeros_like(W0) if V is None else np.asarray(V, dtype=np.float64)
+    h = influence(G, sigma)
+    num = h.T @ S
+    den = h.T @ nn
+    guarded = ~(den >= eps_h)
+    u = np.zeros_like(W0)
+    ok = ~guarded
+    u[ok] = eta * (num[ok] / den[ok, None] - W0[ok])
+    delta = u + mu * V0
+    return W0 + delta, delta, guarded
+
+
 def bmu_gram(X, W, block: int = 65536):
     """BMU through |x|^2 - 2 x.w + |w|^2 with a float64 BLAS product; checked against ``bmu`` in the tests.
 

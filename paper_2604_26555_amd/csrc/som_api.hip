@@ -170,6 +170,19 @@ int som_sync(som_ctx* ctx)
     return check_hip(ctx, hipStreamSynchronize(ctx->stream), "stream synchronize");
 }
 
+int som_set_update_rule(som_ctx* ctx, double eta, double mu, float* velocity)
+{
+    if (!ctx) return SOM_EINVAL;
+    if (!(eta > 0.0 && eta <= 1.0)) return fail(ctx, SOM_EINVAL, "eta must be in (0, 1]");
+    if (!(mu >= 0.0 && mu < 1.0)) return fail(ctx, SOM_EINVAL, "mu must be in [0, 1)");
+    if (mu != 0.0 && !velocity) return fail(ctx, SOM_EINVAL, "momentum needs a velocity buffer");
+    if (velocity && !device_readable(velocity)) return fail(ctx, SOM_EINVAL, "velocity must be device-accessible memory");
+    ctx->eta = eta;
+    ctx->mu = mu;
+    ctx->velocity = velocity;
+    return SOM_OK;
+}
+
 int som_profile(som_ctx* ctx, int enable)
 {
     if (!ctx) return SOM_EINVAL;

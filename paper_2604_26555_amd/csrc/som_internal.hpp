@@ -47,6 +47,8 @@ struct som_ctx {
     hipStream_t stream = nullptr;
     hipStream_t copy_stream = nullptr;
     char err[512] = {0};
+    double eta = 1.0, mu = 0.0;    // update rule (som_set_update_rule)
+    float* velocity = nullptr;
 
     // BMU workspaces (grown on demand)
     void* prep_blob = nullptr;

@@ -99,9 +99,12 @@ __global__ void __launch_bounds__(kTJ * 64) contract_kernel(const double* __rest
     }
 }
 
+// plain = true: w <- Num / Den (eta = 1, no momentum);  otherwise delta = eta (Num / Den - w) + mu v, w += delta
 __global__ void __launch_bounds__(256) finish_kernel(const double* __restrict__ part,
                                                      const unsigned long long* __restrict__ n, int K, int D,
-                                                     double eps_h, float* __restrict__ W, int32_t* __restrict__ small)
+                                                     double eps_h, bool plain, double eta, double mu,
+                                                     float* __restrict__ V, float* __restrict__ W,
+                                                     int32_t* __restrict__ small)
 {
     const int e = blockIdx.x * 256 + threadIdx.x;
     if (e >= K * D) return;
@@ -115,7 +118,14 @@ __global__ void __launch_bounds__(256) finish_kernel(const double* __restrict__ 
         den += row[z * stride + D];
     }
     const bool ok = den >= eps_h;
-    if (ok) W[e] = (float)(num / den);
+    if (plain) {
+        if (ok) W[e] = (float)(num / den);
+    } else {
+        const double w = (double)W[e];
+        const double delta = (ok ? eta * (num / den - w) : 0.0) + (V ? mu * (double)V[e] : 0.0);
+        W[e] = (float)(w + delta);
+        if (V) V[e] = (float)delta;
+    }
     if (d == 0 && small) {
         if (!ok) atomicAdd(&small[0], 1);
         if (n[j] == 0ull) atomicAdd(&small[1], 1);
@@ -148,7 +158,9 @@ int update_run(som_ctx* ctx, const double* S, const unsigned long long* n, const
     dim3 grid((K + kTJ - 1) / kTJ, (D + 63) / 64, kSplitK);
     hipLaunchKernelGGL(contract_kernel, grid, dim3(kTJ * 64), 0, ctx->stream, H, S, n, K, D, part);
     if (int rc = check_hip(ctx, hipGetLastError(), "contraction kernel launch")) return rc;
-    hipLaunchKernelGGL(finish_kernel, dim3((K * D + 255) / 256), dim3(256), 0, ctx->stream, part, n, K, D, eps_h, W, small);
+    const bool plain = ctx->eta == 1.0 && ctx->mu == 0.0;
+    hipLaunchKernelGGL(finish_kernel, dim3((K * D + 255) / 256), dim3(256), 0, ctx->stream, part, n, K, D, eps_h, plain,
+                       ctx->eta, ctx->mu, ctx->velocity, W, small);
     return check_hip(ctx, hipGetLastError(), "update finish launch");
 }
 

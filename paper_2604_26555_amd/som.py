@@ -23,6 +23,7 @@ SOM_KERNEL_GAUSSIAN = 0
 EXPORTS = [
     "som_create", "som_destroy", "som_strerror", "som_last_error", "som_sync", "som_bmu", "som_accumulate",
     "som_neighborhood_update", "som_epoch", "som_epoch_host", "som_profile", "som_profile_read",
+    "som_set_update_rule",
 ]
 
 
@@ -62,6 +63,8 @@ def load_library(path: str = LIB_PATH) -> C.CDLL:
     lib.som_last_error.restype = C.c_char_p
     lib.som_sync.argtypes = [vp]
     lib.som_sync.restype = C.c_int
+    lib.som_set_update_rule.argtypes = [vp, f64, f64, vp]
+    lib.som_set_update_rule.restype = C.c_int
     lib.som_profile.argtypes = [vp, C.c_int]
     lib.som_profile.restype = C.c_int
     lib.som_profile_read.argtypes = [vp, C.POINTER(C.c_float), i32, C.POINTER(i32)]
@@ -171,6 +174,15 @@ class Som:
 
     def som_sync(self):
         self._check(self.lib.som_sync(self._h), "som_sync")
+
+    def som_set_update_rule(self, eta: float = 1.0, mu: float = 0.0, velocity=None):
+        """Learning rate and momentum of every later update on this context; velocity is a K x D float32 GPU tensor."""
+        if velocity is not None and not velocity.is_contiguous():
+            raise ValueError("velocity must be contiguous")
+        self._velocity = velocity                       # keep the caller's buffer alive while the library uses it
+        self._check(self.lib.som_set_update_rule(self._h, float(eta), float(mu),
+                                                 _ptr(velocity, torch.float32, "velocity", self.device)),
+                    "som_set_update_rule")
 
     def som_profile(self, enable: bool):
         self._check(self.lib.som_profile(self._h, 1 if enable else 0), "som_profile")

@@ -174,6 +174,37 @@ def test_update_matches_oracle(som, K, D, sigma, kind):
     assert (Wd.cpu().numpy()[guarded & (den < oracle.DEFAULT_EPS_H / 4)] == W[guarded & (den < oracle.DEFAULT_EPS_H / 4)]).all()
 
 
+@pytest.mark.parametrize("eta,mu", [(0.5, 0.0), (1.0, 0.3), (0.25, 0.9)])
+def test_update_with_learning_rate_and_momentum(som, eta, mu):
+    K, D = 100, 8
+    rng = np.random.default_rng(int(eta * 100 + mu * 10))
+    W = rng.normal(size=(K, D)).astype(np.float32)
+    V = (rng.normal(size=(K, D)) * 0.1).astype(np.float32)
+    n = rng.integers(0, 30, size=K).astype(np.int64)
+    n[rng.random(K) < 0.4] = 0
+    S = rng.normal(size=(K, D)) * n[:, None]
+    G = oracle.rect_lattice_distances(10, 10).astype(np.float32)
+    Wd, Vd = dev(W), dev(V)
+    try:
+        som.som_set_update_rule(eta, mu, Vd)
+        W_or, V_or = W.astype(np.float64), V.astype(np.float64)
+        for step in range(2):                     # two steps: the second one uses the velocity the first one wrote
+            som.som_neighborhood_update(dev(S), dev(n), dev(G), 0.4, Wd)
+            W32, V32 = W_or.astype(np.float32), V_or.astype(np.float32)
+            W_or, V_or, _ = oracle.neighborhood_update_momentum(S, n, G.astype(np.float64), 0.4, W32, V32, eta, mu)
+            weights_close(Wd.cpu().numpy(), W_or)
+            np.testing.assert_allclose(Vd.cpu().numpy(), V_or, rtol=1e-4, atol=1e-6)
+            W_or, V_or = Wd.cpu().numpy().astype(np.float64), Vd.cpu().numpy().astype(np.float64)
+    finally:
+        som.som_set_update_rule(1.0, 0.0, None)
+    from paper_2604_26555_amd import SomError
+    for bad in ((0.0, 0.0), (1.5, 0.0), (1.0, 1.0), (1.0, -0.1)):
+        with pytest.raises(SomError):
+            som.som_set_update_rule(bad[0], bad[1], Vd)
+    with pytest.raises(SomError):
+        som.som_set_update_rule(1.0, 0.5, None)
+
+
 def test_update_with_unreachable_nodes(som):
     K, D = 6, 3
     G = oracle.hop_distances(K, np.array([[0, 1], [1, 2], [3, 4]])).astype(np.float32)   # node 5 isolated

@@ -268,3 +268,40 @@ def test_training_reduces_quantization_error_on_clustered_data():
         W = oracle.epoch_grouped(X, None, W, G, sigma)["W"]
     qe1 = oracle.quantization_error(oracle.bmu(X, W)[1])
     assert qe1 < 0.9 * qe0
+
+
+# ---------------------------------------------------------------- learning rate and momentum (paragraph after Eq. 4)
+def test_general_update_reduces_to_the_plain_one():
+    X, W, G = _random_problem(30, m=200, K=8, D=3)
+    b = oracle.bmu(X, W)[0]
+    S, n = oracle.accumulate(X, None, b, 8)
+    plain, guarded, _ = oracle.neighborhood_update(S, n, G, 0.9, W)
+    Wn, Vn, g2 = oracle.neighborhood_update_momentum(S, n, G, 0.9, W, None, eta=1.0, mu=0.0)
+    np.testing.assert_allclose(Wn, plain, rtol=1e-13, atol=1e-14)
+    np.testing.assert_allclose(Vn, plain - W.astype(np.float64), rtol=1e-12, atol=1e-14)
+    assert (g2 == guarded).all()
+
+
+def test_learning_rate_is_the_eta_of_eq3():
+    X, W, G = _random_problem(31, m=30, K=5, D=2)
+    b = oracle.bmu(X, W)[0]
+    S, n = oracle.accumulate(X, None, b, 5)
+    for eta in (0.25, 0.7):
+        Wn, _, _ = oracle.neighborhood_update_momentum(S, n, G, 1.2, W, None, eta=eta)
+        np.testing.assert_allclose(Wn, oracle.displacement_form_update(X, b, W, G, 1.2, eta=eta), rtol=1e-12, atol=1e-13)
+
+
+def test_momentum_recurrence_single_node():
+    # K = 1: w' = w + eta (mean - w) + mu v, v' = w' - w; two steps by hand
+    X = np.array([[2.0], [4.0]], dtype=np.float32)
+    G = np.zeros((1, 1))
+    S, n = np.array([[6.0]]), np.array([2])
+    W1, V1, _ = oracle.neighborhood_update_momentum(S, n, G, 1.0, np.array([[1.0]]), np.array([[0.5]]), eta=0.5, mu=0.2)
+    assert abs(W1[0, 0] - (1.0 + 0.5 * (3.0 - 1.0) + 0.2 * 0.5)) < 1e-15 and abs(V1[0, 0] - 1.1) < 1e-15
+    W2, V2, _ = oracle.neighborhood_update_momentum(S, n, G, 1.0, W1, V1, eta=0.5, mu=0.2)
+    assert abs(W2[0, 0] - (2.1 + 0.5 * (3.0 - 2.1) + 0.2 * 1.1)) < 1e-15
+    # a node below the denominator threshold only coasts on its velocity
+    G2 = np.array([[0.0, np.inf], [np.inf, 0.0]])
+    Wn, Vn, guarded = oracle.neighborhood_update_momentum(np.array([[6.0], [0.0]]), np.array([2, 0]), G2, 1.0,
+                                                          np.array([[1.0], [9.0]]), np.array([[0.0], [1.0]]), eta=1.0, mu=0.5)
+    assert guarded.tolist() == [False, True] and Wn[:, 0].tolist() == [3.0, 9.5] and Vn[:, 0].tolist() == [2.0, 0.5]
