@@ -50,6 +50,11 @@ enum {
 
 enum { SOM_KERNEL_GAUSSIAN = 0 /* h(g) = exp(-g^2 / (2 sigma^2)) */ };
 
+enum {
+    SOM_TOPOLOGY_MST = 1, /* minimum spanning tree over the node weights (Algorithm 1) */
+    SOM_TOPOLOGY_RNG = 2  /* relative neighbourhood graph (Algorithm 2) */
+};
+
 /* Create a context on HIP device `device`.  `hip_stream` is the hipStream_t the library enqueues all compute on
  * (e.g. the caller's torch stream); NULL is HIP's default stream.  The stream stays the caller's.  The library
  * creates one further stream of its own for host-to-device copies.  *out receives the context. */
@@ -117,6 +122,22 @@ int som_neighborhood_update(som_ctx* ctx, const double* S, const uint64_t* n, co
  * eta must be in (0, 1], mu in [0, 1).
  */
 int som_set_update_rule(som_ctx* ctx, double eta, double mu, float* velocity);
+
+/*
+ * Rebuild a data-driven neighbourhood graph from the current weights and return its hop counts
+ * (Sections 3.2.1-3.2.2, Algorithms 1 and 2): pairwise squared Euclidean distances between the node weight
+ * vectors, then either the minimum spanning tree of the complete graph under those distances, or the relative
+ * neighbourhood graph (p ~ q unless a third node r has max(d(p,r), d(q,r)) < d(p,q), strict), then the number
+ * of edges on the shortest path between every two nodes.
+ *   W [device] K x D float (read only)
+ *   kind  SOM_TOPOLOGY_MST or SOM_TOPOLOGY_RNG
+ *   G [device] float[K*K], caller-owned, OVERWRITTEN: G[p*K+q] = hop count, 0 on the diagonal, +inf between
+ *     nodes in different components (possible only when distances are non-finite)
+ * Distances and every comparison that decides an edge are float64 on direct differences; when several edges
+ * have exactly equal length the spanning tree is one of the minimal ones (lowest node index joins first).
+ * Asynchronous on the context's stream; K is limited to 12000 by the spanning-tree kernel's LDS use.
+ */
+int som_topology(som_ctx* ctx, const float* W, int32_t K, int32_t D, int kind, float* G);
 
 /* [host] statistics of one epoch, filled after the epoch's work has finished. */
 typedef struct {

@@ -152,6 +152,7 @@ void som_destroy(som_ctx* c)
     if (c->bmu_ws) (void)hipFree(c->bmu_ws);
     if (c->acc_blob) (void)hipFree(c->acc_blob);
     if (c->upd_blob) (void)hipFree(c->upd_blob);
+    if (c->topo_blob) (void)hipFree(c->topo_blob);
     if (c->S) (void)hipFree(c->S);
     if (c->n) (void)hipFree(c->n);
     if (c->qe) (void)hipFree(c->qe);

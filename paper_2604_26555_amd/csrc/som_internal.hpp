@@ -61,6 +61,8 @@ struct som_ctx {
     size_t acc_bytes = 0;
     void* upd_blob = nullptr;      // influence matrix + split-k partials of the update
     size_t upd_bytes = 0;
+    void* topo_blob = nullptr;     // node distances, adjacency matrix and lists of the topology rebuild
+    size_t topo_bytes = 0;
     // epoch-internal accumulators
     double* S = nullptr;
     size_t S_elems = 0;

@@ -1,0 +1,285 @@
+// Data-driven neighbourhood graphs on the GPU (paper Sections 3.2.1-3.2.2, Algorithms 1 and 2):
+//   pairwise squared node distances  ->  edge set (minimum spanning tree, or relative neighbourhood graph by the
+//   blocker test)  ->  adjacency lists  ->  all-pairs hop counts G (float32, +inf where unreachable).
+// Everything that decides an edge is float64 and uses direct differences, so the graphs agree with a float64
+// host construction except on exact ties.  Work per rebuild at K = 1024: K^2 D distance flops, K^3 (max, min)
+// operations for the blocker test, K breadth-first searches.
+//   node_d2_kernel     d2[p][q] = sum_d (w_pd - w_qd)^2
+//   mst_prim_kernel    Prim's method in one workgroup: K rounds of (parallel arg-min, key update)
+//   rng_block_kernel   a 32 x 32 tile of pairs per workgroup; third nodes staged through LDS 64 at a time;
+//                      pair (p, q) survives unless some r has max(d2[p][r], d2[q][r]) < d2[p][q]
+//   csr_*              degree count, exclusive scan, ascending neighbour lists
+//   bfs_kernel         one workgroup per source, level-synchronous search with the distance row in LDS
+#include "som_internal.hpp"
+
+#include <math.h>
+
+namespace som {
+
+__global__ void __launch_bounds__(256) node_d2_kernel(const float* __restrict__ W, int K, int D, double* __restrict__ d2)
+{
+    const size_t e = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (e >= (size_t)K * K) return;
+    const int p = (int)(e / K), q = (int)(e % K);
+    const float* a = W + (size_t)p * D;
+    const float* b = W + (size_t)q * D;
+    double s = 0.0;
+    for (int d = 0; d < D; ++d) {
+        const double df = (double)a[d] - (double)b[d];
+        s = fma(df, df, s);
+    }
+    d2[e] = s;
+}
+
+// adjacency matrix A (K x K bytes) <- minimum spanning tree.  Ties between equal keys go to the lowest node index.
+__global__ void __launch_bounds__(1024) mst_prim_kernel(const double* __restrict__ d2, int K, unsigned char* __restrict__ A)
+{
+    extern __shared__ double prim_lds[];
+    double* key = prim_lds;                                   // [K] cheapest connection to the tree
+    int* from = reinterpret_cast<int*>(key + K);              // [K] its tree end
+    __shared__ double red_v[16];
+    __shared__ int red_i[16];
+    __shared__ int chosen;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    for (size_t e = tid; e < (size_t)K * K; e += 1024) A[e] = 0;
+    for (int v = tid; v < K; v += 1024) {
+        key[v] = (v == 0) ? -1.0 : d2[v];                     // node 0 starts the tree; -1 marks "in tree"
+        from[v] = 0;
+    }
+    __syncthreads();
+    for (int round = 1; round < K; ++round) {
+        double bv = INFINITY;
+        int bi = 0x7fffffff;
+        for (int v = tid; v < K; v += 1024) {
+            const double k = key[v];
+            if (k >= 0.0 && (k < bv || (k == bv && v < bi))) {
+                bv = k;
+                bi = v;
+            }
+        }
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) {
+            const double ov = __shfl_xor(bv, o);
+            const int oi = __shfl_xor(bi, o);
+            if (ov < bv || (ov == bv && oi < bi)) {
+                bv = ov;
+                bi = oi;
+            }
+        }
+        if (lane == 0) {
+            red_v[wave] = bv;
+            red_i[wave] = bi;
+        }
+        __syncthreads();
+        if (tid == 0) {
+            double mv = red_v[0];
+            int mi = red_i[0];
+            for (int w = 1; w < 16; ++w)
+                if (red_v[w] < mv || (red_v[w] == mv && red_i[w] < mi)) {
+                    mv = red_v[w];
+                    mi = red_i[w];
+                }
+            chosen = mi;
+            const int f = from[mi];
+            A[(size_t)mi * K + f] = 1;
+            A[(size_t)f * K + mi] = 1;
+            key[mi] = -1.0;
+        }
+        __syncthreads();
+        const int u = chosen;
+        const double* row = d2 + (size_t)u * K;
+        for (int v = tid; v < K; v += 1024) {
+            const double k = key[v];
+            const double c = row[v];
+            if (k >= 0.0 && c < k) {
+                key[v] = c;
+                from[v] = u;
+            }
+        }
+        __syncthreads();
+    }
+}
+
+// adjacency matrix A <- relative neighbourhood graph.  Workgroup = 32 x 32 pairs (p in tile bx, q in tile by).
+__global__ void __launch_bounds__(256) rng_block_kernel(const double* __restrict__ d2, int K, unsigned char* __restrict__ A)
+{
+    __shared__ double P[32][65];   // d2[p0 + i][r0 + j]
+    __shared__ double Q[32][65];
+    const int tid = threadIdx.x;
+    const int p0 = blockIdx.x * 32, q0 = blockIdx.y * 32;
+    // thread -> four pairs: p = p0 + (tid / 32) + 8 t, q = q0 + tid % 32
+    const int pi = tid >> 5, qi = tid & 31;
+    double lim[4];
+    bool blocked[4];
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+        const int p = p0 + pi + 8 * t, q = q0 + qi;
+        lim[t] = (p < K && q < K) ? d2[(size_t)p * K + q] : 0.0;
+        blocked[t] = false;
+    }
+    for (int r0 = 0; r0 < K; r0 += 64) {
+        __syncthreads();
+        for (int e = tid; e < 32 * 64; e += 256) {
+            const int i = e >> 6, jj = e & 63;
+            const int r = r0 + jj;
+            const bool in = r < K;
+            P[i][jj] = (in && p0 + i < K) ? d2[(size_t)(p0 + i) * K + r] : INFINITY;
+            Q[i][jj] = (in && q0 + i < K) ? d2[(size_t)(q0 + i) * K + r] : INFINITY;
+        }
+        __syncthreads();
+        // r = p and r = q give max = d2[p][q] itself, never strictly smaller: no masking needed
+#pragma unroll 8
+        for (int jj = 0; jj < 64; ++jj) {
+            const double qv = Q[qi][jj];
+#pragma unroll
+            for (int t = 0; t < 4; ++t) blocked[t] = blocked[t] || (fmax(P[pi + 8 * t][jj], qv) < lim[t]);
+        }
+    }
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+        const int p = p0 + pi + 8 * t, q = q0 + qi;
+        if (p < K && q < K) A[(size_t)p * K + q] = (p != q && !blocked[t]) ? 1 : 0;
+    }
+}
+
+__global__ void __launch_bounds__(256) csr_degree_kernel(const unsigned char* __restrict__ A, int K, int* __restrict__ deg)
+{
+    const int v = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+    if (v >= K) return;
+    int c = 0;
+    for (int u = lane; u < K; u += 64) c += A[(size_t)v * K + u] ? 1 : 0;
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) c += __shfl_xor(c, o);
+    if (lane == 0) deg[v] = c;
+}
+
+__global__ void __launch_bounds__(1024) csr_scan_kernel(const int* __restrict__ deg, int K, int* __restrict__ off)
+{
+    __shared__ int part[1024];
+    const int tid = threadIdx.x;
+    const int per = (K + 1023) / 1024;
+    int s = 0;
+    for (int t = 0; t < per; ++t) {
+        const int v = tid * per + t;
+        if (v < K) s += deg[v];
+    }
+    part[tid] = s;
+    __syncthreads();
+    for (int o = 1; o < 1024; o <<= 1) {
+        const int add = (tid >= o) ? part[tid - o] : 0;
+        __syncthreads();
+        part[tid] += add;
+        __syncthreads();
+    }
+    int run = part[tid] - s;
+    for (int t = 0; t < per; ++t) {
+        const int v = tid * per + t;
+        if (v < K) {
+            off[v] = run;
+            run += deg[v];
+        }
+    }
+    if (tid == 1023) off[K] = part[1023];
+}
+
+__global__ void __launch_bounds__(256) csr_fill_kernel(const unsigned char* __restrict__ A, int K,
+                                                       const int* __restrict__ off, int* __restrict__ nbr)
+{
+    const int v = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+    if (v >= K) return;
+    int base = off[v];
+    for (int u0 = 0; u0 < K; u0 += 64) {
+        const int u = u0 + lane;
+        const bool on = u < K && A[(size_t)v * K + u];
+        const unsigned long long bal = __ballot(on);
+        const int below = __builtin_amdgcn_mbcnt_hi((unsigned)(bal >> 32), __builtin_amdgcn_mbcnt_lo((unsigned)bal, 0));
+        if (on) nbr[base + below] = u;
+        base += __popcll(bal);
+    }
+}
+
+// hop counts from source = blockIdx.x to every node
+__global__ void __launch_bounds__(256) bfs_kernel(const int* __restrict__ off, const int* __restrict__ nbr, int K,
+                                                  float* __restrict__ G)
+{
+    extern __shared__ int bfs_dist[];      // [K]
+    __shared__ int changed;
+    const int tid = threadIdx.x, src = blockIdx.x;
+    for (int v = tid; v < K; v += 256) bfs_dist[v] = (v == src) ? 0 : -1;
+    __syncthreads();
+    for (int level = 0; level < K; ++level) {
+        if (tid == 0) changed = 0;
+        __syncthreads();
+        for (int v = tid; v < K; v += 256) {
+            if (bfs_dist[v] == level) {
+                for (int e = off[v]; e < off[v + 1]; ++e) {
+                    const int u = nbr[e];
+                    if (bfs_dist[u] < 0) {           // every writer stores the same value
+                        bfs_dist[u] = level + 1;
+                        changed = 1;
+                    }
+                }
+            }
+        }
+        __syncthreads();
+        if (!changed) break;
+        __syncthreads();
+    }
+    for (int v = tid; v < K; v += 256) {
+        const int d = bfs_dist[v];
+        G[(size_t)src * K + v] = d < 0 ? INFINITY : (float)d;
+    }
+}
+
+} // namespace som
+
+using namespace som;
+
+extern "C" int som_topology(som_ctx* ctx, const float* W, int32_t K, int32_t D, int kind, float* G)
+{
+    if (!ctx) return SOM_EINVAL;
+    if (!W || !G) return fail(ctx, SOM_EINVAL, "null W or G");
+    if (K < 1 || D < 1) return fail(ctx, SOM_EINVAL, "K and D must be positive");
+    if (kind != SOM_TOPOLOGY_MST && kind != SOM_TOPOLOGY_RNG) return fail(ctx, SOM_EINVAL, "unknown topology kind %d", kind);
+    if (K > 12000) return fail(ctx, SOM_EINVAL, "K = %d is above the 12000 nodes the graph kernels hold in LDS", K);
+    if (int rc = check_hip(ctx, hipSetDevice(ctx->device), "hipSetDevice")) return rc;
+    const size_t kk = (size_t)K * K;
+    const size_t need = kk * sizeof(double) + kk + (size_t)(2 * K + 2) * sizeof(int) + kk * sizeof(int) + 1024;
+    if (need > ctx->topo_bytes) {
+        if (ctx->topo_blob) {
+            if (int rc = check_hip(ctx, hipStreamSynchronize(ctx->stream), "sync before workspace growth")) return rc;
+            (void)hipFree(ctx->topo_blob);
+            ctx->topo_blob = nullptr;
+            ctx->topo_bytes = 0;
+        }
+        if (hipMalloc(&ctx->topo_blob, need) != hipSuccess) {
+            (void)hipGetLastError();
+            return fail(ctx, SOM_ENOMEM, "cannot allocate %zu bytes for the topology workspace", need);
+        }
+        ctx->topo_bytes = need;
+    }
+    char* base = (char*)ctx->topo_blob;
+    double* d2 = (double*)base;
+    int* deg = (int*)(base + kk * sizeof(double));
+    int* off = deg + K;                                  // K + 1 entries
+    int* nbr = off + K + 2;                              // at most K * K entries
+    unsigned char* A = (unsigned char*)(nbr + kk);
+    hipLaunchKernelGGL(node_d2_kernel, dim3((unsigned)((kk + 255) / 256)), dim3(256), 0, ctx->stream, W, K, D, d2);
+    if (int rc = check_hip(ctx, hipGetLastError(), "node distance launch")) return rc;
+    if (kind == SOM_TOPOLOGY_MST) {
+        const size_t lds = (size_t)K * 12 + 16;
+        if (lds > 48 * 1024) {
+            if (int rc = check_hip(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(mst_prim_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, 150 * 1024), "raising the dynamic LDS limit")) return rc;
+        }
+        hipLaunchKernelGGL(mst_prim_kernel, dim3(1), dim3(1024), lds, ctx->stream, d2, K, A);
+    } else {
+        hipLaunchKernelGGL(rng_block_kernel, dim3((K + 31) / 32, (K + 31) / 32), dim3(256), 0, ctx->stream, d2, K, A);
+    }
+    if (int rc = check_hip(ctx, hipGetLastError(), "edge kernel launch")) return rc;
+    hipLaunchKernelGGL(csr_degree_kernel, dim3((K + 3) / 4), dim3(256), 0, ctx->stream, A, K, deg);
+    hipLaunchKernelGGL(csr_scan_kernel, dim3(1), dim3(1024), 0, ctx->stream, deg, K, off);
+    hipLaunchKernelGGL(csr_fill_kernel, dim3((K + 3) / 4), dim3(256), 0, ctx->stream, A, K, off, nbr);
+    if (int rc = check_hip(ctx, hipGetLastError(), "adjacency launch")) return rc;
+    hipLaunchKernelGGL(bfs_kernel, dim3(K), dim3(256), (size_t)K * sizeof(int), ctx->stream, off, nbr, K, G);
+    return check_hip(ctx, hipGetLastError(), "hop-count launch");
+}

@@ -19,11 +19,13 @@ LIB_PATH = os.path.join(_HERE, "libsom.so")
 
 SOM_OK, SOM_EINVAL, SOM_ENOMEM, SOM_EHIP, SOM_EIO, SOM_ESTATE = 0, -1, -2, -3, -4, -5
 SOM_KERNEL_GAUSSIAN = 0
+SOM_TOPOLOGY_MST = 1
+SOM_TOPOLOGY_RNG = 2
 
 EXPORTS = [
     "som_create", "som_destroy", "som_strerror", "som_last_error", "som_sync", "som_bmu", "som_accumulate",
     "som_neighborhood_update", "som_epoch", "som_epoch_host", "som_profile", "som_profile_read",
-    "som_set_update_rule",
+    "som_set_update_rule", "som_topology",
 ]
 
 
@@ -75,6 +77,8 @@ def load_library(path: str = LIB_PATH) -> C.CDLL:
     lib.som_accumulate.restype = C.c_int
     lib.som_neighborhood_update.argtypes = [vp, vp, vp, vp, i32, i32, f64, C.c_int, f64, vp, vp]
     lib.som_neighborhood_update.restype = C.c_int
+    lib.som_topology.argtypes = [vp, vp, i32, i32, C.c_int, vp]
+    lib.som_topology.restype = C.c_int
     lib.som_epoch.argtypes = [vp, vp, i64, i32, i64, vp, i64, vp, i32, vp, f64, C.c_int, f64, C.POINTER(SomStats)]
     lib.som_epoch.restype = C.c_int
     lib.som_epoch_host.argtypes = [vp, vp, i64, i32, i64, C.c_int, vp, i32, vp, f64, C.c_int, f64,
@@ -241,6 +245,22 @@ class Som:
                                               _ptr(n_guarded, torch.int32, "n_guarded", self.device))
         self._check(rc, "som_neighborhood_update")
         return W
+
+    # ------------------------------------------------------------------ topology rebuild
+    def som_topology(self, W, kind, G=None):
+        K, D, _ = _matrix(W, "W")
+        if not W.is_contiguous():
+            raise ValueError("W must be contiguous")
+        if isinstance(kind, str):
+            kind = {"mst": SOM_TOPOLOGY_MST, "rng": SOM_TOPOLOGY_RNG}[kind]
+        if G is None:
+            G = torch.empty((K, K), dtype=torch.float32, device=W.device)
+        elif G.shape != (K, K) or not G.is_contiguous():
+            raise ValueError("G must be K x K contiguous")
+        rc = self.lib.som_topology(self._h, _ptr(W, torch.float32, "W", self.device), K, D, int(kind),
+                                   _ptr(G, torch.float32, "G", self.device))
+        self._check(rc, "som_topology")
+        return G
 
     # ------------------------------------------------------------------ whole epoch
     def som_epoch(self, X, W, G, sigma, idx=None, eps_h=0.0, want_stats=True, kernel=SOM_KERNEL_GAUSSIAN):

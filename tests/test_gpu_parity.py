@@ -220,6 +220,68 @@ def test_update_with_unreachable_nodes(som):
     assert (Wd.cpu().numpy()[5] == W[5]).all()
 
 
+# ------------------------------------------------------------------------------------------- topology rebuild
+@pytest.mark.parametrize("kind", ["mst", "rng"])
+@pytest.mark.parametrize("K,D", [(1, 3), (2, 1), (37, 5), (200, 8), (333, 50), (1024, 50)])
+def test_topology_matches_oracle(som, kind, K, D):
+    """Hop counts are integers and, with all pairwise distances distinct, both graphs are unique: exact equality."""
+    W = GaussianMixture(90 + K, D, 4).rows(0, K)
+    G = som.som_topology(dev(W), kind).cpu().numpy()
+    G_or = oracle.graph_distances(kind, W)
+    assert np.array_equal(G, G_or.astype(np.float32))
+
+
+def test_topology_on_a_square_grid(som):
+    """Nodes on the integer grid: the relative neighbourhood graph is the 4-neighbour grid (a diagonal of squared
+    length 2 is blocked by a corner at squared length 1 from both ends, a unit edge by nothing), so hop counts are
+    Manhattan distances; every spanning tree of minimal length uses K - 1 unit edges."""
+    rows, cols = 9, 12
+    r, c = np.divmod(np.arange(rows * cols), cols)
+    W = np.stack([c, r, np.zeros_like(r)], axis=1).astype(np.float32)
+    G = som.som_topology(dev(W), "rng").cpu().numpy()
+    assert np.array_equal(G, (np.abs(r[:, None] - r[None, :]) + np.abs(c[:, None] - c[None, :])).astype(np.float32))
+    assert np.array_equal(G, oracle.graph_distances("rng", W).astype(np.float32))
+    T = som.som_topology(dev(W), "mst").cpu().numpy()
+    p, q = np.nonzero(np.triu(T == 1))
+    assert len(p) == rows * cols - 1 and np.isfinite(T).all()
+    assert (np.abs(r[p] - r[q]) + np.abs(c[p] - c[q]) == 1).all()
+
+
+def test_topology_with_duplicate_nodes(som):
+    """Coincident nodes (squared distance 0) stay linked in both graphs; tree length equals the oracle's."""
+    base = GaussianMixture(7, 6, 3).rows(0, 40)
+    W = np.concatenate([base, base[:10], base[5:8]]).astype(np.float32)
+    K = len(W)
+    d2 = oracle.node_sq_distances(W)
+    T = som.som_topology(dev(W), "mst").cpu().numpy()
+    p, q = np.nonzero(np.triu(T == 1))
+    assert len(p) == K - 1 and np.isfinite(T).all()
+    e = oracle.mst_edges(W)
+    np.testing.assert_allclose(np.sqrt(d2[p, q]).sum(), np.sqrt(d2[e[:, 0], e[:, 1]]).sum(), rtol=1e-12)
+    R = som.som_topology(dev(W), "rng").cpu().numpy()
+    assert np.array_equal(R, oracle.graph_distances("rng", W).astype(np.float32))
+
+
+def test_topology_feeds_an_epoch(som):
+    """Graph built on the device drives the update of the same epoch: equals the oracle's epoch on its own graph."""
+    wl = make_workload("cfg0", topology="rng")
+    X = wl.data().rows(0, 20_000)
+    W = X[draw_initial_rows(wl.seed, len(X), wl.k)].copy()
+    Xd, Wd = dev(X), dev(W)
+    for t in range(3):
+        sigma = linear_sigma(*wl.sigma, wl.epochs)[t]
+        Gd = som.som_topology(Wd, "rng")
+        G_or = oracle.graph_distances("rng", W)
+        assert np.array_equal(Gd.cpu().numpy(), G_or.astype(np.float32))
+        b_gpu = som.som_bmu(Xd, Wd)[0].cpu().numpy()
+        b, _, mask = check_bmu(b_gpu, None, X, W)
+        som.som_epoch(Xd, Wd, Gd, sigma)
+        out = oracle.epoch_grouped(X, None, W, G_or, sigma, b=np.where(mask, b_gpu, b))
+        weights_close(Wd.cpu().numpy(), out["W"], out["den"])
+        W = out["W"].astype(np.float32)
+        Wd = dev(W)
+
+
 # ------------------------------------------------------------------------------------------- whole epochs
 def run_teacher_forced(som, wl, n_rows, epochs, idx_fn=None):
     """Each epoch starts from the oracle's weights; compares BMUs, weights, QE and counters of that epoch."""
