@@ -4,8 +4,8 @@
 // S = A^T X with A the N x K one-hot matrix of the BMUs.  Dense, that contraction would cost as much as the BMU
 // search; restricted to the rows that can be non-zero it is tiny.  A workgroup owns a contiguous range of
 // samples and ALL of S for that range: the K x (D + 1) partial (the extra column counts samples: its X entry is a
-// constant 1) is cut into 32-node x 32-feature blocks of 16 accumulator VGPRs, dealt round-robin over the 16
-// wavefronts (node block nb belongs to wavefront nb % 16).  Samples arrive in LDS tiles of 256 full rows.  For
+// constant 1) is cut into 32-node x 32-feature blocks of 16 accumulator VGPRs, dealt round-robin over the 8
+// wavefronts (node block nb belongs to wavefront nb % 8).  Samples arrive in LDS tiles of 256 full rows.  For
 // every tile a wavefront compacts, per node block it owns, the tile positions whose BMU falls into the block
 // (ballot + prefix count; ascending, so the order of additions is fixed), then feeds them two at a time to
 // v_mfma_f32_32x32x2_f32:  A = 32 nodes x 2 samples, 1.0 where the node is the sample's BMU;  B = 2 samples x 32
@@ -13,14 +13,27 @@
 // building an operand costs no vector instructions).  No atomics anywhere, X is read exactly once, and a node
 // that attracts a quarter of all samples only lengthens one wavefront's MFMA chain.
 // The accumulators move into the workgroup's slice of a global workspace every kFlushRows samples (bounding any
-// float32 summation chain); a second kernel adds the slices in a fixed order into S and n.
+// float32 summation chain); a second kernel adds the slices in a fixed order into S and n.  Slices are padded to
+// whole 32-node x 32-column blocks so that every accumulator store is unconditional and covers whole, aligned
+// 128-byte runs.  Eight wavefronts of up to 256 VGPRs per workgroup: with sixteen the 128 accumulator registers of
+// a 1024-node, 64-column partial do not fit and spill.
 #include "som_internal.hpp"
 
 namespace som {
 
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 
-constexpr int kMThreads = 1024;
+// Elements between consecutive workgroups' slices: the padded K x columns block, rounded up to an odd number of
+// 4 KiB pages.  All workgroups store the same slice offsets at the same time; with a power-of-two distance those
+// stores land on a few memory channels only.
+__host__ __device__ inline size_t slice_stride(int K, int cols, size_t elem_bytes)
+{
+    size_t pages = ((size_t)((K + 31) / 32) * 32 * cols * elem_bytes + 4095) / 4096;
+    pages |= 1;
+    return pages * 4096 / elem_bytes;
+}
+
+constexpr int kMThreads = 512;
 constexpr int kMWaves = kMThreads / 64;
 constexpr int kMTile = 256;        // rows per LDS tile; tile positions fit a byte
 constexpr int kMFlushRows = 16384;
@@ -40,12 +53,14 @@ __global__ void __launch_bounds__(kMThreads) accumulate_mfma_kernel(const float*
     int* Bt = reinterpret_cast<int*>(T + kMTile * STRIDE);                  // [kMTile]
     unsigned short* Lst = reinterpret_cast<unsigned short*>(Bt + kMTile);   // [kMWaves * NBW][kMTile]
     const int tid = threadIdx.x;
-    const int lane = tid & 63, wave = tid >> 6;
-    const int DS = D + 1;                                                   // slice row: D sums and the count
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // scalar: row addresses of the tile loads stay in SGPRs
     const int64_t lo = (int64_t)blockIdx.x * rows_per_range;
     int64_t hi = lo + rows_per_range;
     if (hi > m) hi = m;
-    SliceT* mine = part + (size_t)blockIdx.x * K * DS;
+    constexpr int LS = FB * 32;                                             // padded slice row: whole cache lines per store
+    const int KP = ((K + 31) / 32) * 32;                                    // slice rows: whole node blocks
+    SliceT* mine = part + (size_t)blockIdx.x * slice_stride(K, LS, sizeof(SliceT));
 
     // constant columns of the tile: 1.0 in column D, 0.0 behind it
     for (int e = tid; e < kMTile * (COLS - D); e += kMThreads) {
@@ -61,35 +76,47 @@ __global__ void __launch_bounds__(kMThreads) accumulate_mfma_kernel(const float*
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[q][fb][r] = 0.0f;
 
-    // tile loading: wavefront w brings rows w, w + 16, ...; lane = feature (D <= 63 on this path)
+    // tile loading: wavefront w brings rows w, w + 8, ...; lane = feature (D <= 63 on this path)
     float pre[PASSES];
     int preb = -1;
+    const int lanecol = lane < D ? lane : D - 1;              // clamped, so every load is unconditional
+    // Row numbers are wave-uniform: the row base stays in scalar registers and the lane adds its column.  The
+    // fetch only issues loads; anything computed from a loaded value waits for the stash, after the tile before
+    // has been consumed.
     auto fetch = [&](int64_t t0, int64_t top) {
-        int64_t rows[PASSES];
+        if (!idx && t0 + kMTile <= top) {
+            // whole tile of consecutive rows: one base, a constant stride (two scalar adds per row)
+            const float* rowp = X + (t0 + wave) * ldx;
+            const int64_t step = (int64_t)kMWaves * ldx;
 #pragma unroll
-        for (int p = 0; p < PASSES; ++p) {
-            const int64_t i = t0 + wave + p * kMWaves;
-            rows[p] = i < top ? i : top - 1;
-        }
-        if (idx) {
+            for (int p = 0; p < PASSES; ++p) {
+                pre[p] = rowp[lanecol];
+                rowp += step;
+            }
+        } else {
+            // ragged tail or an index list: clamp, translate, then address every row on its own
+            int64_t row[PASSES];
 #pragma unroll
-            for (int p = 0; p < PASSES; ++p) rows[p] = (int64_t)idx[rows[p]];
-        }
-        const float* col = X + (lane < D ? lane : D - 1);     // clamped, so every load is unconditional
+            for (int p = 0; p < PASSES; ++p) {
+                const int64_t i = t0 + wave + p * kMWaves;
+                row[p] = i < top ? i : top - 1;
+            }
+            if (idx) {
 #pragma unroll
-        for (int p = 0; p < PASSES; ++p) pre[p] = col[rows[p] * ldx];
-        {
-            const int64_t i = t0 + (tid & (kMTile - 1));
-            const int b = bmu[i < top ? i : top - 1];
-            preb = (i < top && b >= 0 && b < K) ? b : -1;
+                for (int p = 0; p < PASSES; ++p) row[p] = (int64_t)idx[row[p]];
+            }
+#pragma unroll
+            for (int p = 0; p < PASSES; ++p) pre[p] = X[row[p] * ldx + lanecol];
         }
+        const int64_t i = t0 + (tid & (kMTile - 1));
+        preb = bmu[i < top ? i : top - 1];
     };
-    auto stash = [&]() {
+    auto stash = [&](int64_t t0, int64_t top) {
         if (lane < D) {
 #pragma unroll
             for (int p = 0; p < PASSES; ++p) T[(wave + p * kMWaves) * STRIDE + lane] = pre[p];
         }
-        if (tid < kMTile) Bt[tid] = preb;
+        if (tid < kMTile) Bt[tid] = (t0 + tid < top && preb >= 0 && preb < K) ? preb : -1;
     };
     auto consume = [&]() {
         // 1. per owned node block: ascending list of (tile position | node-in-block << 8)
@@ -151,31 +178,39 @@ __global__ void __launch_bounds__(kMThreads) accumulate_mfma_kernel(const float*
             fetch(base, top);
             for (int64_t t0 = base; t0 < top; t0 += kMTile) {
                 __syncthreads();                                  // tile free (and the constant columns written)
-                stash();
+                stash(t0, top);
                 __syncthreads();
                 if (t0 + kMTile < top) fetch(t0 + kMTile, top);   // in flight while this tile is consumed
                 consume();
             }
         }
         // accumulators -> slice (first flush stores, later ones add), then clear.  Register r of lane l holds
-        // node 8 (r / 4) + 4 (l / 32) + r % 4 of the block, column l % 32.
+        // node 8 (r / 4) + 4 (l / 32) + r % 4 of the block, column l % 32.  Slices are padded to whole node
+        // blocks and whole column blocks, so every store is unconditional and covers aligned 128-byte runs.
 #pragma unroll
         for (int q = 0; q < NBW; ++q) {
             const int nb = wave + q * kMWaves;
+            if (nb * 32 < KP) {
 #pragma unroll
-            for (int fb = 0; fb < FB; ++fb) {
-                const int col = fb * 32 + (lane & 31);
+                for (int fb = 0; fb < FB; ++fb) {
+                    // the offset is made opaque so that the store addresses are formed here, not kept in
+                    // registers for the whole kernel
+                    int off = (nb * 32 + 4 * (lane >> 5)) * LS + fb * 32 + (lane & 31);
+                    asm volatile("" : "+v"(off));
+                    SliceT* cell = mine + off;
+                    if (first) {
 #pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const int node = nb * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-                    if (node < K && col < DS) {
-                        SliceT* cell = mine + (size_t)node * DS + col;
-                        const SliceT val = (SliceT)acc[q][fb][r];
-                        *cell = first ? val : (SliceT)(*cell + val);
+                        for (int r = 0; r < 16; ++r) cell[(8 * (r >> 2) + (r & 3)) * LS] = (SliceT)acc[q][fb][r];
+                    } else {
+#pragma unroll
+                        for (int r = 0; r < 16; ++r) cell[(8 * (r >> 2) + (r & 3)) * LS] += (SliceT)acc[q][fb][r];
                     }
-                    acc[q][fb][r] = 0.0f;
                 }
             }
+#pragma unroll
+            for (int fb = 0; fb < FB; ++fb)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[q][fb][r] = 0.0f;
         }
         first = false;
     }
@@ -190,13 +225,13 @@ __global__ void __launch_bounds__(256) accumulate_mfma_reduce_kernel(const Slice
 {
     __shared__ double qsum[4][64];
     const int q = threadIdx.x >> 6, l = threadIdx.x & 63;
-    const int DS = D + 1;
-    const int c = blockIdx.x * 64 + l;                    // cell of the K x (D + 1) slice layout
+    const int DS = ((D + 1 + 31) / 32) * 32;              // padded slice row (only columns 0..D carry data)
+    const int c = blockIdx.x * 64 + l;                    // cell of the K x DS slice layout
     const int per = (ranges + 3) / 4;
     const int r_lo = q * per, r_hi = (r_lo + per < ranges) ? r_lo + per : ranges;
     double s = 0.0;
-    if (c < K * DS) {
-        const size_t stride = (size_t)K * DS;
+    if (c < K * DS && c % DS <= D) {
+        const size_t stride = slice_stride(K, DS, sizeof(SliceT));
 #pragma unroll 8
         for (int r = r_lo; r < r_hi; ++r) s += (double)part[(size_t)r * stride + c];
     }
@@ -207,7 +242,7 @@ __global__ void __launch_bounds__(256) accumulate_mfma_reduce_kernel(const Slice
         const int k = c / DS, f = c % DS;
         if (f < D)
             S[(size_t)k * D + f] = (zero_first ? 0.0 : S[(size_t)k * D + f]) + tot;
-        else
+        else if (f == D)
             n[k] = (zero_first ? 0ull : n[k]) + (unsigned long long)(tot + 0.5);
     }
 }
@@ -261,7 +296,8 @@ int accumulate_mfma_run(som_ctx* ctx, const float* X, int32_t D, int64_t ldx, co
     const int64_t rows_per_range = (((m + ranges - 1) / ranges + kMTile - 1) / kMTile) * kMTile;
     ranges = (m + rows_per_range - 1) / rows_per_range;
     const bool single_flush = rows_per_range <= kMFlushRows;
-    const size_t need = (size_t)ranges * K * (D + 1) * (single_flush ? sizeof(float) : sizeof(double));
+    const size_t esz = single_flush ? sizeof(float) : sizeof(double);
+    const size_t need = (size_t)ranges * slice_stride(K, fb * 32, esz) * esz;
     if (need > ctx->acc_bytes) {
         if (ctx->acc_blob) {
             if (int rc = check_hip(ctx, hipStreamSynchronize(ctx->stream), "sync before workspace growth")) return rc;
@@ -275,7 +311,7 @@ int accumulate_mfma_run(som_ctx* ctx, const float* X, int32_t D, int64_t ldx, co
         }
         ctx->acc_bytes = need;
     }
-    const int cells = K * (D + 1);
+    const int cells = K * fb * 32;
     const dim3 rgrid((cells + 63) / 64);
     if (single_flush) {
         float* part = (float*)ctx->acc_blob;
