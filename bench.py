@@ -26,15 +26,25 @@ def stream_bench(args, wl, X, W0, sig, som, pkg, torch) -> int:
     if args.stream == "pinned":
         Xh = Xh.pin_memory()
     Wd = torch.from_numpy(W0).cuda()
-    G = torch.from_numpy(pkg.topology.graph_distances(wl.topology, lattice=wl.lattice)).cuda()
+    lattice = wl.topology in ("rect", "hex")
+    if lattice:
+        G = torch.from_numpy(pkg.topology.graph_distances(wl.topology, lattice=wl.lattice)).cuda()
+    else:
+        G = torch.empty((wl.k, wl.k), dtype=torch.float32, device="cuda")
+
+    def epoch(e):
+        if not lattice:                      # data-driven graph, rebuilt on the device from the current weights
+            som.som_topology(Wd, wl.topology, G)
+        return som.som_epoch_host(Xh, Wd, G, float(sig[min(e, len(sig) - 1)]), chunk_rows=args.chunk_rows)
+
     for e in range(args.warmup):
-        som.som_epoch_host(Xh, Wd, G, float(sig[min(e, len(sig) - 1)]), chunk_rows=args.chunk_rows)
+        epoch(e)
     Wd.copy_(torch.from_numpy(W0))
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     h2d_ms = 0.0
     for e in range(args.steps):
-        st = som.som_epoch_host(Xh, Wd, G, float(sig[e]), chunk_rows=args.chunk_rows)
+        st = epoch(e)
         h2d_ms += st.ms_h2d
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
