@@ -133,9 +133,10 @@ int som_set_update_rule(som_ctx* ctx, double eta, double mu, float* velocity);
  *   kind  SOM_TOPOLOGY_MST or SOM_TOPOLOGY_RNG
  *   G [device] float[K*K], caller-owned, OVERWRITTEN: G[p*K+q] = hop count, 0 on the diagonal, +inf between
  *     nodes in different components (possible only when distances are non-finite)
- * Distances and every comparison that decides an edge are float64 on direct differences; when several edges
- * have exactly equal length the spanning tree is one of the minimal ones (lowest node index joins first).
- * Asynchronous on the context's stream; K is limited to 12000 by the spanning-tree kernel's LDS use.
+ * Distances and every comparison that decides an edge are float64 on direct differences.  When several edges
+ * have exactly equal length the spanning tree is a minimal one: for K <= 4096 the one that visiting edges in
+ * (length, lower end, higher end) order would build, above that the one Prim's method grows from node 0.
+ * Asynchronous on the context's stream; K is limited to 12000 by the graph kernels' LDS use.
  */
 int som_topology(som_ctx* ctx, const float* W, int32_t K, int32_t D, int kind, float* G);
 

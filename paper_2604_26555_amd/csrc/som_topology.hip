@@ -5,7 +5,9 @@
 // host construction except on exact ties.  Work per rebuild at K = 1024: K^2 D distance flops, K^3 (max, min)
 // operations for the blocker test, K breadth-first searches.
 //   node_d2_kernel     d2[p][q] = sum_d (w_pd - w_qd)^2
-//   mst_prim_kernel    Prim's method in one workgroup: K rounds of (parallel arg-min, key update)
+//   boruvka_*          spanning tree for K <= 4096: <= log2 K rounds of (cheapest outgoing edge per node over all
+//                      compute units, per-component minimum + merge in one workgroup)
+//   mst_prim_kernel    spanning tree for larger K: Prim's method in one workgroup, K rounds of (arg-min, key update)
 //   rng_block_kernel   a 32 x 32 tile of pairs per workgroup; third nodes staged through LDS 64 at a time;
 //                      pair (p, q) survives unless some r has max(d2[p][r], d2[q][r]) < d2[p][q]
 //   csr_*              degree count, exclusive scan, ascending neighbour lists
@@ -16,19 +18,41 @@
 
 namespace som {
 
+constexpr int kBoruvkaMaxNodes = 4096;   // 24 bytes of LDS per node in the merge kernel
+
+// 32 x 32 pairs per workgroup, features staged through LDS 32 at a time; every pair sums over d in ascending order
 __global__ void __launch_bounds__(256) node_d2_kernel(const float* __restrict__ W, int K, int D, double* __restrict__ d2)
 {
-    const size_t e = (size_t)blockIdx.x * 256 + threadIdx.x;
-    if (e >= (size_t)K * K) return;
-    const int p = (int)(e / K), q = (int)(e % K);
-    const float* a = W + (size_t)p * D;
-    const float* b = W + (size_t)q * D;
-    double s = 0.0;
-    for (int d = 0; d < D; ++d) {
-        const double df = (double)a[d] - (double)b[d];
-        s = fma(df, df, s);
+    __shared__ float Wp[32][33];
+    __shared__ float Wq[32][33];
+    const int tid = threadIdx.x;
+    const int p0 = blockIdx.x * 32, q0 = blockIdx.y * 32;
+    const int pi = tid >> 5, qi = tid & 31;
+    double s[4] = {0.0, 0.0, 0.0, 0.0};
+    for (int d0 = 0; d0 < D; d0 += 32) {
+        __syncthreads();
+        for (int e = tid; e < 32 * 32; e += 256) {
+            const int i = e >> 5, dd = e & 31;
+            const bool in = d0 + dd < D;
+            Wp[i][dd] = (in && p0 + i < K) ? W[(size_t)(p0 + i) * D + d0 + dd] : 0.0f;
+            Wq[i][dd] = (in && q0 + i < K) ? W[(size_t)(q0 + i) * D + d0 + dd] : 0.0f;
+        }
+        __syncthreads();
+        const int lim = (D - d0 < 32) ? D - d0 : 32;
+        for (int dd = 0; dd < lim; ++dd) {
+            const double b = (double)Wq[qi][dd];
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                const double df = (double)Wp[pi + 8 * t][dd] - b;
+                s[t] = fma(df, df, s[t]);
+            }
+        }
     }
-    d2[e] = s;
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+        const int p = p0 + pi + 8 * t, q = q0 + qi;
+        if (p < K && q < K) d2[(size_t)p * K + q] = s[t];
+    }
 }
 
 // adjacency matrix A (K x K bytes) <- minimum spanning tree.  Ties between equal keys go to the lowest node index.
@@ -100,9 +124,139 @@ __global__ void __launch_bounds__(1024) mst_prim_kernel(const double* __restrict
     }
 }
 
-// adjacency matrix A <- relative neighbourhood graph.  Workgroup = 32 x 32 pairs (p in tile bx, q in tile by).
+// ---- Boruvka's method for K <= 4096: every round each component picks its cheapest outgoing edge under the strict
+// order (length, lower end, higher end) -- the order Kruskal's method would visit edges in, so the tree is the
+// same one even when lengths tie -- and the components joined by the picked edges merge.  At most ceil(log2 K)
+// rounds; a round is one scan over all pairs (all compute units) and one single-workgroup merge.
+
+__device__ __forceinline__ bool edge_before(double wa, int la, int ha, double wb, int lb, int hb)
+{
+    return wa < wb || (wa == wb && (la < lb || (la == lb && ha < hb)));
+}
+
+// state[0] = number of components, comp[v] = label of v's component (the label is one of its nodes)
+__global__ void __launch_bounds__(256) boruvka_init_kernel(int K, int* __restrict__ comp, int* __restrict__ state,
+                                                           unsigned char* __restrict__ A)
+{
+    const size_t e = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (e < (size_t)K * K) A[e] = 0;
+    if (e < (size_t)K) comp[e] = (int)e;
+    if (e == 0) state[0] = K;
+}
+
+// one wavefront per node v: cheapest edge to a node of another component
+__global__ void __launch_bounds__(256) boruvka_scan_kernel(const double* __restrict__ d2, int K, const int* __restrict__ comp,
+                                                           const int* __restrict__ state, double* __restrict__ best_w,
+                                                           int* __restrict__ best_u)
+{
+    if (state[0] <= 1) return;
+    const int v = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+    if (v >= K) return;
+    const int cv = comp[v];
+    double bw = INFINITY;
+    int bu = -1, blo = 0x7fffffff, bhi = 0x7fffffff;
+    for (int u = lane; u < K; u += 64) {
+        if (comp[u] == cv) continue;
+        const double w = d2[(size_t)v * K + u];
+        const int lo = v < u ? v : u, hi = v < u ? u : v;
+        if (bu < 0 || edge_before(w, lo, hi, bw, blo, bhi)) {
+            bw = w;
+            bu = u;
+            blo = lo;
+            bhi = hi;
+        }
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        const double ow = __shfl_xor(bw, o);
+        const int ou = __shfl_xor(bu, o), olo = __shfl_xor(blo, o), ohi = __shfl_xor(bhi, o);
+        if (ou >= 0 && (bu < 0 || edge_before(ow, olo, ohi, bw, blo, bhi))) {
+            bw = ow;
+            bu = ou;
+            blo = olo;
+            bhi = ohi;
+        }
+    }
+    if (lane == 0) {
+        best_w[v] = bw;
+        best_u[v] = bu;
+    }
+}
+
+// single workgroup: per-component minimum of the node picks, edges into A, merge of the joined components
+__global__ void __launch_bounds__(1024) boruvka_merge_kernel(int K, int* __restrict__ comp, int* __restrict__ state,
+                                                             const double* __restrict__ best_w, const int* __restrict__ best_u,
+                                                             unsigned char* __restrict__ A)
+{
+    if (state[0] <= 1) return;
+    extern __shared__ unsigned long long bor_lds[];
+    unsigned long long* cw = bor_lds;                                 // [K] bit pattern of the cheapest length
+    unsigned long long* ce = cw + K;                                  // [K] its ends, lower << 32 | higher
+    int* parent = reinterpret_cast<int*>(ce + K);                     // [K]
+    int* parent2 = parent + K;                                        // [K]
+    __shared__ int count;
+    const int tid = threadIdx.x;
+    for (int c = tid; c < K; c += 1024) {
+        cw[c] = ~0ull;
+        ce[c] = ~0ull;
+    }
+    if (tid == 0) count = 0;
+    __syncthreads();
+    // lengths are non-negative doubles (or +inf): their bit patterns order like the values
+    for (int v = tid; v < K; v += 1024)
+        if (best_u[v] >= 0) atomicMin(&cw[comp[v]], (unsigned long long)__double_as_longlong(best_w[v]));
+    __syncthreads();
+    for (int v = tid; v < K; v += 1024) {
+        const int u = best_u[v];
+        if (u >= 0 && (unsigned long long)__double_as_longlong(best_w[v]) == cw[comp[v]]) {
+            const unsigned long long lo = v < u ? v : u, hi = v < u ? u : v;
+            atomicMin(&ce[comp[v]], (lo << 32) | hi);
+        }
+    }
+    __syncthreads();
+    for (int c = tid; c < K; c += 1024) {
+        int par = c;
+        if (comp[c] == c && ce[c] != ~0ull) {
+            const int lo = (int)(ce[c] >> 32), hi = (int)(ce[c] & 0xffffffffull);
+            A[(size_t)lo * K + hi] = 1;
+            A[(size_t)hi * K + lo] = 1;
+            par = (comp[lo] == c) ? comp[hi] : comp[lo];
+        }
+        parent[c] = par;
+    }
+    __syncthreads();
+    // two components that picked each other (necessarily the same edge): the lower label becomes the root
+    for (int c = tid; c < K; c += 1024) {
+        const int par = parent[c];
+        parent2[c] = (parent[par] == c && c < par) ? c : par;
+    }
+    __syncthreads();
+    int* from = parent2;
+    int* to = parent;
+    for (int span = 1; span < K; span <<= 1) {
+        for (int c = tid; c < K; c += 1024) to[c] = from[from[c]];
+        __syncthreads();
+        int* t = from;
+        from = to;
+        to = t;
+    }
+    int mine = 0;
+    for (int v = tid; v < K; v += 1024) {
+        const int root = from[comp[v]];      // from[] is not written any more; comp[v] is this thread's own entry
+        comp[v] = root;
+        if (root == v) ++mine;
+    }
+    if (mine) atomicAdd(&count, mine);
+    __syncthreads();
+    if (tid == 0) state[0] = count;
+}
+
+// adjacency matrix A <- relative neighbourhood graph.  Workgroup = 32 x 32 pairs (p in tile bx, q in tile by >= bx;
+// the criterion is symmetric, so the tile below the diagonal is written from the one above).  The scan over third
+// nodes stops as soon as every pair of the tile has found a blocker.
 __global__ void __launch_bounds__(256) rng_block_kernel(const double* __restrict__ d2, int K, unsigned char* __restrict__ A)
 {
+    if (blockIdx.x > blockIdx.y) return;
     __shared__ double P[32][65];   // d2[p0 + i][r0 + j]
     __shared__ double Q[32][65];
     const int tid = threadIdx.x;
@@ -114,11 +268,13 @@ __global__ void __launch_bounds__(256) rng_block_kernel(const double* __restrict
 #pragma unroll
     for (int t = 0; t < 4; ++t) {
         const int p = p0 + pi + 8 * t, q = q0 + qi;
-        lim[t] = (p < K && q < K) ? d2[(size_t)p * K + q] : 0.0;
-        blocked[t] = false;
+        const bool real = p < K && q < K && p != q;
+        lim[t] = real ? d2[(size_t)p * K + q] : 0.0;
+        blocked[t] = !real;                               // nothing to decide for padding and for the diagonal
     }
     for (int r0 = 0; r0 < K; r0 += 64) {
-        __syncthreads();
+        // also the barrier that frees P and Q; every thread evaluates it the same number of times
+        if (__syncthreads_and(blocked[0] && blocked[1] && blocked[2] && blocked[3])) break;
         for (int e = tid; e < 32 * 64; e += 256) {
             const int i = e >> 6, jj = e & 63;
             const int r = r0 + jj;
@@ -138,7 +294,11 @@ __global__ void __launch_bounds__(256) rng_block_kernel(const double* __restrict
 #pragma unroll
     for (int t = 0; t < 4; ++t) {
         const int p = p0 + pi + 8 * t, q = q0 + qi;
-        if (p < K && q < K) A[(size_t)p * K + q] = (p != q && !blocked[t]) ? 1 : 0;
+        if (p < K && q < K) {
+            const unsigned char keep = (p != q && !blocked[t]) ? 1 : 0;
+            A[(size_t)p * K + q] = keep;
+            A[(size_t)q * K + p] = keep;
+        }
     }
 }
 
@@ -244,7 +404,7 @@ extern "C" int som_topology(som_ctx* ctx, const float* W, int32_t K, int32_t D, 
     if (K > 12000) return fail(ctx, SOM_EINVAL, "K = %d is above the 12000 nodes the graph kernels hold in LDS", K);
     if (int rc = check_hip(ctx, hipSetDevice(ctx->device), "hipSetDevice")) return rc;
     const size_t kk = (size_t)K * K;
-    const size_t need = kk * sizeof(double) + kk + (size_t)(2 * K + 2) * sizeof(int) + kk * sizeof(int) + 1024;
+    const size_t need = kk * sizeof(double) + (size_t)K * sizeof(double) + ((size_t)4 * K + 8 + kk) * sizeof(int) + kk + 1024;
     if (need > ctx->topo_bytes) {
         if (ctx->topo_blob) {
             if (int rc = check_hip(ctx, hipStreamSynchronize(ctx->stream), "sync before workspace growth")) return rc;
@@ -258,22 +418,38 @@ extern "C" int som_topology(som_ctx* ctx, const float* W, int32_t K, int32_t D, 
         }
         ctx->topo_bytes = need;
     }
-    char* base = (char*)ctx->topo_blob;
-    double* d2 = (double*)base;
-    int* deg = (int*)(base + kk * sizeof(double));
+    double* d2 = (double*)ctx->topo_blob;
+    double* best_w = d2 + kk;
+    int* deg = (int*)(best_w + K);
     int* off = deg + K;                                  // K + 1 entries
-    int* nbr = off + K + 2;                              // at most K * K entries
+    int* comp = off + K + 2;
+    int* best_u = comp + K;
+    int* state = best_u + K;                             // 4 entries
+    int* nbr = state + 4;                                // at most K * K entries
     unsigned char* A = (unsigned char*)(nbr + kk);
-    hipLaunchKernelGGL(node_d2_kernel, dim3((unsigned)((kk + 255) / 256)), dim3(256), 0, ctx->stream, W, K, D, d2);
+    const dim3 tiles((K + 31) / 32, (K + 31) / 32);
+    hipLaunchKernelGGL(node_d2_kernel, tiles, dim3(256), 0, ctx->stream, W, K, D, d2);
     if (int rc = check_hip(ctx, hipGetLastError(), "node distance launch")) return rc;
-    if (kind == SOM_TOPOLOGY_MST) {
+    if (kind == SOM_TOPOLOGY_MST && K <= kBoruvkaMaxNodes) {
+        const size_t lds = (size_t)K * 24;
+        if (lds > 48 * 1024) {
+            if (int rc = check_hip(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(boruvka_merge_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, kBoruvkaMaxNodes * 24), "raising the dynamic LDS limit")) return rc;
+        }
+        hipLaunchKernelGGL(boruvka_init_kernel, dim3((unsigned)((kk + 255) / 256)), dim3(256), 0, ctx->stream, K, comp, state, A);
+        int rounds = 0;
+        while ((1 << rounds) < K) ++rounds;              // the number of components at least halves every round
+        for (int r = 0; r < rounds; ++r) {
+            hipLaunchKernelGGL(boruvka_scan_kernel, dim3((K + 3) / 4), dim3(256), 0, ctx->stream, d2, K, comp, state, best_w, best_u);
+            hipLaunchKernelGGL(boruvka_merge_kernel, dim3(1), dim3(1024), lds, ctx->stream, K, comp, state, best_w, best_u, A);
+        }
+    } else if (kind == SOM_TOPOLOGY_MST) {
         const size_t lds = (size_t)K * 12 + 16;
         if (lds > 48 * 1024) {
             if (int rc = check_hip(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(mst_prim_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, 150 * 1024), "raising the dynamic LDS limit")) return rc;
         }
         hipLaunchKernelGGL(mst_prim_kernel, dim3(1), dim3(1024), lds, ctx->stream, d2, K, A);
     } else {
-        hipLaunchKernelGGL(rng_block_kernel, dim3((K + 31) / 32, (K + 31) / 32), dim3(256), 0, ctx->stream, d2, K, A);
+        hipLaunchKernelGGL(rng_block_kernel, tiles, dim3(256), 0, ctx->stream, d2, K, A);
     }
     if (int rc = check_hip(ctx, hipGetLastError(), "edge kernel launch")) return rc;
     hipLaunchKernelGGL(csr_degree_kernel, dim3((K + 3) / 4), dim3(256), 0, ctx->stream, A, K, deg);

@@ -245,6 +245,27 @@ def test_topology_on_a_square_grid(som):
     p, q = np.nonzero(np.triu(T == 1))
     assert len(p) == rows * cols - 1 and np.isfinite(T).all()
     assert (np.abs(r[p] - r[q]) + np.abs(c[p] - c[q]) == 1).all()
+    # all lengths are exact here, and both sides break ties by (length, lower end, higher end): the same tree
+    assert np.array_equal(T, oracle.graph_distances("mst", W).astype(np.float32))
+
+
+def test_topology_spanning_tree_above_the_boruvka_limit(som):
+    """More than 4096 nodes take the single-workgroup Prim kernel."""
+    K = 4100
+    W = GaussianMixture(17, 3, 4).rows(0, K)
+    T = som.som_topology(dev(W), "mst").cpu().numpy()
+    e = oracle.mst_edges(W)
+    adj = np.zeros((K, K), dtype=bool)
+    adj[e[:, 0], e[:, 1]] = adj[e[:, 1], e[:, 0]] = True
+    assert np.array_equal(T == 1, adj)                       # the tree itself
+    assert np.isfinite(T).all() and (T.diagonal() == 0).all() and np.array_equal(T, T.T)
+    # hop counts from a few sources (the oracle's all-pairs search takes too long at this size; scipy's unweighted
+    # shortest paths are what the oracle's search is pinned to)
+    from scipy.sparse import csr_matrix
+    from scipy.sparse.csgraph import shortest_path
+    src = [0, 1234, K - 1]
+    hops = shortest_path(csr_matrix(adj.astype(np.int8)), unweighted=True, indices=src)
+    assert np.array_equal(T[src], hops.astype(np.float32))
 
 
 def test_topology_with_duplicate_nodes(som):
