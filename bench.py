@@ -69,7 +69,11 @@ def main() -> int:
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=2)
-    ap.add_argument("--workload", default="cfg1", choices=["cfg0", "cfg1", "cfg2", "cfg4"])
+    ap.add_argument("--workload", default="cfg1", choices=["cfg0", "cfg1", "cfg2", "cfg4", "scale"],
+                    help="cfg1 is the headline workload; 'scale' is the default point of the paper's speed runs "
+                         "(uniform data, Section 4.2.1), to be varied with --rows / --features / --grid")
+    ap.add_argument("--features", type=int, default=None, help="override the feature count D (scale workload)")
+    ap.add_argument("--grid", type=int, default=None, help="override the lattice side length, K = side^2 (scale workload)")
     ap.add_argument("--stream", default=None, choices=["pinned", "pageable"],
                     help="keep X in host memory and run som_epoch_host (the chunked loading path) instead")
     ap.add_argument("--chunk-rows", type=int, default=4_000_000)
@@ -89,7 +93,12 @@ def main() -> int:
     import paper_2604_26555_amd as pkg
     from synth import draw_initial_rows, linear_sigma, make_workload
 
-    wl = make_workload(args.workload, n=args.rows)
+    over = {}
+    if args.features:
+        over["d"] = args.features
+    if args.grid:
+        over.update(k=args.grid * args.grid, lattice=(args.grid, args.grid), sigma=(args.grid / 2.0, 1.0))
+    wl = make_workload(args.workload, n=args.rows, **over)
     t0 = time.time()
     X = wl.data().rows(0, wl.n)
     W0 = X[draw_initial_rows(wl.seed, wl.n, wl.k)].copy()
@@ -140,7 +149,7 @@ def main() -> int:
     traffic = None
     # measured off-line with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (scaled by a plain copy); see profiles/
     pmc = os.path.join(ROOT, "profiles", f"epoch_{wl.name}_hbm_traffic.md")
-    if os.path.exists(pmc) and args.rows is None:
+    if os.path.exists(pmc) and args.rows is None and not over:
         for line in open(pmc):
             if line.startswith("traffic_bytes_per_launch_bmu_kernel:"):
                 traffic = float(line.split(":")[1])

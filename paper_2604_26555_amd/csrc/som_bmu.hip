@@ -45,10 +45,30 @@ constexpr int stage_floats_for(int stride)
 // chunk.  One thread per element of the padded matrix (coalesced reads of W); the first kpad threads also compute
 // their node's norm in float64.
 // ---------------------------------------------------------------------------------------------------------
+// centre[f] = mean over nodes of W[k][f], f < D; zero up to the next multiple of 64.  Any vector would do (distances do not change when the same vector is
+// taken off samples and weights); the mean keeps |w_k - centre| as small as the spread of the map.
+__global__ void __launch_bounds__(1024) bmu_centre_kernel(const float* __restrict__ W, int K, int D, float* __restrict__ centre)
+{
+    __shared__ double part[16][64];
+    const int fl = threadIdx.x & 63, grp = threadIdx.x >> 6;
+    const int f = blockIdx.x * 64 + fl;
+    double s = 0.0;
+    if (f < D)
+        for (int k = grp; k < K; k += 16) s += (double)W[(size_t)k * D + f];
+    part[grp][fl] = s;
+    __syncthreads();
+    if (grp == 0) {                       // the padding up to the next multiple of 64 entries is zeroed
+        double t = 0.0;
+        for (int q = 0; q < 16; ++q) t += part[q][fl];
+        centre[f] = (f < D) ? (float)(t / K) : 0.0f;
+    }
+}
+
 __global__ void __launch_bounds__(256) bmu_prep_kernel(const float* __restrict__ W, int K, int D, int kpad, int stride,
-                                                       int nch, int stage_floats, float* __restrict__ stage,
-                                                       float* __restrict__ wt, unsigned int* __restrict__ scal,
-                                                       double* __restrict__ qe, int32_t* __restrict__ small)
+                                                       int nch, int stage_floats, const float* __restrict__ centre,
+                                                       float* __restrict__ stage, float* __restrict__ wt,
+                                                       unsigned int* __restrict__ scal, double* __restrict__ qe,
+                                                       int32_t* __restrict__ small)
 {
     const int e = blockIdx.x * 256 + threadIdx.x;
     const int cols = nch * stride;
@@ -61,15 +81,16 @@ __global__ void __launch_bounds__(256) bmu_prep_kernel(const float* __restrict__
         const bool real = k < K && fl < stride - 1 && f < D;
         const float v = real ? W[(size_t)k * D + f] : 0.0f;
         const int st = k / kNodesPerStage, r = k % kNodesPerStage;
-        stage[((size_t)st * nch + ch) * stage_floats + (size_t)r * stride + fl] = v;
+        stage[((size_t)st * nch + ch) * stage_floats + (size_t)r * stride + fl] = real ? v - centre[f] : 0.0f;
         if (fl < stride - 1 && f < D) wt[(size_t)f * kpad + k] = v;
     }
     if (e < kpad) {
+        // squared norm of the centred row exactly as the stage holds it (float32 differences), summed in float64
         const int k = e;
         double nrm = 0.0;
         if (k < K)
             for (int f = 0; f < D; ++f) {
-                const double v = (double)W[(size_t)k * D + f];
+                const double v = (double)(W[(size_t)k * D + f] - centre[f]);
                 nrm += v * v;
             }
         const int st = k / kNodesPerStage, r = k % kNodesPerStage;
@@ -130,6 +151,13 @@ __global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2
     const int g = lane >> 5;
     const int64_t wave0 = ((int64_t)blockIdx.x * kWavesPerGroup + wave) * (MS * 32);
 
+    // centre[2 s + g]: both candidates are read through wave-uniform addresses (scalar loads), the lane picks one
+    // (the array is zero-padded to a multiple of 64 entries, so no index needs a bound)
+    auto centre_of = [&](int s) {
+        const float c0 = a.centre[2 * s], c1 = a.centre[2 * s + 1];
+        return g ? c1 : c0;
+    };
+
     // ---- this wavefront's samples, kept in registers
     float x[MS][STEPS];
     bool valid[MS];
@@ -143,7 +171,9 @@ __global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2
 #pragma unroll
         for (int s = 0; s < STEPS; ++s) {
             const int f = 2 * s + g;
-            x[mb][s] = (f < a.D) ? xr[f] : 0.0f;
+            // Unconditional load through a clamped index.  Beyond D the value is a copy of the last feature; it
+            // meets zero weights in the stage rows, and the epilogue masks it out of the norms.
+            x[mb][s] = xr[f < a.D ? f : a.D - 1];
         }
     }
 
@@ -165,6 +195,11 @@ __global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2
         float4 first[PRE];
 #pragma unroll
         for (int p = 0; p < PRE; ++p) first[p] = src4[tid + p * kThreads];
+        // the samples are centred only now, with the first stage's loads already on their way
+#pragma unroll
+        for (int mb = 0; mb < MS; ++mb)
+#pragma unroll
+            for (int s = 0; s < STEPS; ++s) x[mb][s] -= centre_of(s);
 #pragma unroll
         for (int p = 0; p < PRE; ++p) lds4[tid + p * kThreads] = first[p];
     }
@@ -190,15 +225,17 @@ __global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2
         const float* wbuf = lds + buf * STAGE_FLOATS;
         const float* nbuf = wbuf + kNodesPerStage * STRIDE;
 
-        // fully unrolled: with the stage body in one basic block the prefetch loads above stay ahead of the MFMAs
-#pragma unroll
-        for (int nb = 0; nb < kNodesPerStage / 32; ++nb) {
-            const float* wrow = wbuf + (nb * 32 + j) * STRIDE + g;
-            float wa[STEPS];
+        // Fully unrolled: with the stage body in one basic block the prefetch loads above stay ahead of the MFMAs.
+        // The LDS reads of node block nb + 1 (weights and -|w|^2/2) are written into the MFMA sequence of block nb,
+        // one read per pair of MFMAs, and pinned there: left alone the scheduler sometimes gathers all reads of a
+        // block in front of its first MFMA, and the matrix pipe then idles for an LDS round trip per block.
+        float wa[STEPS];
+        floatx16 c;
+        {
+            const float* wrow = wbuf + j * STRIDE + g;
 #pragma unroll
             for (int s = 0; s < STEPS; ++s) wa[s] = wrow[2 * s];
-            const float4* nh = reinterpret_cast<const float4*>(nbuf + nb * 32 + 4 * g);
-            floatx16 c;
+            const float4* nh = reinterpret_cast<const float4*>(nbuf + 4 * g);
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
                 const float4 t = nh[2 * q];
@@ -207,6 +244,15 @@ __global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2
                 c[4 * q + 2] = t.z;
                 c[4 * q + 3] = t.w;
             }
+        }
+#pragma unroll
+        for (int nb = 0; nb < kNodesPerStage / 32; ++nb) {
+            constexpr int NB = kNodesPerStage / 32;
+            const int nx = (nb + 1 < NB) ? nb + 1 : nb;                    // the last block re-reads itself (unused)
+            const float* wnext = wbuf + (nx * 32 + j) * STRIDE + g;
+            const float4* nhnext = reinterpret_cast<const float4*>(nbuf + nx * 32 + 4 * g);
+            float wn[STEPS];
+            floatx16 cn;
             floatx16 acc[MS];
 #pragma unroll
             for (int mb = 0; mb < MS; ++mb) acc[mb] = c;
@@ -215,6 +261,18 @@ __global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2
 #pragma unroll
                 for (int mb = 0; mb < MS; ++mb)
                     acc[mb] = __builtin_amdgcn_mfma_f32_32x32x2f32(wa[s], x[mb][s], acc[mb], 0, 0, 0);
+                if (nb + 1 < NB) {
+                    wn[s] = wnext[2 * s];
+                    if (s < 4) {
+                        const float4 t = nhnext[2 * s];
+                        cn[4 * s + 0] = t.x;
+                        cn[4 * s + 1] = t.y;
+                        cn[4 * s + 2] = t.z;
+                        cn[4 * s + 3] = t.w;
+                    }
+                    __builtin_amdgcn_sched_group_barrier(0x008, MS, 0);    // MS MFMAs
+                    __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);     // one LDS read
+                }
             }
             // fold the 16 scores of each block into the running triple: four VALU instructions per score
             const int tile = st * (kNodesPerStage / 32) + nb;
@@ -230,6 +288,11 @@ __global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2
                 }
                 tsel[mb] = (best[mb] > before) ? tile : tsel[mb];
             }
+            if (nb + 1 < NB) {
+#pragma unroll
+                for (int s = 0; s < STEPS; ++s) wa[s] = wn[s];
+                c = cn;
+            }
         }
 
         {
@@ -244,7 +307,10 @@ __global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2
 
     // ---- join the two half-wavefronts, then lane (j, g) finishes block mp + g
     const float wmax2 = __uint_as_float(a.scal[0]);
-    const float rel = (float)(2 * STEPS + 8) * 5.9604645e-08f;    // (roundings per score + slack) * 2^-24
+    const float wmax = sqrtf(wmax2) * 1.000001f;
+    // two scores, each with two roundings per MFMA step (k = 2) and one in -|w|^2/2; the roundings of x - centre
+    // and w - centre move a score difference by at most 2 and 4 more units: (4 STEPS + 8) * 2^-24, plus slack
+    const float rel = (float)(4 * STEPS + 12) * 5.9604645e-08f;
     double qs = 0.0, qs2 = 0.0;
 #pragma unroll
     for (int mp = 0; mp < MS; mp += 2) {
@@ -264,15 +330,17 @@ __global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2
             const float bst = other ? ob : best[mb];
             node = other ? on : node;
             node = node < a.K ? node : a.K - 1;
-            // squared norm of the sample and exact squared distance to the winner, half the features per lane
+            // squared norm of the centred sample and squared distance to the winner (both centred the same way),
+            // half the features per lane
             float xn = 0.f, part = 0.f;
             const float* wr = a.W + (size_t)node * a.D;
 #pragma unroll
             for (int s = 0; s < STEPS; ++s) {
                 const int f = 2 * s + g;
-                const float wv = (f < a.D) ? wr[f] : 0.0f;
-                const float df = x[mb][s] - wv;
-                xn = fmaf(x[mb][s], x[mb][s], xn);
+                const float wv = wr[f < a.D ? f : a.D - 1] - centre_of(s);
+                const float xm = (f < a.D) ? x[mb][s] : 0.0f;
+                const float df = (f < a.D) ? x[mb][s] - wv : 0.0f;
+                xn = fmaf(xm, xm, xn);
                 part = fmaf(df, df, part);
             }
             xn += __shfl_xor(xn, 32);
@@ -288,9 +356,13 @@ __global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2
         }
         if (r_valid) {
             const int64_t i = wave0 + (mp + g) * 32 + j;
-            // magnitude bound of every partial sum of the score: |w|^2/2 + sum |x_d w_d| <= |x|^2/2 + |w|^2
-            const float bound = (0.5f * r_xn + wmax2) * rel;
-            const bool close = !((r_best - r_second) > bound);
+            // magnitude bound of every partial sum of the score: |w|^2/2 + |sum x_d w_d| <= |w|^2/2 + |x| |w|
+            const float xl = sqrtf(r_xn);
+            const float bound = (xl * wmax + 0.5f * wmax2) * rel;
+            // the two centring roundings leave an error of 2^-23 d (|x| + |w|) in d^2: hand the few samples that
+            // sit within 2^-9 (|x| + |w|) of their node to the exact pass, which works on the values as given
+            const float tiny = (xl + wmax) * (xl + wmax) * 3.8146973e-06f;
+            const bool close = !((r_best - r_second) > bound) || r_part < tiny;
             a.bmu[i] = r_node;
             if (a.d2) a.d2[i] = r_part;
             if (close && a.K > 1) {
@@ -365,7 +437,9 @@ __global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2
 #pragma unroll
         for (int s = 0; s < STEPS; ++s) {
             const int f = 64 * ch + 2 * s + g;
-            x[s] = (f < a.D) ? xr[f] : 0.0f;
+            // wave-uniform addresses (scalar loads); the array is zero-padded to a multiple of 64 entries
+            const float c0 = a.centre[64 * ch + 2 * s], c1 = a.centre[64 * ch + 2 * s + 1];
+            x[s] = xr[f < a.D ? f : a.D - 1] - (g ? c1 : c0);      // beyond D: meets zero weights
         }
         __builtin_amdgcn_sched_barrier(0);
         const float* wbuf = lds + buf * STAGE_FLOATS;
@@ -426,8 +500,9 @@ __global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2
     const float* wr = a.W + (size_t)node * a.D;
     for (int f = g; f < a.D; f += 2) {
         const float xv = xr[f];
+        const float xc = xv - a.centre[f];
         const float df = xv - wr[f];
-        xn = fmaf(xv, xv, xn);
+        xn = fmaf(xc, xc, xn);
         part = fmaf(df, df, part);
     }
     xn += __shfl_xor(xn, 32);
@@ -435,8 +510,9 @@ __global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2
     double qs = 0.0, qs2 = 0.0;
     if (valid && g == 0) {
         const float wmax2 = __uint_as_float(a.scal[0]);
-        const float rel = (float)(2 * STEPS * nch + 8) * 5.9604645e-08f;    // (roundings per score + slack) * 2^-24
-        const float bound = (0.5f * xn + wmax2) * rel;
+        const float wmax = sqrtf(wmax2) * 1.000001f;
+        const float rel = (float)(4 * STEPS * nch + 12) * 5.9604645e-08f;   // as in bmu_kernel, STEPS * nch steps per score
+        const float bound = (sqrtf(xn) * wmax + 0.5f * wmax2) * rel;
         const bool close = !((bst - sec) > bound);
         a.bmu[i] = node;
         if (a.d2) a.d2[i] = part;
@@ -625,7 +701,8 @@ int bmu_prepare(som_ctx* ctx, const float* W, int32_t K, int32_t D, BmuPrep* out
     const int kpad = ((K + kNodesPerStage - 1) / kNodesPerStage) * kNodesPerStage;
     const size_t stage_bytes = (size_t)(kpad / kNodesPerStage) * nch * stage_floats_for(stride) * sizeof(float);
     const size_t wt_bytes = (size_t)D * kpad * sizeof(float);
-    const size_t need = stage_bytes + wt_bytes + 256;
+    const size_t centre_bytes = (((size_t)D * sizeof(float)) + 255) / 256 * 256;
+    const size_t need = stage_bytes + wt_bytes + centre_bytes + 256;
     if (need > ctx->prep_bytes) {
         if (ctx->prep_blob) {
             if (int rc = check_hip(ctx, hipStreamSynchronize(ctx->stream), "sync before workspace growth")) return rc;
@@ -643,15 +720,17 @@ int bmu_prepare(som_ctx* ctx, const float* W, int32_t K, int32_t D, BmuPrep* out
     out->scal = (unsigned int*)base;
     out->stage = (float*)(base + 256);
     out->wt = (float*)(base + 256 + stage_bytes);
+    out->centre = (float*)(base + 256 + stage_bytes + wt_bytes);
     out->kpad = kpad;
     out->steps = steps;
     out->stride = stride;
     out->nch = nch;
     out->calls = 0;
     if (int rc = launch_fill_zero(ctx, out->scal, 32)) return rc;
+    hipLaunchKernelGGL(bmu_centre_kernel, dim3((D + 63) / 64), dim3(1024), 0, ctx->stream, W, K, D, out->centre);
     const long long elems = (long long)kpad * nch * stride;
     hipLaunchKernelGGL(bmu_prep_kernel, dim3((unsigned)((elems + 255) / 256)), dim3(256), 0, ctx->stream, W, K, D, kpad,
-                       stride, nch, stage_floats_for(stride), out->stage, out->wt, out->scal, qe, small);
+                       stride, nch, stage_floats_for(stride), out->centre, out->stage, out->wt, out->scal, qe, small);
     return check_hip(ctx, hipGetLastError(), "bmu_prep launch");
 }
 
@@ -725,6 +804,7 @@ int bmu_run(som_ctx* ctx, BmuPrep& prep, BmuArgs a)
     a.kpad = prep.kpad;
     a.stage = prep.stage;
     a.wt = prep.wt;
+    a.centre = prep.centre;
     a.scal = prep.scal;
     a.recheck = ctx->recheck;
     // the list length restarts for every call (chunk): calls alternate between two counters, and each call's

@@ -16,8 +16,9 @@ constexpr int kMaxStepsResident = 32; // BMU kernel keeps a sample's features in
 
 struct BmuPrep {
     float* stage = nullptr;        // [Kpad / 128][nch] blobs: 128 padded weight rows of a chunk, then -|w|^2 / 2
-    float* wt = nullptr;           // [D][Kpad] transposed weights
-    unsigned int* scal = nullptr;  // [0] = bits of max_k |w_k|^2, [1], [2] = recheck-list length (alternating calls), [3] = total
+    float* wt = nullptr;           // [D][Kpad] transposed weights (as given, not centred)
+    float* centre = nullptr;       // [D] column means of W; stage rows and sample registers hold values minus this
+    unsigned int* scal = nullptr;  // [0] = bits of max_k |w_k - centre|^2, [1], [2] = recheck-list length (alternating calls), [3] = total
     int kpad = 0, steps = 0, stride = 0;
     int nch = 1;                   // feature chunks of 2 * steps features (1 unless D > 64)
     int calls = 0;                 // bmu_run calls served by this preparation (selects the list counter)
@@ -32,6 +33,7 @@ struct BmuArgs {
     const float* W;          // caller's dense K x D weights (exact distances)
     const float* stage;      // BmuPrep::stage
     const float* wt;         // BmuPrep::wt
+    const float* centre;     // BmuPrep::centre
     unsigned int* scal;      // BmuPrep::scal
     int32_t slot;            // which of scal[1], scal[2] this call counts into
     uint32_t* recheck;       // [m] sample positions to re-decide

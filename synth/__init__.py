@@ -4,11 +4,11 @@ This package produces *inputs only*: sample matrices, index lists, initial weigh
 radius values.  It contains none of the SOM arithmetic (no distances, no best-matching-unit search,
 no neighbourhood function, no update) so that the oracle and the HIP path stay independent.
 """
-from .mixtures import GaussianMixture, uniform01_rows
+from .mixtures import GaussianMixture, Uniform01, uniform01_rows
 from .configs import WORKLOADS, Workload, make_workload
 from .draws import linear_sigma, draw_initial_rows, draw_subset
 
 __all__ = [
-    "GaussianMixture", "uniform01_rows", "WORKLOADS", "Workload", "make_workload",
+    "GaussianMixture", "Uniform01", "uniform01_rows", "WORKLOADS", "Workload", "make_workload",
     "linear_sigma", "draw_initial_rows", "draw_subset",
 ]

@@ -1,4 +1,4 @@
-"""The five synthetic workloads (shapes, distributions, radii) the build is measured and tested on.
+"""The synthetic workloads (shapes, distributions, radii) the build is measured and tested on.
 
 Each entry only *describes inputs*: which mixture, how many rows, which lattice shape or graph kind, the
 radius endpoints and epoch count.  The distance matrices themselves are built by whoever consumes the
@@ -9,7 +9,7 @@ from __future__ import annotations
 from dataclasses import dataclass, field
 from typing import Optional, Tuple
 
-from .mixtures import GaussianMixture
+from .mixtures import GaussianMixture, Uniform01
 
 
 @dataclass(frozen=True)
@@ -26,7 +26,9 @@ class Workload:
     seed: int = 1000
     mixture: dict = field(default_factory=dict)
 
-    def data(self) -> GaussianMixture:
+    def data(self):
+        if self.mixture.get("uniform"):
+            return Uniform01(self.seed, self.d)
         return GaussianMixture(self.seed, self.d, **self.mixture)
 
 
@@ -46,6 +48,10 @@ WORKLOADS = {
     # 32x32 rectangular lattice, 1e9 rows streamed from host memory in chunks
     "cfg4": Workload("cfg4", 1_000_000_000, 50, 1024, "rect", (32, 32), (16.0, 1.0), 10, seed=1004,
                      mixture=dict(n_comp=100, std=(0.2, 3.0))),
+    # default point of the paper's speed runs (Section 4.2.1): uniform [0,1) matrix, 32x32 grid, 10 iterations;
+    # one axis at a time is varied from here (Supplementary Table S3)
+    "scale": Workload("scale", 10_000_000, 50, 1024, "hex", (32, 32), (16.0, 1.0), 10, seed=1005,
+                      mixture=dict(uniform=True)),
 }
 
 

@@ -91,3 +91,20 @@ def uniform01_rows(seed: int, start: int, stop: int, d: int) -> np.ndarray:
             out[lo - start:hi - start] = blk[lo - b * BLOCK_ROWS:hi - b * BLOCK_ROWS]
         b += 1
     return out
+
+
+class Uniform01:
+    """U[0,1) rows behind the same interface as GaussianMixture (``rows``, ``fill``)."""
+
+    def __init__(self, seed: int, d: int):
+        self.seed, self.d = int(seed), int(d)
+
+    def rows(self, start: int, stop: int) -> np.ndarray:
+        return uniform01_rows(self.seed, start, stop, self.d)
+
+    def fill(self, out: np.ndarray, start: int = 0) -> np.ndarray:
+        step = BLOCK_ROWS * 16
+        for lo in range(0, out.shape[0], step):
+            hi = min(out.shape[0], lo + step)
+            out[lo:hi] = self.rows(start + lo, start + hi)
+        return out
