@@ -37,6 +37,7 @@ constexpr int kMThreads = 512;
 constexpr int kMWaves = kMThreads / 64;
 constexpr int kMTile = 256;        // rows per LDS tile; tile positions fit a byte
 constexpr int kMFlushRows = 16384;
+constexpr int kMWindow = 63;       // features per pass: 63 + the count column fill two 32-column blocks
 
 // NBW = node blocks per wavefront, FB = feature blocks (of 32 columns, the count column included)
 template <typename SliceT, int NBW, int FB>
@@ -221,8 +222,10 @@ __global__ void __launch_bounds__(kMThreads) accumulate_mfma_kernel(const float*
 template <typename SliceT>
 __global__ void __launch_bounds__(256) accumulate_mfma_reduce_kernel(const SliceT* __restrict__ part, int K, int D,
                                                                      int ranges, int zero_first, double* __restrict__ S,
-                                                                     unsigned long long* __restrict__ n)
+                                                                     int ldS, unsigned long long* __restrict__ n)
 {
+    // D = columns of this launch's feature window, S points at the window's first column, ldS = row length of S;
+    // n may be null (the counts are taken from the first window only)
     __shared__ double qsum[4][64];
     const int q = threadIdx.x >> 6, l = threadIdx.x & 63;
     const int DS = ((D + 1 + 31) / 32) * 32;              // padded slice row (only columns 0..D carry data)
@@ -241,8 +244,8 @@ __global__ void __launch_bounds__(256) accumulate_mfma_reduce_kernel(const Slice
         const double tot = ((qsum[0][l] + qsum[1][l]) + qsum[2][l]) + qsum[3][l];
         const int k = c / DS, f = c % DS;
         if (f < D)
-            S[(size_t)k * D + f] = (zero_first ? 0.0 : S[(size_t)k * D + f]) + tot;
-        else if (f == D)
+            S[(size_t)k * ldS + f] = (zero_first ? 0.0 : S[(size_t)k * ldS + f]) + tot;
+        else if (f == D && n)
             n[k] = (zero_first ? 0ull : n[k]) + (unsigned long long)(tot + 0.5);
     }
 }
@@ -280,15 +283,19 @@ static int dispatch_mfma(som_ctx* ctx, int nbw, int fb, const float* X, int32_t 
 }
 
 // Returns 1 when the shape is not served by this path (the caller then uses the LDS-atomic kernel), SOM_OK on
-// success, a negative code on failure.  Served: D + 1 <= 64 columns and up to 8 accumulator blocks per wavefront.
+// success, a negative code on failure.  Served: up to 8 accumulator blocks per wavefront (K <= 1024 when a feature
+// window needs two column blocks, K <= 2048 when D <= 31); D above 63 goes through in windows of 63 features.
 int accumulate_mfma_run(som_ctx* ctx, const float* X, int32_t D, int64_t ldx, const uint32_t* idx, int64_t m,
                         const int32_t* bmu, int32_t K, double* S, unsigned long long* n, bool zero_first)
 {
-    const int fb = (D + 1 + 31) / 32;
+    // feature windows of at most 63 columns (+ the count column = two blocks of 32); one window after the other
+    // through the same slices
+    const int window = (D <= kMWindow) ? D : kMWindow;
+    const int fb = (window + 1 + 31) / 32;
     const int nblocks = (K + 31) / 32;
     int nbw = 1;
     while (nbw * kMWaves < nblocks) nbw *= 2;
-    if (fb > 2 || nbw * fb > 8 || m <= 0) return 1;
+    if (nbw * fb > 8 || m <= 0) return 1;
     // one workgroup per compute unit, at least one tile each
     int64_t ranges = 256;
     const int64_t by_rows = (m + kMTile - 1) / kMTile;
@@ -311,20 +318,27 @@ int accumulate_mfma_run(som_ctx* ctx, const float* X, int32_t D, int64_t ldx, co
         }
         ctx->acc_bytes = need;
     }
-    const int cells = K * fb * 32;
-    const dim3 rgrid((cells + 63) / 64);
-    if (single_flush) {
-        float* part = (float*)ctx->acc_blob;
-        if (int rc = dispatch_mfma<float>(ctx, nbw, fb, X, D, ldx, idx, m, bmu, K, ranges, rows_per_range, part)) return rc;
-        hipLaunchKernelGGL(accumulate_mfma_reduce_kernel<float>, rgrid, dim3(256), 0, ctx->stream, part, K, D, (int)ranges,
-                           zero_first ? 1 : 0, S, n);
-    } else {
-        double* part = (double*)ctx->acc_blob;
-        if (int rc = dispatch_mfma<double>(ctx, nbw, fb, X, D, ldx, idx, m, bmu, K, ranges, rows_per_range, part)) return rc;
-        hipLaunchKernelGGL(accumulate_mfma_reduce_kernel<double>, rgrid, dim3(256), 0, ctx->stream, part, K, D, (int)ranges,
-                           zero_first ? 1 : 0, S, n);
+    for (int f0 = 0; f0 < D; f0 += window) {
+        const int dw = (D - f0 < window) ? D - f0 : window;
+        const int fbw = (dw + 1 + 31) / 32;
+        const dim3 rgrid((K * fbw * 32 + 63) / 64);
+        unsigned long long* nw = (f0 == 0) ? n : nullptr;
+        if (single_flush) {
+            float* part = (float*)ctx->acc_blob;
+            if (int rc = dispatch_mfma<float>(ctx, nbw, fbw, X + f0, dw, ldx, idx, m, bmu, K, ranges, rows_per_range, part))
+                return rc;
+            hipLaunchKernelGGL(accumulate_mfma_reduce_kernel<float>, rgrid, dim3(256), 0, ctx->stream, part, K, dw,
+                               (int)ranges, zero_first ? 1 : 0, S + f0, D, nw);
+        } else {
+            double* part = (double*)ctx->acc_blob;
+            if (int rc = dispatch_mfma<double>(ctx, nbw, fbw, X + f0, dw, ldx, idx, m, bmu, K, ranges, rows_per_range, part))
+                return rc;
+            hipLaunchKernelGGL(accumulate_mfma_reduce_kernel<double>, rgrid, dim3(256), 0, ctx->stream, part, K, dw,
+                               (int)ranges, zero_first ? 1 : 0, S + f0, D, nw);
+        }
+        if (int rc = check_hip(ctx, hipGetLastError(), "accumulate (MFMA) reduce launch")) return rc;
     }
-    return check_hip(ctx, hipGetLastError(), "accumulate (MFMA) reduce launch");
+    return SOM_OK;
 }
 
 } // namespace som

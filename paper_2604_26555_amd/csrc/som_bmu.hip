@@ -457,10 +457,19 @@ __global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2
                     acc[nb][4 * t + 3] = v.w;
                 }
             }
+            // The chunk's 64-feature partial product is summed on its own, from zero, and then added to the
+            // running score: every rounding inside the chunk is relative to the chunk's own magnitude
+            // |x_chunk| |w_chunk|, and those add up to at most |x| |w| over the chunks (Cauchy-Schwarz), so the
+            // error bound grows with 2 STEPS + nch roundings per score instead of 2 STEPS nch.
             const float* wrow = wbuf + (nb * 32 + j) * STRIDE + g;
+            floatx16 part;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) part[r] = 0.0f;
 #pragma unroll
             for (int s = 0; s < STEPS; ++s)
-                acc[nb] = __builtin_amdgcn_mfma_f32_32x32x2f32(wrow[2 * s], x[s], acc[nb], 0, 0, 0);
+                part = __builtin_amdgcn_mfma_f32_32x32x2f32(wrow[2 * s], x[s], part, 0, 0, 0);
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[nb][r] += part[r];
             if (ch == nch - 1) {
                 const int tile = st * NBS + nb;
                 const float before = best;
@@ -511,7 +520,9 @@ __global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2
     if (valid && g == 0) {
         const float wmax2 = __uint_as_float(a.scal[0]);
         const float wmax = sqrtf(wmax2) * 1.000001f;
-        const float rel = (float)(4 * STEPS * nch + 12) * 5.9604645e-08f;   // as in bmu_kernel, STEPS * nch steps per score
+        // per score: 2 STEPS roundings inside the chunks (see the stage loop), nch chunk additions, one for
+        // -|w|^2/2; two scores, plus the centring roundings and slack as in bmu_kernel
+        const float rel = (float)(4 * STEPS + 2 * nch + 12) * 5.9604645e-08f;
         const float bound = (sqrtf(xn) * wmax + 0.5f * wmax2) * rel;
         const bool close = !((bst - sec) > bound);
         a.bmu[i] = node;
