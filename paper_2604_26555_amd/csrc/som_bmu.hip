@@ -77,7 +77,9 @@ __global__ void __launch_bounds__(256) bmu_prep_kernel(const float* __restrict__
     if (e < kpad * cols) {
         const int k = e / cols, c = e - k * cols;
         const int ch = c / stride, fl = c - ch * stride;
-        const int f = ch * (stride - 1) + fl;
+        // stage column fl = 2 s + g feeds MFMA step s, half-wavefront g.  One chunk (D <= 64): feature fl.  Several
+        // chunks: feature 32 g + s of the chunk, so that a lane's 32 features are contiguous in a sample row.
+        const int f = (nch == 1) ? fl : ch * (stride - 1) + (fl & 1) * 32 + (fl >> 1);
         const bool real = k < K && fl < stride - 1 && f < D;
         const float v = real ? W[(size_t)k * D + f] : 0.0f;
         const int st = k / kNodesPerStage, r = k % kNodesPerStage;
@@ -423,6 +425,17 @@ __global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2
 
     floatx16 acc[NBS];
     int st = 0, ch = 0;
+    // centred features of the current chunk; centre[] is read through wave-uniform addresses (scalar loads) and is
+    // zero-padded to a multiple of 64 entries
+    // Lane (j, g) holds features 32 g + s (s = 0..31) of the chunk: contiguous, so whole chunks of suitably aligned
+    // rows come in as eight 16-byte loads per lane instead of 32 scattered dwords.
+    const bool wide_loads = (reinterpret_cast<uintptr_t>(a.X) % 16 == 0) && (a.ldx % 4 == 0);
+    float x[STEPS];
+#pragma unroll
+    for (int s = 0; s < STEPS; ++s) {
+        const int f = 32 * g + s;
+        x[s] = xr[f < a.D ? f : a.D - 1] - a.centre[f];            // centre[] is zero-padded to whole chunks
+    }
     for (int q = 0; q < nq; ++q) {
         const int buf = q & 1;
         float4 pre0, pre1, pre2, pre3, pre4, pre5, pre6, pre7, pre8;
@@ -433,13 +446,38 @@ __global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2
             pre3 = s4[3 * kThreads]; pre4 = s4[4 * kThreads]; pre5 = s4[5 * kThreads];
             pre6 = s4[6 * kThreads]; pre7 = s4[7 * kThreads]; pre8 = s4[8 * kThreads];
         }
-        float x[STEPS];
+        // the samples' next chunk travels to registers during this chunk's arithmetic, like the next stage blob
+        // (and with them the matching entries of the centre vector: vector loads cost no matrix-pipe time, a
+        // select between two scalar values per entry would)
+        float xn[STEPS], cn[STEPS];
+        {
+            const int chn = (ch + 1 == nch) ? 0 : ch + 1;
+            const float4* cc = reinterpret_cast<const float4*>(a.centre + 64 * chn + 32 * g);
 #pragma unroll
-        for (int s = 0; s < STEPS; ++s) {
-            const int f = 64 * ch + 2 * s + g;
-            // wave-uniform addresses (scalar loads); the array is zero-padded to a multiple of 64 entries
-            const float c0 = a.centre[64 * ch + 2 * s], c1 = a.centre[64 * ch + 2 * s + 1];
-            x[s] = xr[f < a.D ? f : a.D - 1] - (g ? c1 : c0);      // beyond D: meets zero weights
+            for (int t = 0; t < STEPS / 4; ++t) {
+                const float4 v = cc[t];
+                cn[4 * t + 0] = v.x;
+                cn[4 * t + 1] = v.y;
+                cn[4 * t + 2] = v.z;
+                cn[4 * t + 3] = v.w;
+            }
+            if (wide_loads && 64 * chn + 64 <= a.D) {
+                const float4* xc = reinterpret_cast<const float4*>(xr + 64 * chn + 32 * g);
+#pragma unroll
+                for (int t = 0; t < STEPS / 4; ++t) {
+                    const float4 v = xc[t];
+                    xn[4 * t + 0] = v.x;
+                    xn[4 * t + 1] = v.y;
+                    xn[4 * t + 2] = v.z;
+                    xn[4 * t + 3] = v.w;
+                }
+            } else {
+#pragma unroll
+                for (int s = 0; s < STEPS; ++s) {
+                    const int f = 64 * chn + 32 * g + s;
+                    xn[s] = xr[f < a.D ? f : a.D - 1];             // beyond D: meets zero weights
+                }
+            }
         }
         __builtin_amdgcn_sched_barrier(0);
         const float* wbuf = lds + buf * STAGE_FLOATS;
@@ -494,6 +532,8 @@ __global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2
             ch = 0;
             ++st;
         }
+#pragma unroll
+        for (int s = 0; s < STEPS; ++s) x[s] = xn[s] - cn[s];
     }
 
     // ---- join the two half-wavefronts; squared norm and exact winner distance from memory, half the features each
