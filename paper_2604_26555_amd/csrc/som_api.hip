@@ -115,6 +115,8 @@ int som_create(som_ctx** out, int device, void* hip_stream)
     bool ok = hipStreamCreateWithFlags(&c->copy_stream, hipStreamNonBlocking) == hipSuccess;
     ok = ok && hipMalloc((void**)&c->qe, 2 * sizeof(double)) == hipSuccess;
     ok = ok && hipMalloc((void**)&c->small, 64) == hipSuccess;
+    ok = ok && hipMalloc((void**)&c->qe_part, kQeSlots * 2 * sizeof(double)) == hipSuccess;
+    ok = ok && hipMemset(c->qe_part, 0, kQeSlots * 2 * sizeof(double)) == hipSuccess;
     ok = ok && hipHostMalloc(&c->host_small, 256, hipHostMallocDefault) == hipSuccess;
     for (int i = 0; i < 2 && ok; ++i) {
         ok = ok && hipEventCreateWithFlags(&c->ev_copied[i], hipEventDisableTiming) == hipSuccess;
@@ -157,6 +159,7 @@ void som_destroy(som_ctx* c)
     if (c->n) (void)hipFree(c->n);
     if (c->qe) (void)hipFree(c->qe);
     if (c->small) (void)hipFree(c->small);
+    if (c->qe_part) (void)hipFree(c->qe_part);
     if (c->host_small) (void)hipHostFree(c->host_small);
     for (auto& pr : c->prof_events) {
         (void)hipEventDestroy(pr.first);

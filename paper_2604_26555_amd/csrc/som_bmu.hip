@@ -123,6 +123,34 @@ __device__ __forceinline__ double wave_sum(double v)
     return v;
 }
 
+// Sum of distances and squared distances of a workgroup's samples -> one of kQeSlots partial-sum slots.  Every
+// wavefront adding to the same two words would serialise tens of thousands of atomics on one address; one pair
+// per workgroup spread over 256 slots does not show in the kernel time.  Called by all threads of the workgroup.
+__device__ __forceinline__ void group_qe_add(double* __restrict__ part, double qs, double qs2)
+{
+    __shared__ double wsum[16][2];
+    qs = wave_sum(qs);
+    qs2 = wave_sum(qs2);
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    if (lane == 0) {
+        wsum[wave][0] = qs;
+        wsum[wave][1] = qs2;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        double t0 = 0.0, t1 = 0.0;
+        for (int w = 0; w < (int)(blockDim.x >> 6); ++w) {
+            t0 += wsum[w][0];
+            t1 += wsum[w][1];
+        }
+        if (t0 != 0.0 || t1 != 0.0) {
+            const int slot = blockIdx.x & (kQeSlots - 1);
+            unsafeAtomicAdd(&part[2 * slot], t0);
+            unsafeAtomicAdd(&part[2 * slot + 1], t1);
+        }
+    }
+}
+
 // plain v_max_f32: the scores are never signalling NaNs worth quieting, and every VALU instruction here is paid
 // for in matrix time (float32 MFMA and the vector ALU share the same lanes)
 __device__ __forceinline__ float vmax(float a, float b)
@@ -163,6 +191,8 @@ __global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2
     // ---- this wavefront's samples, kept in registers
     float x[MS][STEPS];
     bool valid[MS];
+    // (Staging the workgroup's rows through LDS with coalesced 16-byte loads was measured against this direct
+    // gather and lost by 3 to 10 %: the gather is served by the vector L1, the staging adds two barriers.)
 #pragma unroll
     for (int mb = 0; mb < MS; ++mb) {
         const int64_t i = wave0 + mb * 32 + j;
@@ -376,14 +406,7 @@ __global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2
             }
         }
     }
-    if (a.qe) {
-        qs = wave_sum(qs);
-        qs2 = wave_sum(qs2);
-        if (lane == 0 && (qs != 0.0 || qs2 != 0.0)) {
-            unsafeAtomicAdd(&a.qe[0], qs);
-            unsafeAtomicAdd(&a.qe[1], qs2);
-        }
-    }
+    if (a.qe) group_qe_add(a.qe_part, qs, qs2);
 }
 
 // ---------------------------------------------------------------------------------------------------------
@@ -575,14 +598,7 @@ __global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2
             qs2 = (double)part;
         }
     }
-    if (a.qe) {
-        qs = wave_sum(qs);
-        qs2 = wave_sum(qs2);
-        if (lane == 0 && (qs != 0.0 || qs2 != 0.0)) {
-            unsafeAtomicAdd(&a.qe[0], qs);
-            unsafeAtomicAdd(&a.qe[1], qs2);
-        }
-    }
+    if (a.qe) group_qe_add(a.qe_part, qs, qs2);
 }
 
 // ---------------------------------------------------------------------------------------------------------
@@ -716,9 +732,32 @@ __global__ void __launch_bounds__(256) bmu_exact_kernel(const BmuArgs a)
             qs2 += (double)bd;
         }
     }
-    if (a.qe && tid < kExactGroup && (qs != 0.0 || qs2 != 0.0)) {
-        unsafeAtomicAdd(&a.qe[0], qs);
-        unsafeAtomicAdd(&a.qe[1], qs2);
+    if (a.qe) group_qe_add(a.qe_part, tid < kExactGroup ? qs : 0.0, tid < kExactGroup ? qs2 : 0.0);
+}
+
+// qe[0..1] += the call's partial sums, which are left zero for the next call
+__global__ void __launch_bounds__(kQeSlots) qe_finish_kernel(double* __restrict__ part, double* __restrict__ qe)
+{
+    __shared__ double w[kQeSlots / 64][2];
+    const int tid = threadIdx.x;
+    double s0 = part[2 * tid], s1 = part[2 * tid + 1];
+    part[2 * tid] = 0.0;
+    part[2 * tid + 1] = 0.0;
+    s0 = wave_sum(s0);
+    s1 = wave_sum(s1);
+    if ((tid & 63) == 0) {
+        w[tid >> 6][0] = s0;
+        w[tid >> 6][1] = s1;
+    }
+    __syncthreads();
+    if (tid == 0) {
+        double t0 = 0.0, t1 = 0.0;
+        for (int q = 0; q < kQeSlots / 64; ++q) {
+            t0 += w[q][0];
+            t1 += w[q][1];
+        }
+        qe[0] += t0;
+        qe[1] += t1;
     }
 }
 
@@ -858,6 +897,7 @@ int bmu_run(som_ctx* ctx, BmuPrep& prep, BmuArgs a)
     a.centre = prep.centre;
     a.scal = prep.scal;
     a.recheck = ctx->recheck;
+    a.qe_part = ctx->qe_part;
     // the list length restarts for every call (chunk): calls alternate between two counters, and each call's
     // exact pass clears the counter of the next one
     a.slot = 1 + (prep.calls & 1);
@@ -879,7 +919,11 @@ int bmu_run(som_ctx* ctx, BmuPrep& prep, BmuArgs a)
     if (rc) return rc;
     if (a.K > 1) {
         hipLaunchKernelGGL(bmu_exact_kernel, dim3(1024), dim3(256), 0, ctx->stream, a);
-        rc = check_hip(ctx, hipGetLastError(), "bmu exact-pass launch");
+        if ((rc = check_hip(ctx, hipGetLastError(), "bmu exact-pass launch"))) return rc;
+    }
+    if (a.qe) {
+        hipLaunchKernelGGL(qe_finish_kernel, dim3(1), dim3(kQeSlots), 0, ctx->stream, a.qe_part, a.qe);
+        rc = check_hip(ctx, hipGetLastError(), "quantisation-error reduction launch");
     }
     return rc;
 }

@@ -40,7 +40,10 @@ struct BmuArgs {
     int32_t* bmu;            // [m], always written
     float* d2;               // may be null
     double* qe;              // [2], accumulated (caller zeroes); may be null
+    double* qe_part;         // [kQeSlots][2] partial sums of this call (zero on entry, zeroed again by qe_finish_kernel)
 };
+
+constexpr int kQeSlots = 256;
 
 } // namespace som
 
@@ -63,6 +66,7 @@ struct som_ctx {
     size_t acc_bytes = 0;
     void* upd_blob = nullptr;      // influence matrix + split-k partials of the update
     size_t upd_bytes = 0;
+    double* qe_part = nullptr;     // [kQeSlots][2], zero between calls
     void* topo_blob = nullptr;     // node distances, adjacency matrix and lists of the topology rebuild
     size_t topo_bytes = 0;
     // epoch-internal accumulators
