@@ -164,6 +164,22 @@ __device__ __forceinline__ void group_qe_add(double* __restrict__ part, double q
     }
 }
 
+// Append sample i to the re-decision list for every lane with `push` set: one atomic per wavefront (the list
+// length is a single word; one atomic per listed sample serialises on it when a tenth of all samples is listed).
+// Called in converged control flow by all lanes of the wavefront.
+__device__ __forceinline__ void list_push(unsigned int* __restrict__ counter, uint32_t* __restrict__ list, bool push, int64_t i)
+{
+    const unsigned long long mask = __ballot(push);
+    if (mask == 0ull) return;
+    const int lane = threadIdx.x & 63;
+    const int leader = __ffsll((long long)mask) - 1;
+    unsigned int base = 0u;
+    if (lane == leader) base = atomicAdd(counter, (unsigned int)__popcll(mask));
+    base = __shfl(base, leader);
+    const unsigned int below = __builtin_amdgcn_mbcnt_hi((unsigned)(mask >> 32), __builtin_amdgcn_mbcnt_lo((unsigned)mask, 0));
+    if (push) list[base + below] = (uint32_t)i;
+}
+
 // plain v_max_f32: the scores are never signalling NaNs worth quieting, and every VALU instruction here is paid
 // for in matrix time (float32 MFMA and the vector ALU share the same lanes)
 __device__ __forceinline__ float vmax(float a, float b)
@@ -399,25 +415,23 @@ __global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2
                 r_valid = valid[mb];
             }
         }
+        const int64_t i = wave0 + (mp + g) * 32 + j;
+        // magnitude bound of every partial sum of the score: |w|^2/2 + |sum x_d w_d| <= |w|^2/2 + |x| |w|
+        const float xl = sqrtf(r_xn);
+        const float bound = (xl * wmax + 0.5f * wmax2) * rel;
+        // the two centring roundings leave an error of 2^-23 d (|x| + |w|) in d^2: hand the few samples that
+        // sit within 2^-9 (|x| + |w|) of their node to the exact pass, which works on the values as given
+        const float tiny = (xl + wmax) * (xl + wmax) * 3.8146973e-06f;
+        const bool close = r_valid && a.K > 1 && (!((r_best - r_second) > bound) || r_part < tiny);
         if (r_valid) {
-            const int64_t i = wave0 + (mp + g) * 32 + j;
-            // magnitude bound of every partial sum of the score: |w|^2/2 + |sum x_d w_d| <= |w|^2/2 + |x| |w|
-            const float xl = sqrtf(r_xn);
-            const float bound = (xl * wmax + 0.5f * wmax2) * rel;
-            // the two centring roundings leave an error of 2^-23 d (|x| + |w|) in d^2: hand the few samples that
-            // sit within 2^-9 (|x| + |w|) of their node to the exact pass, which works on the values as given
-            const float tiny = (xl + wmax) * (xl + wmax) * 3.8146973e-06f;
-            const bool close = !((r_best - r_second) > bound) || r_part < tiny;
             a.bmu[i] = r_node;
             if (a.d2) a.d2[i] = r_part;
-            if (close && a.K > 1) {
-                const unsigned int pos = atomicAdd(&a.scal[a.slot], 1u);
-                a.recheck[pos] = (uint32_t)i;
-            } else {
+            if (!close) {
                 qs += sqrt((double)r_part);
                 qs2 += (double)r_part;
             }
         }
+        list_push(&a.scal[a.slot], a.recheck, close, i);
     }
     if (a.qe) group_qe_add(a.qe_part, qs, qs2);
 }
@@ -593,24 +607,23 @@ __global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2
     xn += __shfl_xor(xn, 32);
     part += __shfl_xor(part, 32);
     double qs = 0.0, qs2 = 0.0;
-    if (valid && g == 0) {
-        const float wmax2 = __uint_as_float(a.scal[0]);
-        const float wmax = sqrtf(wmax2) * 1.000001f;
-        // per score: 2 STEPS roundings inside the chunks (see the stage loop), nch chunk additions, one for
-        // -|w|^2/2; two scores, plus the centring roundings and slack as in bmu_kernel
-        const float rel = (float)(4 * STEPS + 2 * nch + 12) * 5.9604645e-08f;
-        const float bound = (sqrtf(xn) * wmax + 0.5f * wmax2) * rel;
-        const bool close = !((bst - sec) > bound);
+    const float wmax2 = __uint_as_float(a.scal[0]);
+    const float wmax = sqrtf(wmax2) * 1.000001f;
+    // per score: 2 STEPS roundings inside the chunks (see the stage loop), nch chunk additions, one for
+    // -|w|^2/2; two scores, plus the centring roundings and slack as in bmu_kernel
+    const float rel = (float)(4 * STEPS + 2 * nch + 12) * 5.9604645e-08f;
+    const float bound = (sqrtf(xn) * wmax + 0.5f * wmax2) * rel;
+    const bool mine = valid && g == 0;
+    const bool close = mine && a.K > 1 && !((bst - sec) > bound);
+    if (mine) {
         a.bmu[i] = node;
         if (a.d2) a.d2[i] = part;
-        if (close && a.K > 1) {
-            const unsigned int pos = atomicAdd(&a.scal[a.slot], 1u);
-            a.recheck[pos] = (uint32_t)i;
-        } else {
+        if (!close) {
             qs = sqrt((double)part);
             qs2 = (double)part;
         }
     }
+    list_push(&a.scal[a.slot], a.recheck, close, i);
     if (a.qe) group_qe_add(a.qe_part, qs, qs2);
 }
 
