@@ -14,11 +14,13 @@
 // float32 MFMA and ordinary vector instructions occupy the same lanes (they do not overlap, not even across
 // wavefronts), so the fold is held to four vector instructions per score.
 //
-// Exactness.  float32 accumulation leaves an error of a few units in the last place of the score magnitude, so
-// a sample whose best two scores are closer than a rigorous bound of that error is put on a list and re-decided
-// by a second kernel that evaluates sum_d (x_d - w_kd)^2 directly for every node (lowest index wins ties).  For
-// all other samples the winner's squared distance is recomputed by direct differences as well, so the reported
-// distances never carry the cancellation error of the score form.
+// Exactness.  Scores are formed on centred values x - c, w - c (c = column means of W: distances are unchanged,
+// magnitudes shrink to the spread of the map).  float32 accumulation leaves an error of at most
+// (roundings) * 2^-24 * (|x - c| max|w - c| + max|w - c|^2 / 2) in a score, so a sample whose best two scores are
+// closer than that worst-case bound is put on a list and re-decided by a second kernel that evaluates
+// sum_d (x_d - w_kd)^2 directly, on the values as given, for every node (lowest index wins ties).  For all other
+// samples the winner's squared distance is recomputed by direct differences as well, so the reported distances
+// never carry the cancellation error of the score form.
 #include "som_internal.hpp"
 
 #include <hip/amd_detail/amd_hip_unsafe_atomics.h>
