@@ -108,6 +108,42 @@ def test_bmu_large_norm_small_gap(som):
     check_bmu(b_gpu.cpu().numpy(), None, X, W)
 
 
+def test_bmu_wide_rows_that_are_not_16_byte_aligned(som):
+    """D > 64 with a row stride that is no multiple of four floats and a base that is only 4-byte aligned: the
+    kernel must fall back from its 16-byte loads and still match."""
+    m, K, D = 700, 150, 131
+    X, W = problem(5, m, K, D)
+    buf = torch.full((m * 133 + 1,), 1e9, dtype=torch.float32, device="cuda")     # garbage between the rows
+    Xd = buf[1:].view(m, 133)[:, :D]
+    Xd.copy_(dev(X))
+    assert Xd.data_ptr() % 16 != 0 and Xd.stride(0) % 4 != 0
+    d2 = torch.empty(m, dtype=torch.float32, device="cuda")
+    b_gpu, _, _ = som.som_bmu(Xd, dev(W), d2=d2)
+    check_bmu(b_gpu.cpu().numpy(), d2.cpu().numpy(), X, W)
+
+
+@pytest.mark.parametrize("D", [20, 200])
+def test_bmu_far_from_the_origin(som, D):
+    """Data and weights sit at 1000 +- 0.01 per coordinate: |x|^2 is 10^6 D while neighbouring nodes differ by about
+    1e-4 in squared distance.  Only the centred score form (and the exact re-decision behind it) can tell them apart."""
+    rng = np.random.default_rng(D)
+    X = (1000.0 + rng.normal(size=(3000, D)) * 0.01).astype(np.float32)
+    W = (1000.0 + rng.normal(size=(200, D)) * 0.01).astype(np.float32)
+    b_gpu, _, _ = som.som_bmu(dev(X), dev(W))
+    check_bmu(b_gpu.cpu().numpy(), None, X, W)
+
+
+def test_bmu_sample_on_a_node(som):
+    """Samples that coincide with a node (distance exactly zero) or sit next to one far from the origin."""
+    rng = np.random.default_rng(9)
+    W = (50.0 + rng.normal(size=(64, 30))).astype(np.float32)
+    X = np.concatenate([W[:10], W[10:20] + np.float32(1e-4), (50.0 + rng.normal(size=(100, 30))).astype(np.float32)])
+    d2 = torch.empty(len(X), dtype=torch.float32, device="cuda")
+    b_gpu, _, _ = som.som_bmu(dev(X), dev(W), d2=d2)
+    check_bmu(b_gpu.cpu().numpy(), d2.cpu().numpy(), X, W)
+    assert (d2.cpu().numpy()[:10] == 0).all() and (b_gpu.cpu().numpy()[:10] == np.arange(10)).all()
+
+
 # ------------------------------------------------------------------------------------------- stage 2
 @pytest.mark.parametrize("m,K,D", [(1, 1, 1), (1000, 100, 8), (50_000, 1024, 50), (30_001, 37, 64), (4096, 2000, 5),
                                    (20_000, 500, 63), (9000, 100, 200), (5000, 3000, 40), (40_000, 2048, 31)])
@@ -125,6 +161,22 @@ def test_accumulate_matches_oracle(som, m, K, D):
     som.som_accumulate(dev(X), dev(b), K, S, n, zero_first=False)
     assert (n.cpu().numpy() == 2 * n_or).all()
     assert (np.abs(S.cpu().numpy() - 2 * S_or) <= 2e-6 * scale).all()
+
+
+def test_accumulate_wide_rows_with_an_index_list(som):
+    """D above 63 goes through in feature windows; with an index list and a padded row stride."""
+    m, K, D = 6000, 300, 130
+    X, _ = problem(21, m, K, D)
+    pad = np.full((m, D + 3), 1e9, dtype=np.float32)
+    pad[:, :D] = X
+    idx = draw_subset(21, 0, m, 2500)
+    b = np.random.default_rng(21).integers(0, K, size=2500).astype(np.int32)
+    S = torch.empty((K, D), dtype=torch.float64, device="cuda")
+    n = torch.empty((K,), dtype=torch.int64, device="cuda")
+    som.som_accumulate(dev(pad)[:, :D], dev(b), K, S, n, idx=dev(idx.astype(np.int32)), zero_first=True)
+    S_or, n_or = oracle.accumulate(X, idx, b, K)
+    assert (n.cpu().numpy() == n_or).all()
+    assert (np.abs(S.cpu().numpy() - S_or) <= 1e-6 * np.abs(X).max() * np.maximum(n_or, 1)[:, None]).all()
 
 
 def test_accumulate_shards_add_up(som):
