@@ -2,22 +2,22 @@
 // per-sample sums of Eq. 3 grouped by best-matching unit):
 //     Num_j = sum_k h(G[k][j]) S_k,   Den_j = sum_k h(G[k][j]) n_k,   h(g) = exp(-g^2 / (2 sigma^2)),
 //     w_j <- Num_j / Den_j  where Den_j >= eps_h, otherwise w_j stays.
-// Three small launches, all latency-bound at K ~ 1000, so each is shaped for many independent workgroups:
-//   1. influence_kernel    h[k][j] for all K x K pairs, one exp per thread (K^2 threads);
-//   2. contract_kernel     partial Num / Den over an eighth of the k range per workgroup (split-k keeps several
-//                          workgroups per compute unit in flight; partials are stored, not atomically added);
-//   3. finish_kernel       adds the partials in a fixed order, applies the threshold, writes W, counts.
-// The contraction is 2 K^2 (D + 1) float64 flops (0.1 GFLOP at K = 1024, D = 50): microseconds on the vector
-// ALUs, so it stays a plain FMA loop.
+// The contraction Num = H^T S (with n as one more column of S) is a dense K x K . K x (D + 1) product in float64:
+// it runs on v_mfma_f64_16x16x4_f64.
+//   1. contract_kernel     one wavefront = 16 updated nodes x up to 64 columns x one sixteenth of the k range; for
+//                          D + 1 <= 64 the influences h = exp(-G^2 / 2 sigma^2) are computed in the wavefront right
+//                          where the MFMA needs them (each one is needed exactly once), otherwise influence_kernel
+//                          writes them out first and the wavefronts of the column slabs read them;
+//   2. finish_kernel       adds the sixteen partials in a fixed order, applies the threshold, writes W, counts.
 #include "som_internal.hpp"
 
 #include <math.h>
 
 namespace som {
 
-constexpr int kTJ = 4;       // updated nodes per workgroup (one wavefront each)
-constexpr int kKC = 32;      // contributing nodes staged per step (two LDS buffers of kKC x 64 doubles)
-constexpr int kSplitK = 8;   // workgroups sharing one block of updated nodes
+typedef double doublex4 __attribute__((ext_vector_type(4)));
+
+constexpr int kSplitK = 16;  // wavefronts sharing one block of updated nodes (partials are stored, then summed in order)
 
 __global__ void __launch_bounds__(256) influence_kernel(const float* __restrict__ G, int K, double inv2s2,
                                                         double* __restrict__ H)
@@ -28,74 +28,72 @@ __global__ void __launch_bounds__(256) influence_kernel(const float* __restrict_
     H[e] = isinf(gd) ? 0.0 : exp(-(gd * gd) * inv2s2);
 }
 
-// grid (K / kTJ, ceil(D / 64), kSplitK); thread = (node jj = tid / 64, feature dl = tid % 64)
-__global__ void __launch_bounds__(kTJ * 64) contract_kernel(const double* __restrict__ H, const double* __restrict__ S,
-                                                            const unsigned long long* __restrict__ n, int K, int D,
-                                                            double* __restrict__ part)
+// grid (ceil(K / 16), ceil((D + 1) / 64), kSplitK / 4), 4 wavefronts per workgroup, one k-split each.
+// MFMA operands (16 x 16 x 4, float64): lane l supplies A[i = l % 16][k = l / 16] = h[k][j0 + i] and
+// B[k = l / 16][c = l % 16] = S[k][c0 + c] (column D is n); its register r receives row l / 16 + 4 r, column l % 16.
+template <bool FUSED>
+__global__ void __launch_bounds__(256) contract_kernel(const float* __restrict__ G, const double* __restrict__ H,
+                                                       double inv2s2, const double* __restrict__ S,
+                                                       const unsigned long long* __restrict__ n, int K, int D,
+                                                       double* __restrict__ part)
 {
-    __shared__ double hs[2][kKC][kTJ];
-    __shared__ double ns[2][kKC];
-    __shared__ double Ss[2][kKC][64];
-    const int tid = threadIdx.x;
-    const int jj = tid >> 6, dl = tid & 63;
-    const int j0 = blockIdx.x * kTJ;
-    const int d0 = blockIdx.y * 64;
-    const int kper = ((K + kSplitK * kKC - 1) / (kSplitK * kKC)) * kKC;
-    const int k_lo = blockIdx.z * kper;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int z = blockIdx.z * 4 + wave;
+    const int j0 = blockIdx.x * 16, c0 = blockIdx.y * 64;
+    const int kper = ((K + kSplitK * 4 - 1) / (kSplitK * 4)) * 4;
+    const int k_lo = z * kper;
     const int k_hi = (k_lo + kper < K) ? k_lo + kper : K;
-    constexpr int SLOADS = kKC * 64 / (kTJ * 64);
-    double num = 0.0, den = 0.0;
-    double pre_s[SLOADS], pre_h = 0.0, pre_n = 0.0;
-
-    auto fetch = [&](int kc) {
+    const int li = lane & 15, lk = lane >> 4;
+    const int j = j0 + li;
+    doublex4 acc[4];
 #pragma unroll
-        for (int p = 0; p < SLOADS; ++p) {
-            const int e = tid + p * kTJ * 64;
-            const int kk = e >> 6, f = e & 63;
-            const int k = kc + kk;
-            pre_s[p] = (k < k_hi && d0 + f < D) ? S[(size_t)k * D + d0 + f] : 0.0;
-        }
-        const int kk = tid / kTJ, q = tid % kTJ;      // the first kKC * kTJ threads bring the influences
-        const int k = kc + kk;
-        const bool mine = kk < kKC && k < k_hi;
-        pre_h = (mine && j0 + q < K) ? H[(size_t)k * K + j0 + q] : 0.0;
-        pre_n = (mine && q == 0) ? (double)n[k] : 0.0;
-    };
-    auto stash = [&](int buf) {
+    for (int t = 0; t < 4; ++t) acc[t] = doublex4{0.0, 0.0, 0.0, 0.0};
+    // Sixteen k-steps at a time: first every load of the batch (one wavefront per SIMD has nothing else to cover a
+    // round trip to L2 with), then the sixteen exponentials, then the MFMAs.
+    constexpr int kBatch = 16;
+    const int jc = j < K ? j : K - 1;
+    for (int kb = k_lo; kb < k_hi; kb += 4 * kBatch) {
+        float gv[kBatch];
+        double nv[kBatch], sv[kBatch][4];
 #pragma unroll
-        for (int p = 0; p < SLOADS; ++p) {
-            const int e = tid + p * kTJ * 64;
-            Ss[buf][e >> 6][e & 63] = pre_s[p];
+        for (int s = 0; s < kBatch; ++s) {
+            const int k = kb + 4 * s + lk;
+            const int kc = k < K ? k : K - 1;                 // clamped row: the loads are unconditional
+            if (FUSED) gv[s] = G[(size_t)kc * K + jc];
+            else nv[s] = H[(size_t)kc * K + jc];              // holds h until it is replaced by n below
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                const int c = c0 + 16 * t + li;
+                sv[s][t] = (c == D) ? (double)n[kc] : S[(size_t)kc * D + (c < D ? c : D - 1)];
+            }
         }
-        if (tid < kKC * kTJ) {
-            hs[buf][tid / kTJ][tid % kTJ] = pre_h;
-            if (tid % kTJ == 0) ns[buf][tid / kTJ] = pre_n;
+#pragma unroll
+        for (int s = 0; s < kBatch; ++s) {
+            const int k = kb + 4 * s + lk;
+            const bool in = k < k_hi && j < K;
+            double h;
+            if (FUSED) {
+                const double gd = (double)gv[s];
+                h = (in && !isinf(gd)) ? exp(-(gd * gd) * inv2s2) : 0.0;
+            } else {
+                h = in ? nv[s] : 0.0;
+            }
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                const int c = c0 + 16 * t + li;
+                const double b = (k < k_hi && c <= D) ? sv[s][t] : 0.0;
+                acc[t] = __builtin_amdgcn_mfma_f64_16x16x4f64(h, b, acc[t], 0, 0, 0);
+            }
         }
-    };
-
-    if (k_lo < k_hi) {
-        fetch(k_lo);
-        stash(0);
     }
-    __syncthreads();
-    int buf = 0;
-    for (int kc = k_lo; kc < k_hi; kc += kKC, buf ^= 1) {
-        const bool more = kc + kKC < k_hi;
-        if (more) fetch(kc + kKC);
-#pragma unroll 8
-        for (int kk = 0; kk < kKC; ++kk) {
-            const double h = hs[buf][kk][jj];
-            num = fma(h, Ss[buf][kk][dl], num);
-            den = fma(h, ns[buf][kk], den);
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+        const int c = c0 + 16 * t + li;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const int jr = j0 + lk + 4 * r;
+            if (jr < K && c <= D) part[((size_t)z * K + jr) * (D + 1) + c] = acc[t][r];
         }
-        if (more) stash(buf ^ 1);
-        __syncthreads();
-    }
-    const int j = j0 + jj, d = d0 + dl;
-    if (j < K) {
-        double* row = part + ((size_t)blockIdx.z * K + j) * (D + 1);
-        if (d < D) row[d] = num;
-        if (dl == 0 && blockIdx.y == 0) row[D] = den;
     }
 }
 
@@ -153,10 +151,16 @@ int update_run(som_ctx* ctx, const double* S, const unsigned long long* n, const
     double* H = (double*)ctx->upd_blob;
     double* part = H + h_elems;
     const double inv2s2 = 1.0 / (2.0 * sigma * sigma);
-    hipLaunchKernelGGL(influence_kernel, dim3((unsigned)((h_elems + 255) / 256)), dim3(256), 0, ctx->stream, G, K, inv2s2, H);
-    if (int rc = check_hip(ctx, hipGetLastError(), "influence kernel launch")) return rc;
-    dim3 grid((K + kTJ - 1) / kTJ, (D + 63) / 64, kSplitK);
-    hipLaunchKernelGGL(contract_kernel, grid, dim3(kTJ * 64), 0, ctx->stream, H, S, n, K, D, part);
+    const dim3 grid((K + 15) / 16, (D + 1 + 63) / 64, kSplitK / 4);
+    if (grid.y == 1) {
+        hipLaunchKernelGGL(contract_kernel<true>, grid, dim3(256), 0, ctx->stream, G, (const double*)nullptr, inv2s2, S, n, K,
+                           D, part);
+    } else {
+        hipLaunchKernelGGL(influence_kernel, dim3((unsigned)((h_elems + 255) / 256)), dim3(256), 0, ctx->stream, G, K, inv2s2, H);
+        if (int rc = check_hip(ctx, hipGetLastError(), "influence kernel launch")) return rc;
+        hipLaunchKernelGGL(contract_kernel<false>, grid, dim3(256), 0, ctx->stream, G, (const double*)H, inv2s2, S, n, K, D,
+                           part);
+    }
     if (int rc = check_hip(ctx, hipGetLastError(), "contraction kernel launch")) return rc;
     const bool plain = ctx->eta == 1.0 && ctx->mu == 0.0;
     hipLaunchKernelGGL(finish_kernel, dim3((K * D + 255) / 256), dim3(256), 0, ctx->stream, part, n, K, D, eps_h, plain,
