@@ -22,7 +22,7 @@ METRIC = "samples/sec per batch-SOM epoch (BMU+update), 1024 nodes x 50 features
 
 def stream_bench(args, wl, X, W0, sig, som, pkg, torch) -> int:
     """Host-resident X through som_epoch_host; reports whole-epoch samples/s and the copy stream's GB/s."""
-    Xh = torch.from_numpy(X)
+    Xh = X if args.stream == "mmap" else torch.from_numpy(X)
     if args.stream == "pinned":
         Xh = Xh.pin_memory()
     Wd = torch.from_numpy(W0).cuda()
@@ -74,8 +74,10 @@ def main() -> int:
                          "(uniform data, Section 4.2.1), to be varied with --rows / --features / --grid")
     ap.add_argument("--features", type=int, default=None, help="override the feature count D (scale workload)")
     ap.add_argument("--grid", type=int, default=None, help="override the lattice side length, K = side^2 (scale workload)")
-    ap.add_argument("--stream", default=None, choices=["pinned", "pageable"],
-                    help="keep X in host memory and run som_epoch_host (the chunked loading path) instead")
+    ap.add_argument("--stream", default=None, choices=["pinned", "pageable", "mmap"],
+                    help="keep X in host memory (or, mmap, in a memory-mapped file written to --mmap-dir first) and run "
+                         "som_epoch_host (the chunked loading path) instead")
+    ap.add_argument("--mmap-dir", default="/tmp", help="where --stream mmap writes its sample file (deleted afterwards)")
     ap.add_argument("--chunk-rows", type=int, default=4_000_000)
     ap.add_argument("--rows", type=int, default=None, help="override the workload's sample count")
     ap.add_argument("--cpu-rows", type=int, default=1_000_000, help="rows of the workload the CPU oracle is timed on")
@@ -100,14 +102,29 @@ def main() -> int:
         over.update(k=args.grid * args.grid, lattice=(args.grid, args.grid), sigma=(args.grid / 2.0, 1.0))
     wl = make_workload(args.workload, n=args.rows, **over)
     t0 = time.time()
-    X = wl.data().rows(0, wl.n)
-    W0 = X[draw_initial_rows(wl.seed, wl.n, wl.k)].copy()
+    mmap_path = None
+    if args.stream == "mmap":
+        # the paper's disk-backed regime (Section 3.3.2): the matrix lives in a file and is mapped, never loaded whole
+        mmap_path = os.path.join(args.mmap_dir, f"som_bench_{os.getpid()}.f32")
+        Xw = np.lib.format.open_memmap(mmap_path, mode="w+", dtype=np.float32, shape=(wl.n, wl.d))
+        wl.data().fill(Xw)
+        Xw.flush()
+        del Xw
+        X = np.load(mmap_path, mmap_mode="r")
+    else:
+        X = wl.data().rows(0, wl.n)
+    W0 = np.ascontiguousarray(X[draw_initial_rows(wl.seed, wl.n, wl.k)])
     sig = linear_sigma(wl.sigma[0], wl.sigma[1], max(args.steps, 1))
     print(f"[bench] generated {wl.name}: {wl.n} x {wl.d} in {time.time() - t0:.1f}s", file=sys.stderr, flush=True)
 
     som = pkg.Som(0)
     if args.stream:
-        return stream_bench(args, wl, X, W0, sig, som, pkg, torch)
+        try:
+            return stream_bench(args, wl, X, W0, sig, som, pkg, torch)
+        finally:
+            if mmap_path:
+                del X
+                os.remove(mmap_path)
     Xd = torch.from_numpy(X).cuda()
     Wd = torch.from_numpy(W0).cuda()
     lattice_G = None

@@ -217,6 +217,37 @@ def neighborhood_update_momentum(S, n, G, sigma, W, V, eta: float = 1.0, mu: flo
     return W0 + delta, delta, guarded
 
 
+def neighborhood_update_shifted(S, n, G, sigma, W):
+    """The update with the other possible reading of the "numerical safeguards" on U_j / H_j (paragraph after Eq. 4):
+    instead of a threshold on the denominator, every updated node j has its exponents shifted by the smallest
+    squared distance to an occupied node,
+
+        m_j = min_{k: n_k > 0} G[k][j]^2,     h'_kj = exp(-(G[k][j]^2 - m_j) / (2 sigma^2))  for n_k > 0, else 0,
+
+    and w_j = sum_k h'_kj S_k / sum_k h'_kj n_k.  The factor exp(m_j / 2 sigma^2) cancels in the ratio, so wherever
+    the plain sums do not underflow the result is the same; where they do, the node follows its nearest occupied
+    nodes instead of standing still.  A node that no occupied node reaches (m_j infinite) is left unchanged.
+    Returns (W_new, unchanged) with ``unchanged`` the mask of such nodes.
+    """
+    S = np.asarray(S, dtype=np.float64)
+    nn = np.asarray(n, dtype=np.float64)
+    W0 = np.asarray(W, dtype=np.float64)
+    g2 = np.asarray(G, dtype=np.float64) ** 2
+    K = g2.shape[0]
+    occupied = nn > 0
+    Wn = W0.copy()
+    unchanged = np.ones(K, dtype=bool)
+    for j in range(K):
+        col = g2[occupied, j]
+        if col.size == 0 or not np.isfinite(col.min()):
+            continue
+        hj = np.exp(-(col - col.min()) / (2.0 * sigma * sigma))
+        hj[~np.isfinite(col)] = 0.0
+        Wn[j] = (hj @ S[occupied]) / (hj @ nn[occupied])
+        unchanged[j] = False
+    return Wn, unchanged
+
+
 def bmu_gram(X, W, block: int = 65536):
     """BMU through |x|^2 - 2 x.w + |w|^2 with a float64 BLAS product; checked against ``bmu`` in the tests.
 

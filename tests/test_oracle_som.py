@@ -305,3 +305,46 @@ def test_momentum_recurrence_single_node():
     Wn, Vn, guarded = oracle.neighborhood_update_momentum(np.array([[6.0], [0.0]]), np.array([2, 0]), G2, 1.0,
                                                           np.array([[1.0], [9.0]]), np.array([[0.0], [1.0]]), eta=1.0, mu=0.5)
     assert guarded.tolist() == [False, True] and Wn[:, 0].tolist() == [3.0, 9.5] and Vn[:, 0].tolist() == [2.0, 0.5]
+
+
+# ---------------------------------------------------------------- the shifted-exponent reading of the safeguard
+def test_shifted_update_equals_the_plain_one_where_nothing_underflows():
+    """exp(m_j / 2 sigma^2) cancels in Num / Den: with a wide radius both readings give the same weights."""
+    rng = np.random.default_rng(5)
+    K, D = 30, 4
+    G = oracle.rect_lattice_distances(5, 6)
+    n = rng.integers(0, 9, size=K)
+    n[::4] = 0
+    S = rng.normal(size=(K, D)) * n[:, None]
+    W = rng.normal(size=(K, D))
+    plain, guarded, _ = oracle.neighborhood_update(S, n, G, 2.0, W)
+    shifted, unchanged = oracle.neighborhood_update_shifted(S, n, G, 2.0, W)
+    assert not guarded.any() and not unchanged.any()
+    np.testing.assert_allclose(shifted, plain, rtol=1e-12, atol=1e-14)
+
+
+def test_shifted_update_far_empty_node_follows_its_nearest_occupied_node():
+    """Chain 0 - 1 - 2, only node 0 occupied, tiny radius: the threshold reading leaves nodes 1 and 2 where they are
+    (their denominators are e^-200 and e^-800 times n_0), the shifted reading moves both onto node 0's sample mean."""
+    G = np.array([[0, 1, 2], [1, 0, 1], [2, 1, 0]], dtype=np.float64)
+    n = np.array([4, 0, 0])
+    S = np.array([[8.0, -4.0], [0.0, 0.0], [0.0, 0.0]])
+    W = np.array([[0.0, 0.0], [5.0, 5.0], [9.0, 9.0]])
+    plain, guarded, _ = oracle.neighborhood_update(S, n, G, 0.05, W)
+    assert guarded.tolist() == [False, True, True] and (plain[1:] == W[1:]).all()
+    shifted, unchanged = oracle.neighborhood_update_shifted(S, n, G, 0.05, W)
+    assert not unchanged.any()
+    np.testing.assert_allclose(shifted, np.array([[2.0, -1.0]] * 3), rtol=1e-14)
+
+
+def test_shifted_update_equidistant_occupied_nodes_and_unreachable_node():
+    """Node 1 sits between two occupied nodes at the same distance: for sigma -> 0 it takes their count-weighted mean.
+    Node 3 is in another component of the graph: nothing reaches it, it stays."""
+    inf = np.inf
+    G = np.array([[0, 1, 2, inf], [1, 0, 1, inf], [2, 1, 0, inf], [inf, inf, inf, 0]])
+    n = np.array([1, 0, 3, 0])
+    S = np.array([[1.0], [0.0], [9.0], [0.0]])          # means 1 and 3
+    W = np.array([[0.0], [7.0], [0.0], [-5.0]])
+    shifted, unchanged = oracle.neighborhood_update_shifted(S, n, G, 0.01, W)
+    assert unchanged.tolist() == [False, False, False, True]
+    np.testing.assert_allclose(shifted[:, 0], [1.0, (1.0 + 9.0) / 4.0, 3.0, -5.0], rtol=1e-12)
