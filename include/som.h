@@ -140,6 +140,20 @@ int som_set_update_rule(som_ctx* ctx, double eta, double mu, float* velocity);
  */
 int som_topology(som_ctx* ctx, const float* W, int32_t K, int32_t D, int kind, float* G);
 
+/*
+ * How the update keeps U_j / H_j finite (the "numerical safeguards" of the paragraph after Eq. 4), for every later
+ * update on this context:
+ *   SOM_SAFEGUARD_THRESHOLD (default)  w_j is left unchanged where Den_j < eps_h;
+ *   SOM_SAFEGUARD_SHIFT                the exponents of updated node j are shifted by m_j = min over occupied nodes k
+ *                                      (n_k > 0) of G[k][j]^2:  h'_kj = exp(-(G[k][j]^2 - m_j) / (2 sigma^2)) for
+ *                                      n_k > 0, else 0.  The ratio Num_j / Den_j is the same wherever the plain sums
+ *                                      do not underflow; where they do, node j follows its nearest occupied nodes.
+ *                                      Nodes no occupied node reaches (m_j infinite) are left unchanged and counted
+ *                                      as guarded.
+ */
+enum { SOM_SAFEGUARD_THRESHOLD = 0, SOM_SAFEGUARD_SHIFT = 1 };
+int som_set_safeguard(som_ctx* ctx, int mode);
+
 /* [host] statistics of one epoch, filled after the epoch's work has finished. */
 typedef struct {
     double sum_dist;   /* sum over presented samples of the distance to the BMU (pre-update weights) */

@@ -174,6 +174,14 @@ int som_sync(som_ctx* ctx)
     return check_hip(ctx, hipStreamSynchronize(ctx->stream), "stream synchronize");
 }
 
+int som_set_safeguard(som_ctx* ctx, int mode)
+{
+    if (!ctx) return SOM_EINVAL;
+    if (mode != SOM_SAFEGUARD_THRESHOLD && mode != SOM_SAFEGUARD_SHIFT) return fail(ctx, SOM_EINVAL, "unknown safeguard mode %d", mode);
+    ctx->safeguard = mode;
+    return SOM_OK;
+}
+
 int som_set_update_rule(som_ctx* ctx, double eta, double mu, float* velocity)
 {
     if (!ctx) return SOM_EINVAL;

@@ -66,6 +66,7 @@ struct som_ctx {
     size_t acc_bytes = 0;
     void* upd_blob = nullptr;      // influence matrix + split-k partials of the update
     size_t upd_bytes = 0;
+    int safeguard = 0;             // SOM_SAFEGUARD_*
     double* qe_part = nullptr;     // [kQeSlots][2], zero between calls
     void* topo_blob = nullptr;     // node distances, adjacency matrix and lists of the topology rebuild
     size_t topo_bytes = 0;

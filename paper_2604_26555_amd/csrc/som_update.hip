@@ -19,13 +19,35 @@ typedef double doublex4 __attribute__((ext_vector_type(4)));
 
 constexpr int kSplitK = 16;  // wavefronts sharing one block of updated nodes (partials are stored, then summed in order)
 
+// shift[j] = min over occupied nodes k of G[k][j]^2 (+inf when there is none): one thread per updated node j
+__global__ void __launch_bounds__(256) shift_kernel(const float* __restrict__ G, const unsigned long long* __restrict__ n,
+                                                    int K, double* __restrict__ shift)
+{
+    const int j = blockIdx.x * 256 + threadIdx.x;
+    if (j >= K) return;
+    double m = INFINITY;
+    for (int k = 0; k < K; ++k) {
+        const double gd = (double)G[(size_t)k * K + j];
+        if (n[k] != 0ull && gd * gd < m) m = gd * gd;
+    }
+    shift[j] = m;
+}
+
+// h = exp(-(g^2 - shift_j) / 2 sigma^2); with a shift only occupied nodes k contribute (their exponent is <= 0)
+__device__ __forceinline__ double influence_of(double gd, double inv2s2, double shift_j, bool occupied)
+{
+    const double e = -(gd * gd - shift_j) * inv2s2;
+    return (isinf(gd) || isinf(shift_j) || !occupied) ? 0.0 : exp(e);
+}
+
 __global__ void __launch_bounds__(256) influence_kernel(const float* __restrict__ G, int K, double inv2s2,
-                                                        double* __restrict__ H)
+                                                        const double* __restrict__ shift,
+                                                        const unsigned long long* __restrict__ n, double* __restrict__ H)
 {
     const size_t e = (size_t)blockIdx.x * 256 + threadIdx.x;
     if (e >= (size_t)K * K) return;
-    const double gd = (double)G[e];
-    H[e] = isinf(gd) ? 0.0 : exp(-(gd * gd) * inv2s2);
+    const int k = (int)(e / K), j = (int)(e % K);
+    H[e] = influence_of((double)G[e], inv2s2, shift ? shift[j] : 0.0, !shift || n[k] != 0ull);
 }
 
 // grid (ceil(K / 16), ceil((D + 1) / 64), kSplitK / 4), 4 wavefronts per workgroup, one k-split each.
@@ -33,7 +55,8 @@ __global__ void __launch_bounds__(256) influence_kernel(const float* __restrict_
 // B[k = l / 16][c = l % 16] = S[k][c0 + c] (column D is n); its register r receives row l / 16 + 4 r, column l % 16.
 template <bool FUSED>
 __global__ void __launch_bounds__(256) contract_kernel(const float* __restrict__ G, const double* __restrict__ H,
-                                                       double inv2s2, const double* __restrict__ S,
+                                                       double inv2s2, const double* __restrict__ shift,
+                                                       const double* __restrict__ S,
                                                        const unsigned long long* __restrict__ n, int K, int D,
                                                        double* __restrict__ part)
 {
@@ -52,6 +75,7 @@ __global__ void __launch_bounds__(256) contract_kernel(const float* __restrict__
     // round trip to L2 with), then the sixteen exponentials, then the MFMAs.
     constexpr int kBatch = 16;
     const int jc = j < K ? j : K - 1;
+    const double shift_j = (FUSED && shift) ? shift[jc] : 0.0;
     for (int kb = k_lo; kb < k_hi; kb += 4 * kBatch) {
         float gv[kBatch];
         double nv[kBatch], sv[kBatch][4];
@@ -73,8 +97,8 @@ __global__ void __launch_bounds__(256) contract_kernel(const float* __restrict__
             const bool in = k < k_hi && j < K;
             double h;
             if (FUSED) {
-                const double gd = (double)gv[s];
-                h = (in && !isinf(gd)) ? exp(-(gd * gd) * inv2s2) : 0.0;
+                const bool occupied = !shift || n[k < K ? k : K - 1] != 0ull;
+                h = in ? influence_of((double)gv[s], inv2s2, shift_j, occupied) : 0.0;
             } else {
                 h = in ? nv[s] : 0.0;
             }
@@ -134,7 +158,7 @@ int update_run(som_ctx* ctx, const double* S, const unsigned long long* n, const
                double sigma, double eps_h, float* W, int32_t* small)
 {
     const size_t h_elems = (size_t)K * K;
-    const size_t need = (h_elems + (size_t)kSplitK * K * (D + 1)) * sizeof(double);
+    const size_t need = (h_elems + (size_t)kSplitK * K * (D + 1) + K) * sizeof(double);
     if (need > ctx->upd_bytes) {
         if (ctx->upd_blob) {
             if (int rc = check_hip(ctx, hipStreamSynchronize(ctx->stream), "sync before workspace growth")) return rc;
@@ -152,14 +176,21 @@ int update_run(som_ctx* ctx, const double* S, const unsigned long long* n, const
     double* part = H + h_elems;
     const double inv2s2 = 1.0 / (2.0 * sigma * sigma);
     const dim3 grid((K + 15) / 16, (D + 1 + 63) / 64, kSplitK / 4);
+    double* shift = nullptr;
+    if (ctx->safeguard == SOM_SAFEGUARD_SHIFT) {
+        shift = part + (size_t)kSplitK * K * (D + 1);
+        hipLaunchKernelGGL(shift_kernel, dim3((K + 255) / 256), dim3(256), 0, ctx->stream, G, n, K, shift);
+        if (int rc = check_hip(ctx, hipGetLastError(), "exponent shift launch")) return rc;
+    }
     if (grid.y == 1) {
-        hipLaunchKernelGGL(contract_kernel<true>, grid, dim3(256), 0, ctx->stream, G, (const double*)nullptr, inv2s2, S, n, K,
-                           D, part);
+        hipLaunchKernelGGL(contract_kernel<true>, grid, dim3(256), 0, ctx->stream, G, (const double*)nullptr, inv2s2,
+                           (const double*)shift, S, n, K, D, part);
     } else {
-        hipLaunchKernelGGL(influence_kernel, dim3((unsigned)((h_elems + 255) / 256)), dim3(256), 0, ctx->stream, G, K, inv2s2, H);
+        hipLaunchKernelGGL(influence_kernel, dim3((unsigned)((h_elems + 255) / 256)), dim3(256), 0, ctx->stream, G, K, inv2s2,
+                           (const double*)shift, n, H);
         if (int rc = check_hip(ctx, hipGetLastError(), "influence kernel launch")) return rc;
-        hipLaunchKernelGGL(contract_kernel<false>, grid, dim3(256), 0, ctx->stream, G, (const double*)H, inv2s2, S, n, K, D,
-                           part);
+        hipLaunchKernelGGL(contract_kernel<false>, grid, dim3(256), 0, ctx->stream, G, (const double*)H, inv2s2,
+                           (const double*)nullptr, S, n, K, D, part);
     }
     if (int rc = check_hip(ctx, hipGetLastError(), "contraction kernel launch")) return rc;
     const bool plain = ctx->eta == 1.0 && ctx->mu == 0.0;

@@ -19,13 +19,15 @@ LIB_PATH = os.path.join(_HERE, "libsom.so")
 
 SOM_OK, SOM_EINVAL, SOM_ENOMEM, SOM_EHIP, SOM_EIO, SOM_ESTATE = 0, -1, -2, -3, -4, -5
 SOM_KERNEL_GAUSSIAN = 0
+SOM_SAFEGUARD_THRESHOLD = 0
+SOM_SAFEGUARD_SHIFT = 1
 SOM_TOPOLOGY_MST = 1
 SOM_TOPOLOGY_RNG = 2
 
 EXPORTS = [
     "som_create", "som_destroy", "som_strerror", "som_last_error", "som_sync", "som_bmu", "som_accumulate",
     "som_neighborhood_update", "som_epoch", "som_epoch_host", "som_profile", "som_profile_read",
-    "som_set_update_rule", "som_topology",
+    "som_set_update_rule", "som_topology", "som_set_safeguard",
 ]
 
 
@@ -77,6 +79,8 @@ def load_library(path: str = LIB_PATH) -> C.CDLL:
     lib.som_accumulate.restype = C.c_int
     lib.som_neighborhood_update.argtypes = [vp, vp, vp, vp, i32, i32, f64, C.c_int, f64, vp, vp]
     lib.som_neighborhood_update.restype = C.c_int
+    lib.som_set_safeguard.argtypes = [vp, C.c_int]
+    lib.som_set_safeguard.restype = C.c_int
     lib.som_topology.argtypes = [vp, vp, i32, i32, C.c_int, vp]
     lib.som_topology.restype = C.c_int
     lib.som_epoch.argtypes = [vp, vp, i64, i32, i64, vp, i64, vp, i32, vp, f64, C.c_int, f64, C.POINTER(SomStats)]
@@ -245,6 +249,11 @@ class Som:
                                               _ptr(n_guarded, torch.int32, "n_guarded", self.device))
         self._check(rc, "som_neighborhood_update")
         return W
+
+    def som_set_safeguard(self, mode):
+        if isinstance(mode, str):
+            mode = {"threshold": SOM_SAFEGUARD_THRESHOLD, "shift": SOM_SAFEGUARD_SHIFT}[mode]
+        self._check(self.lib.som_set_safeguard(self._h, int(mode)), "som_set_safeguard")
 
     # ------------------------------------------------------------------ topology rebuild
     def som_topology(self, W, kind, G=None):

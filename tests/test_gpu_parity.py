@@ -257,6 +257,45 @@ def test_update_with_learning_rate_and_momentum(som, eta, mu):
         som.som_set_update_rule(1.0, 0.5, None)
 
 
+@pytest.mark.parametrize("K,D,sigma", [(3, 2, 0.05), (100, 8, 0.3), (100, 8, 4.0), (256, 70, 0.2)])
+def test_update_with_shifted_exponents(som, K, D, sigma):
+    """The other reading of the safeguard: exponents shifted per updated node, so far empty nodes follow their
+    nearest occupied nodes instead of standing still."""
+    rng = np.random.default_rng(K + D)
+    W = rng.normal(size=(K, D)).astype(np.float32)
+    n = rng.integers(1, 30, size=K).astype(np.int64)
+    n[rng.random(K) < 0.6] = 0
+    n[0] = 5
+    S = rng.normal(size=(K, D)) * n[:, None]
+    if K == 3:
+        G = oracle.hop_distances(3, np.array([[0, 1], [1, 2]]))
+    elif K == 100:
+        G = oracle.rect_lattice_distances(10, 10)
+        G[37, :] = G[:, 37] = np.inf                         # one node cut off from everything
+        G[37, 37] = 0.0
+        n[37] = 0
+        S[37] = 0.0
+    else:
+        G = oracle.hex_lattice_distances(16, 16)
+    G = G.astype(np.float32)
+    Wd = dev(W)
+    guarded = torch.zeros(1, dtype=torch.int32, device="cuda")
+    som.som_set_safeguard("shift")
+    try:
+        som.som_neighborhood_update(dev(S), dev(n), dev(G), sigma, Wd, n_guarded=guarded)
+    finally:
+        som.som_set_safeguard("threshold")
+    W_or, unchanged = oracle.neighborhood_update_shifted(S, n, G.astype(np.float64), sigma, W)
+    weights_close(Wd.cpu().numpy(), W_or)
+    assert int(guarded.item()) == int(unchanged.sum())
+    assert (Wd.cpu().numpy()[unchanged] == W[unchanged]).all()
+    # and the default reading is back afterwards
+    Wd2 = dev(W)
+    som.som_neighborhood_update(dev(S), dev(n), dev(G), sigma, Wd2)
+    W_pl, _, den = oracle.neighborhood_update(S, n, G.astype(np.float64), sigma, W)
+    weights_close(Wd2.cpu().numpy(), W_pl, den)
+
+
 def test_update_with_unreachable_nodes(som):
     K, D = 6, 3
     G = oracle.hop_distances(K, np.array([[0, 1], [1, 2], [3, 4]])).astype(np.float32)   # node 5 isolated
