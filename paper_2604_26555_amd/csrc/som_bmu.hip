@@ -93,8 +93,8 @@ __global__ void __launch_bounds__(256) bmu_prep_kernel(const float* __restrict__
         const int k = e / cols, c = e - k * cols;
         const int ch = c / stride, fl = c - ch * stride;
         // stage column fl = 2 s + g feeds MFMA step s, half-wavefront g.  One chunk (D <= 64): feature fl.  Several
-        // chunks: feature 32 g + s of the chunk, so that a lane's 32 features are contiguous in a sample row.
-        const int f = (nch == 1) ? fl : ch * (stride - 1) + (fl & 1) * 32 + (fl >> 1);
+        // chunks: feature STEPS g + s of the chunk, so that a lane's STEPS features are contiguous in a sample row.
+        const int f = (nch == 1) ? fl : ch * (stride - 1) + (fl & 1) * ((stride - 1) / 2) + (fl >> 1);
         const bool real = k < K && fl < stride - 1 && f < D;
         const float v = real ? W[(size_t)k * D + f] : 0.0f;
         const int st = k / kNodesPerStage, r = k % kNodesPerStage;
@@ -443,13 +443,16 @@ __global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2
 // the accumulators of a stage's four node blocks stay live across the chunks, the samples' features of the
 // current chunk are re-read from memory (they stay cache-resident: one workgroup touches 128 rows).
 // ---------------------------------------------------------------------------------------------------------
+template <int STEPS>
 __global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 2))) bmu_wide_kernel(const BmuArgs a)
 {
-    constexpr int STEPS = 32, STRIDE = 2 * STEPS + 1, NBS = kNodesPerStage / 32;
+    static_assert(STEPS % 4 == 0, "a lane's STEPS features are loaded as whole float4s");
+    constexpr int CH = 2 * STEPS;                        // features per chunk
+    constexpr int STRIDE = 2 * STEPS + 1, NBS = kNodesPerStage / 32;
     constexpr int STAGE_FLOATS = stage_floats_for(STRIDE);
     constexpr int STAGE_F4 = STAGE_FLOATS / 4;
     constexpr int PRE = STAGE_F4 / kThreads;
-    static_assert(PRE == 9, "stage copy of the wide kernel holds nine float4 per thread");
+    static_assert(PRE <= 9, "stage copy holds at most nine float4 per thread");
     extern __shared__ float4 lds4[];
     float* lds = reinterpret_cast<float*>(lds4);
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -463,7 +466,7 @@ __global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2
     float best = -INFINITY, second = -INFINITY;
     int rsel = 0, tsel = 0;
     const int nstages = a.kpad / kNodesPerStage;
-    const int nch = (a.D + 63) / 64;
+    const int nch = (a.D + CH - 1) / CH;
     const int nq = nstages * nch;
     const float4* src4 = reinterpret_cast<const float4*>(a.stage);
     {
@@ -485,7 +488,7 @@ __global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2
     float x[STEPS];
 #pragma unroll
     for (int s = 0; s < STEPS; ++s) {
-        const int f = 32 * g + s;
+        const int f = STEPS * g + s;
         x[s] = xr[f < a.D ? f : a.D - 1] - a.centre[f];            // centre[] is zero-padded to whole chunks
     }
     for (int q = 0; q < nq; ++q) {
@@ -494,9 +497,10 @@ __global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2
         {
             const int nxt = (q + 1 < nq) ? q + 1 : q;
             const float4* s4 = src4 + (size_t)nxt * STAGE_F4 + tid;
-            pre0 = s4[0 * kThreads]; pre1 = s4[1 * kThreads]; pre2 = s4[2 * kThreads];
-            pre3 = s4[3 * kThreads]; pre4 = s4[4 * kThreads]; pre5 = s4[5 * kThreads];
-            pre6 = s4[6 * kThreads]; pre7 = s4[7 * kThreads]; pre8 = s4[8 * kThreads];
+#define SOM_PRE_LOAD(i) if constexpr (PRE > i) pre##i = s4[i * kThreads];
+            SOM_PRE_LOAD(0) SOM_PRE_LOAD(1) SOM_PRE_LOAD(2) SOM_PRE_LOAD(3) SOM_PRE_LOAD(4)
+            SOM_PRE_LOAD(5) SOM_PRE_LOAD(6) SOM_PRE_LOAD(7) SOM_PRE_LOAD(8)
+#undef SOM_PRE_LOAD
         }
         // the samples' next chunk travels to registers during this chunk's arithmetic, like the next stage blob
         // (and with them the matching entries of the centre vector: vector loads cost no matrix-pipe time, a
@@ -504,7 +508,7 @@ __global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2
         float xn[STEPS], cn[STEPS];
         {
             const int chn = (ch + 1 == nch) ? 0 : ch + 1;
-            const float4* cc = reinterpret_cast<const float4*>(a.centre + 64 * chn + 32 * g);
+            const float4* cc = reinterpret_cast<const float4*>(a.centre + CH * chn + STEPS * g);
 #pragma unroll
             for (int t = 0; t < STEPS / 4; ++t) {
                 const float4 v = cc[t];
@@ -513,8 +517,8 @@ __global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2
                 cn[4 * t + 2] = v.z;
                 cn[4 * t + 3] = v.w;
             }
-            if (wide_loads && 64 * chn + 64 <= a.D) {
-                const float4* xc = reinterpret_cast<const float4*>(xr + 64 * chn + 32 * g);
+            if (wide_loads && CH * chn + CH <= a.D) {
+                const float4* xc = reinterpret_cast<const float4*>(xr + CH * chn + STEPS * g);
 #pragma unroll
                 for (int t = 0; t < STEPS / 4; ++t) {
                     const float4 v = xc[t];
@@ -526,7 +530,7 @@ __global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2
             } else {
 #pragma unroll
                 for (int s = 0; s < STEPS; ++s) {
-                    const int f = 64 * chn + 32 * g + s;
+                    const int f = CH * chn + STEPS * g + s;
                     xn[s] = xr[f < a.D ? f : a.D - 1];             // beyond D: meets zero weights
                 }
             }
@@ -575,9 +579,10 @@ __global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2
         }
         {
             float4* d4 = lds4 + (buf ^ 1) * STAGE_F4 + tid;
-            d4[0 * kThreads] = pre0; d4[1 * kThreads] = pre1; d4[2 * kThreads] = pre2;
-            d4[3 * kThreads] = pre3; d4[4 * kThreads] = pre4; d4[5 * kThreads] = pre5;
-            d4[6 * kThreads] = pre6; d4[7 * kThreads] = pre7; d4[8 * kThreads] = pre8;
+#define SOM_PRE_STORE(i) if constexpr (PRE > i) d4[i * kThreads] = pre##i;
+            SOM_PRE_STORE(0) SOM_PRE_STORE(1) SOM_PRE_STORE(2) SOM_PRE_STORE(3) SOM_PRE_STORE(4)
+            SOM_PRE_STORE(5) SOM_PRE_STORE(6) SOM_PRE_STORE(7) SOM_PRE_STORE(8)
+#undef SOM_PRE_STORE
         }
         __syncthreads();
         if (++ch == nch) {
@@ -816,13 +821,24 @@ int launch_fill_zero(som_ctx* ctx, void* p, size_t bytes)
 
 int bmu_prepare(som_ctx* ctx, const float* W, int32_t K, int32_t D, BmuPrep* out, double* qe, int32_t* small)
 {
-    const int steps = (D <= 2 * kMaxStepsResident) ? steps_for(D) : kMaxStepsResident;
-    const int nch = (D <= 2 * kMaxStepsResident) ? 1 : (D + 2 * kMaxStepsResident - 1) / (2 * kMaxStepsResident);
+    int steps, nch;
+    if (D <= 2 * kMaxStepsResident) {
+        steps = steps_for(D);
+        nch = 1;
+    } else {
+        // chunk width 56 or 64 features, whichever wastes less (a chunk costs about three MFMA steps of overhead)
+        const int n28 = (D + 55) / 56, n32 = (D + 63) / 64;
+        const bool narrow = n28 * (28 + 3) < n32 * (32 + 3);
+        steps = narrow ? 28 : 32;
+        nch = narrow ? n28 : n32;
+    }
     const int stride = 2 * steps + 1;
     const int kpad = ((K + kNodesPerStage - 1) / kNodesPerStage) * kNodesPerStage;
     const size_t stage_bytes = (size_t)(kpad / kNodesPerStage) * nch * stage_floats_for(stride) * sizeof(float);
     const size_t wt_bytes = (size_t)D * kpad * sizeof(float);
-    const size_t centre_bytes = (((size_t)D * sizeof(float)) + 255) / 256 * 256;
+    // the centre vector is zero-padded to whole chunks (and to the 64 entries the resident kernel reads)
+    const size_t centre_floats = (size_t)(nch > 1 ? nch * 2 * steps : 64);
+    const size_t centre_bytes = ((centre_floats > (size_t)D ? centre_floats : (size_t)D) * sizeof(float) + 255) / 256 * 256;
     const size_t need = stage_bytes + wt_bytes + centre_bytes + 256;
     if (need > ctx->prep_bytes) {
         if (ctx->prep_blob) {
@@ -847,20 +863,23 @@ int bmu_prepare(som_ctx* ctx, const float* W, int32_t K, int32_t D, BmuPrep* out
     out->stride = stride;
     out->nch = nch;
     out->calls = 0;
-    hipLaunchKernelGGL(bmu_centre_kernel, dim3((D + 63) / 64), dim3(1024), 0, ctx->stream, W, K, D, out->centre, out->scal);
+    hipLaunchKernelGGL(bmu_centre_kernel, dim3((unsigned)(centre_bytes / 256)), dim3(1024), 0, ctx->stream, W, K, D,
+                       out->centre, out->scal);
     const long long elems = (long long)kpad * nch * stride;
     hipLaunchKernelGGL(bmu_prep_kernel, dim3((unsigned)((elems + 255) / 256)), dim3(256), 0, ctx->stream, W, K, D, kpad,
                        stride, nch, stage_floats_for(stride), out->centre, out->stage, out->wt, out->scal, qe, small);
     return check_hip(ctx, hipGetLastError(), "bmu_prep launch");
 }
 
+template <int STEPS>
 static int launch_bmu_wide(som_ctx* ctx, const BmuArgs& a)
 {
-    constexpr size_t lds_bytes = 2 * (size_t)stage_floats_for(2 * kMaxStepsResident + 1) * sizeof(float);
+    constexpr size_t lds_bytes = 2 * (size_t)stage_floats_for(2 * STEPS + 1) * sizeof(float);
     static bool attr_set = false;
+    auto kern = bmu_wide_kernel<STEPS>;
     if (!attr_set) {
         if (int rc = check_hip(ctx,
-                               hipFuncSetAttribute(reinterpret_cast<const void*>(bmu_wide_kernel),
+                               hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes),
                                "raising the dynamic LDS limit"))
             return rc;
@@ -868,7 +887,7 @@ static int launch_bmu_wide(som_ctx* ctx, const BmuArgs& a)
     }
     const int64_t per_group = (int64_t)kWavesPerGroup * 32;
     const int64_t groups = (a.m + per_group - 1) / per_group;
-    hipLaunchKernelGGL(bmu_wide_kernel, dim3((unsigned)groups), dim3(kThreads), lds_bytes, ctx->stream, a);
+    hipLaunchKernelGGL(kern, dim3((unsigned)groups), dim3(kThreads), lds_bytes, ctx->stream, a);
     return check_hip(ctx, hipGetLastError(), "bmu (wide) kernel launch");
 }
 
@@ -944,7 +963,8 @@ int bmu_run(som_ctx* ctx, BmuPrep& prep, BmuArgs a)
         stop = ctx->prof_events[ctx->prof_used].second;
         ++ctx->prof_used;
     }
-    int rc = prep.nch > 1 ? launch_bmu_wide(ctx, a) : dispatch_bmu(ctx, prep.steps, a);
+    int rc = prep.nch > 1 ? (prep.steps == 28 ? launch_bmu_wide<28>(ctx, a) : launch_bmu_wide<32>(ctx, a))
+                          : dispatch_bmu(ctx, prep.steps, a);
     if (stop) (void)hipEventRecord(stop, ctx->stream);
     if (rc) return rc;
     if (a.K > 1) {
