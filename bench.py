@@ -184,8 +184,32 @@ def main() -> int:
         torch.cuda.synchronize()
         del Xcopy
     qe = torch.zeros(2, dtype=torch.float64, device="cuda")
-    som.som_bmu(Xd, Wd, qe=qe)                    # quantisation error of the final weights over all rows
+    b_final, _, _ = som.som_bmu(Xd, Wd, qe=qe)    # quantisation error of the final weights over all rows
     final_qe = float(qe[0].item()) / wl.n
+
+    # the other stages on their own, outside the timed region: the accumulation (HBM-bound in principle: one row and
+    # one BMU index read per sample) over all rows with the final BMUs, and the update
+    S_t = torch.empty((wl.k, wl.d), dtype=torch.float64, device="cuda")
+    n_t = torch.empty((wl.k,), dtype=torch.int64, device="cuda")
+    W_t = Wd.clone()
+
+    def event_ms(fn, reps=5):
+        fn()
+        pairs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
+        for a, b in pairs:
+            a.record()
+            fn()
+            b.record()
+        torch.cuda.synchronize()
+        return float(np.median([a.elapsed_time(b) for a, b in pairs]))
+
+    acc_ms = event_ms(lambda: som.som_accumulate(Xd, b_final, wl.k, S_t, n_t, zero_first=True))
+    upd_ms = event_ms(lambda: som.som_neighborhood_update(S_t, n_t, Gd, float(sig[-1]), W_t))
+    acc_bytes = wl.n * (wl.d * 4 + 4)
+    stages = {"accumulate_ms": acc_ms, "accumulate_GBps": acc_bytes / (acc_ms * 1e-3) / 1e9,
+              "accumulate_frac_of_hbm_peak": acc_bytes / (acc_ms * 1e-3) / 8e12, "update_ms": upd_ms,
+              "note": "stand-alone som_accumulate over all rows with the final BMUs (algorithmic bytes: one row + "
+                      "one int32 per sample) and som_neighborhood_update, HIP events, median of 5"}
 
     out = {
         "metric": METRIC, "value": value, "unit": "samples/s", "n_gpus": 1, "steps": args.steps,
@@ -200,6 +224,7 @@ def main() -> int:
                      "achieved": achieved, "peak": PEAK_FP32_MFMA_TFLOPS, "unit": "TFLOP/s",
                      "frac": achieved / PEAK_FP32_MFMA_TFLOPS if kernel_ms else None,
                      "avg_kernel_ms": avg_kernel_ms, "launches": len(kernel_ms), "traffic": traffic},
+        "stages": stages,
     }
 
     if not args.no_cpu_baseline:
