@@ -552,6 +552,13 @@ def test_argument_errors_are_reported_not_fatal(som):
     assert lib.som_epoch(h, p(Xd), 64, 3, 3, None, 64, p(Wd), 4, p(G), 1.0, 5, 0.0, None) == SOM_EINVAL   # unknown kernel
     with pytest.raises(SomError):
         som.som_epoch_host(X, Wd, G, 1.0, chunk_rows=0)
+    Gout = torch.empty((4, 4), dtype=torch.float32, device="cuda")
+    assert lib.som_topology(h, p(Wd), 4, 3, 7, p(Gout)) == SOM_EINVAL                                  # unknown graph kind
+    assert lib.som_topology(h, p(Wd), 4, 3, 1, None) == SOM_EINVAL
+    assert lib.som_topology(h, p(Wd), 20000, 3, 1, p(Gout)) == SOM_EINVAL                              # above the node limit
+    assert lib.som_set_safeguard(h, 9) == SOM_EINVAL
+    assert lib.som_set_update_rule(h, 0.0, 0.0, None) == SOM_EINVAL                                    # eta out of (0, 1]
+    assert lib.som_set_update_rule(h, 1.0, 0.5, None) == SOM_EINVAL                                    # momentum needs a velocity
     assert (Wd.cpu().numpy() == W).all()            # rejected calls leave W alone
     # the context is still usable
     st = som.som_epoch(Xd, Wd, G, 1.0)
