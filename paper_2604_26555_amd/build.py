@@ -10,7 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libsom.so")
-SOURCES = ["som_api.hip", "som_bmu.hip", "som_accumulate.hip", "som_accumulate_mfma.hip", "som_update.hip", "som_topology.hip"]
+SOURCES = ["som_api.hip", "som_bmu.hip", "som_accumulate.hip", "som_accumulate_mfma.hip", "som_accumulate_f64.hip", "som_update.hip", "som_topology.hip"]
 
 FLAGS = [
     "-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950",

@@ -1,0 +1,215 @@
+// Per-BMU sample sums and counts in LDS with float64 atomics:
+//     S_k += x_i,  n_k += 1   for k = b_i       (the inner sums of Eq. 3 grouped by best-matching unit).
+//
+// Measured on gfx950: ds_add_f64 and the integer LDS atomics complete a 64-lane instruction in about 15 cycles,
+// ds_add_f32 needs about 190.  With 8-byte cells the K x (D + 1) partial (the extra column counts samples) does
+// not fit one compute unit's LDS, so the NODES are cut into slabs: a workgroup owns a contiguous range of samples
+// and one slab of nodes, reads the BMU of every sample of its range (4 bytes), and loads and adds only the rows
+// whose BMU falls into its slab.  Every row of X is therefore read exactly once, by exactly one workgroup, as one
+// coalesced 64-lane load (lane 0 adds the count, lane l > 0 feature l - 1), followed by one LDS atomic instruction.
+// Wavefronts work independently: each takes the rows of its own 64 samples that belong to the slab off a ballot
+// mask with scalar instructions, eight rows at a time (that many row loads in flight); there is no barrier and no
+// LDS traffic other than the atomics inside the range loop.
+// At the end the slab moves to the range's slice of a global workspace and a second kernel adds the slices in a
+// fixed order.  Counts are exact; the sums are float64 throughout (the order of the atomic additions varies from
+// run to run, which moves a sum by a few units in the 16th digit).
+// The slabs of one sample range get workgroup numbers 8 apart so that they run on the same XCD: rows are not
+// aligned to cache lines, and the lines two neighbouring rows share are then fetched into that XCD's L2 once.
+#include "som_internal.hpp"
+
+#include <hip/amd_detail/amd_hip_unsafe_atomics.h>
+
+namespace som {
+
+constexpr int kFThreads = 1024;
+constexpr size_t kFLdsBytes = 150 * 1024;     // slab
+constexpr int kFMaxSlabs = 16;
+
+// GATHER: rows are taken through the index list (a scalar load per row; kept out of the plain variant because its
+// wait would also wait for the LDS atomics in flight)
+template <bool GATHER>
+__global__ void __launch_bounds__(kFThreads) accumulate_f64_kernel(const float* __restrict__ X, int D, int64_t ldx,
+                                                                   const uint32_t* __restrict__ idx, int64_t m,
+                                                                   const int32_t* __restrict__ bmu, int K, int ks,
+                                                                   int nslabs, int64_t rows_per_range,
+                                                                   double* __restrict__ part)
+{
+    extern __shared__ double f64_lds[];
+    const int DS = D + 1;
+    double* P = f64_lds;                                                   // [ks][DS]
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    // workgroup number -> (range, slab): slabs of a range sit 8 apart inside a block of 8 * nslabs workgroups
+    const int blk = blockIdx.x / (8 * nslabs), within = blockIdx.x % (8 * nslabs);
+    const int slab = within / 8;
+    const int64_t range = (int64_t)blk * 8 + (within % 8);
+    const int k0 = slab * ks;
+    const int kn = (k0 + ks <= K) ? ks : K - k0;                           // nodes of this slab (may be <= 0)
+    const int64_t lo = range * rows_per_range;
+    if (lo >= m) return;                                   // padding of the last block of 8 ranges (whole workgroup)
+    int64_t hi = lo + rows_per_range;
+    if (hi > m) hi = m;
+
+    for (int c = tid; c < ks * DS; c += kFThreads) P[c] = 0.0;
+    __syncthreads();
+
+    constexpr int G = 8;                                                  // rows in flight per wavefront
+    int b_next = -1;
+    {
+        const int64_t i = lo + wave * 64 + lane;
+        if (i < hi) b_next = bmu[i];
+    }
+    for (int64_t base = lo + wave * 64; base < hi; base += kFThreads) {
+        const int b = b_next;
+        {
+            // the next pass's BMUs are requested before this pass's rows
+            const int64_t i = base + kFThreads + lane;
+            b_next = (i < hi) ? bmu[i] : -1;
+        }
+        const bool in = b >= k0 && b < k0 + kn;
+        unsigned long long todo = __ballot(in);                            // wave-uniform: lanes whose row is ours
+        const float* xpass = X + base * ldx;
+        const int ldx32 = (int)ldx;
+        const int nloc = b - k0;
+        int p_last = 0;
+        // Rows are taken off the mask with scalar instructions only (find-first-set, read-lane): no list in LDS,
+        // no wait between a row's decoding and its load, so G row loads are in flight per wavefront.
+        while (todo != 0ull) {
+            float v[G];
+            int cell[G];
+            const float* xrow[G];
+            bool live[G];
+#pragma unroll
+            for (int t = 0; t < G; ++t) {
+                live[t] = todo != 0ull;
+                const int p = live[t] ? (int)__ffsll((long long)todo) - 1 : p_last;
+                if (live[t]) {
+                    todo &= todo - 1ull;
+                    p_last = p;
+                }
+                // plain variant: 32-bit offset from the pass's first row (64 rows x ldx floats stay far below 2^31)
+                xrow[t] = GATHER ? X + (int64_t)idx[base + p] * ldx : xpass + p * ldx32;
+                cell[t] = __builtin_amdgcn_readlane(nloc, p) * DS;
+                // one pass of 64 lanes per row: lane 0 carries the count, lane l > 0 feature l - 1
+                const int f = lane - 1;
+                const float xv = xrow[t][f < 0 ? 0 : (f < D ? f : D - 1)];
+                v[t] = (lane == 0) ? 1.0f : xv;
+            }
+#pragma unroll
+            for (int t = 0; t < G; ++t) {
+                if (live[t]) {
+                    if (lane < DS) unsafeAtomicAdd(&P[cell[t] + lane], (double)v[t]);
+                    // rows wider than 63 features: the remaining columns, 64 at a time
+                    for (int f = lane + 63; f < D; f += 64) unsafeAtomicAdd(&P[cell[t] + f + 1], (double)xrow[t][f]);
+                }
+            }
+        }
+    }
+    __syncthreads();
+    // slab -> the range's slice [K][DS]
+    if (kn > 0) {
+        double* out = part + ((size_t)range * K + k0) * DS;
+        for (int c = tid; c < kn * DS; c += kFThreads) out[c] = P[c];
+    }
+}
+
+// S[k][f] (+)= sum over the ranges' slices, n[k] (+)= sum of their count columns, always in the same order:
+// a workgroup takes 64 cells, its four wavefronts a quarter of the slices each, then the quarters are added 0..3.
+__global__ void __launch_bounds__(256) accumulate_f64_reduce_kernel(const double* __restrict__ part, int K, int D,
+                                                                    int ranges, int zero_first, double* __restrict__ S,
+                                                                    unsigned long long* __restrict__ n)
+{
+    __shared__ double qsum[4][64];
+    const int q = threadIdx.x >> 6, l = threadIdx.x & 63;
+    const int DS = D + 1;
+    const int c = blockIdx.x * 64 + l;
+    const int per = (ranges + 3) / 4;
+    const int r_lo = q * per, r_hi = (r_lo + per < ranges) ? r_lo + per : ranges;
+    double s = 0.0;
+    if (c < K * DS) {
+        const size_t stride = (size_t)K * DS;
+#pragma unroll 8
+        for (int r = r_lo; r < r_hi; ++r) s += part[(size_t)r * stride + c];
+    }
+    qsum[q][l] = s;
+    __syncthreads();
+    if (q == 0 && c < K * DS) {
+        const double tot = ((qsum[0][l] + qsum[1][l]) + qsum[2][l]) + qsum[3][l];
+        const int k = c / DS, f = c % DS;
+        if (f == 0)
+            n[k] = (zero_first ? 0ull : n[k]) + (unsigned long long)(tot + 0.5);
+        else
+            S[(size_t)k * D + f - 1] = (zero_first ? 0.0 : S[(size_t)k * D + f - 1]) + tot;
+    }
+}
+
+// Returns 1 when the shape is not served by this path (the caller then tries the others), SOM_OK on success, a
+// negative code on failure.  Served: the K x (D + 1) float64 partial fits kFMaxSlabs slabs of LDS.
+int accumulate_f64_run(som_ctx* ctx, const float* X, int32_t D, int64_t ldx, const uint32_t* idx, int64_t m,
+                       const int32_t* bmu, int32_t K, double* S, unsigned long long* n, bool zero_first)
+{
+    if (m <= 0 || ldx >= (1 << 24)) return 1;               // row offsets inside a 64-row pass are 32-bit
+    const size_t row_bytes = (size_t)(D + 1) * sizeof(double);
+    const size_t slab_budget = kFLdsBytes;
+    const int ks_max = (int)(slab_budget / row_bytes);
+    if (ks_max < 1) return 1;
+    const int nslabs = (K + ks_max - 1) / ks_max;
+    if (nslabs > kFMaxSlabs) return 1;
+    const int ks = (K + nslabs - 1) / nslabs;                  // balanced slabs
+    // one workgroup per compute unit: 256 / nslabs ranges of whole 1024-row passes; the grid is padded to blocks of
+    // 8 ranges (workgroups of ranges that start beyond m return at once)
+    int64_t ranges = (256 / nslabs) / 8 * 8;
+    if (ranges < 8) ranges = 256 / nslabs;
+    if (ranges < 1) ranges = 1;
+    const int64_t by_rows = (m + kFThreads - 1) / kFThreads;
+    if (ranges > by_rows) ranges = by_rows;
+    // an odd number of 64-row units per range: the workgroups stream through their ranges in step, and range
+    // starts that are a large power of two apart in bytes land on a few memory channels (measured: 130 us
+    // instead of 85 with 12288-row ranges)
+    int64_t units = ((m + ranges - 1) / ranges + 63) / 64;
+    units |= 1;
+    const int64_t rows_per_range = units * 64;
+    ranges = (m + rows_per_range - 1) / rows_per_range;      // every remaining range holds at least one row
+    const int64_t ranges_padded = (ranges + 7) / 8 * 8;
+    const size_t need = (size_t)ranges * K * (D + 1) * sizeof(double);
+    if (need > ctx->acc_bytes) {
+        if (ctx->acc_blob) {
+            if (int rc = check_hip(ctx, hipStreamSynchronize(ctx->stream), "sync before workspace growth")) return rc;
+            (void)hipFree(ctx->acc_blob);
+            ctx->acc_blob = nullptr;
+            ctx->acc_bytes = 0;
+        }
+        if (hipMalloc(&ctx->acc_blob, need) != hipSuccess) {
+            (void)hipGetLastError();
+            return fail(ctx, SOM_ENOMEM, "cannot allocate %zu bytes for the accumulation workspace", need);
+        }
+        ctx->acc_bytes = need;
+    }
+    double* part = (double*)ctx->acc_blob;
+    const size_t lds = (size_t)ks * row_bytes;
+    const dim3 grid((unsigned)(ranges_padded * nslabs));
+    if (idx) {
+        if (int rc = check_hip(ctx,
+                               hipFuncSetAttribute(reinterpret_cast<const void*>(accumulate_f64_kernel<true>),
+                                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)kFLdsBytes),
+                               "raising the dynamic LDS limit"))
+            return rc;
+        hipLaunchKernelGGL(accumulate_f64_kernel<true>, grid, dim3(kFThreads), lds, ctx->stream, X, D, ldx, idx, m, bmu, K, ks,
+                           nslabs, rows_per_range, part);
+    } else {
+        if (int rc = check_hip(ctx,
+                               hipFuncSetAttribute(reinterpret_cast<const void*>(accumulate_f64_kernel<false>),
+                                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)kFLdsBytes),
+                               "raising the dynamic LDS limit"))
+            return rc;
+        hipLaunchKernelGGL(accumulate_f64_kernel<false>, grid, dim3(kFThreads), lds, ctx->stream, X, D, ldx, idx, m, bmu, K, ks,
+                           nslabs, rows_per_range, part);
+    }
+    if (int rc = check_hip(ctx, hipGetLastError(), "accumulate (float64 LDS) launch")) return rc;
+    const int cells = K * (D + 1);
+    hipLaunchKernelGGL(accumulate_f64_reduce_kernel, dim3((cells + 63) / 64), dim3(256), 0, ctx->stream, part, K, D,
+                       (int)ranges, zero_first ? 1 : 0, S, n);
+    return check_hip(ctx, hipGetLastError(), "accumulate (float64 LDS) reduce launch");
+}
+
+} // namespace som

@@ -106,6 +106,8 @@ int accumulate_run(som_ctx* ctx, const float* X, int32_t D, int64_t ldx, const u
 // 1 = shape not served by the MFMA path (caller falls back), otherwise SOM_OK or an error code
 int accumulate_mfma_run(som_ctx* ctx, const float* X, int32_t D, int64_t ldx, const uint32_t* idx, int64_t m,
                         const int32_t* bmu, int32_t K, double* S, unsigned long long* n, bool zero_first);
+int accumulate_f64_run(som_ctx* ctx, const float* X, int32_t D, int64_t ldx, const uint32_t* idx, int64_t m,
+                        const int32_t* bmu, int32_t K, double* S, unsigned long long* n, bool zero_first);
 int update_run(som_ctx* ctx, const double* S, const unsigned long long* n, const float* G, int32_t K,
                int32_t D, double sigma, double eps_h, float* W, int32_t* small);
 
