@@ -154,6 +154,15 @@ int som_topology(som_ctx* ctx, const float* W, int32_t K, int32_t D, int kind, f
 enum { SOM_SAFEGUARD_THRESHOLD = 0, SOM_SAFEGUARD_SHIFT = 1 };
 int som_set_safeguard(som_ctx* ctx, int mode);
 
+/*
+ * Accumulation order (not an operation of the paper).  By default the per-BMU sums are taken with float64 LDS
+ * atomics: counts are exact, a sum can differ between two runs by a few units in its 16th digit because the order
+ * of the additions is not fixed.  With on != 0 every later som_accumulate / som_epoch / som_epoch_host on this
+ * context uses the slower kernel that adds in a fixed order wherever it applies (K <= 1024, or K <= 2048 with
+ * D <= 31): S, and with it W, is then bit-identical from run to run.
+ */
+int som_set_reproducible(som_ctx* ctx, int on);
+
 /* [host] statistics of one epoch, filled after the epoch's work has finished. */
 typedef struct {
     double sum_dist;   /* sum over presented samples of the distance to the BMU (pre-update weights) */

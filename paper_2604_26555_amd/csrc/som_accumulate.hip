@@ -181,13 +181,17 @@ __global__ void __launch_bounds__(256) accumulate_direct_kernel(const float* __r
 int accumulate_run(som_ctx* ctx, const float* X, int32_t D, int64_t ldx, const uint32_t* idx, int64_t m,
                    const int32_t* bmu, int32_t K, double* S, unsigned long long* n, bool zero_first)
 {
-    // float64 LDS atomics over node slabs when the K x (D + 1) partial fits a few slabs
+    // fixed-order sums in MFMA accumulators when asked for (and the shape fits one workgroup's registers)
+    if (ctx->reproducible) {
+        const int rc = accumulate_mfma_run(ctx, X, D, ldx, idx, m, bmu, K, S, n, zero_first);
+        if (rc != 1) return rc;
+    }
+    // float64 LDS atomics over node slabs when the K x 64 partial fits a few slabs
     {
         const int rc = accumulate_f64_run(ctx, X, D, ldx, idx, m, bmu, K, S, n, zero_first);
         if (rc != 1) return rc;
     }
-    // maps whose K x (D + 1) partial fits one workgroup's MFMA accumulators take the atomic-free path
-    {
+    if (!ctx->reproducible) {
         const int rc = accumulate_mfma_run(ctx, X, D, ldx, idx, m, bmu, K, S, n, zero_first);
         if (rc != 1) return rc;
     }

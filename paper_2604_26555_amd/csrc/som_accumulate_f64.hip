@@ -99,8 +99,6 @@ __global__ void __launch_bounds__(kFThreads) accumulate_f64_kernel(const float* 
             for (int t = 0; t < G; ++t) {
                 if (live[t]) {
                     if (lane < DS) unsafeAtomicAdd(&P[cell[t] + lane], (double)v[t]);
-                    // rows wider than 63 features: the remaining columns, 64 at a time
-                    for (int f = lane + 63; f < D; f += 64) unsafeAtomicAdd(&P[cell[t] + f + 1], (double)xrow[t][f]);
                 }
             }
         }
@@ -115,9 +113,11 @@ __global__ void __launch_bounds__(kFThreads) accumulate_f64_kernel(const float* 
 
 // S[k][f] (+)= sum over the ranges' slices, n[k] (+)= sum of their count columns, always in the same order:
 // a workgroup takes 64 cells, its four wavefronts a quarter of the slices each, then the quarters are added 0..3.
+// D = columns of this launch's feature window, S points at the window's first column, ldS = row length of S; n may
+// be null (the counts are taken from the first window only).
 __global__ void __launch_bounds__(256) accumulate_f64_reduce_kernel(const double* __restrict__ part, int K, int D,
                                                                     int ranges, int zero_first, double* __restrict__ S,
-                                                                    unsigned long long* __restrict__ n)
+                                                                    int ldS, unsigned long long* __restrict__ n)
 {
     __shared__ double qsum[4][64];
     const int q = threadIdx.x >> 6, l = threadIdx.x & 63;
@@ -136,42 +136,42 @@ __global__ void __launch_bounds__(256) accumulate_f64_reduce_kernel(const double
     if (q == 0 && c < K * DS) {
         const double tot = ((qsum[0][l] + qsum[1][l]) + qsum[2][l]) + qsum[3][l];
         const int k = c / DS, f = c % DS;
-        if (f == 0)
-            n[k] = (zero_first ? 0ull : n[k]) + (unsigned long long)(tot + 0.5);
-        else
-            S[(size_t)k * D + f - 1] = (zero_first ? 0.0 : S[(size_t)k * D + f - 1]) + tot;
+        if (f == 0) {
+            if (n) n[k] = (zero_first ? 0ull : n[k]) + (unsigned long long)(tot + 0.5);
+        } else {
+            S[(size_t)k * ldS + f - 1] = (zero_first ? 0.0 : S[(size_t)k * ldS + f - 1]) + tot;
+        }
     }
 }
 
 // Returns 1 when the shape is not served by this path (the caller then tries the others), SOM_OK on success, a
-// negative code on failure.  Served: the K x (D + 1) float64 partial fits kFMaxSlabs slabs of LDS.
+// negative code on failure.  Rows wider than 63 features go through in windows of 63 (one kernel + reduce per
+// window through the same slices).  Served: a K x 64 float64 partial that fits kFMaxSlabs slabs of LDS.
 int accumulate_f64_run(som_ctx* ctx, const float* X, int32_t D, int64_t ldx, const uint32_t* idx, int64_t m,
                        const int32_t* bmu, int32_t K, double* S, unsigned long long* n, bool zero_first)
 {
     if (m <= 0 || ldx >= (1 << 24)) return 1;               // row offsets inside a 64-row pass are 32-bit
-    const size_t row_bytes = (size_t)(D + 1) * sizeof(double);
-    const size_t slab_budget = kFLdsBytes;
-    const int ks_max = (int)(slab_budget / row_bytes);
-    if (ks_max < 1) return 1;
+    const int window = D < 63 ? D : 63;                      // features per pass; lane 0 carries the count
+    const size_t row_bytes = (size_t)(window + 1) * sizeof(double);
+    const int ks_max = (int)(kFLdsBytes / row_bytes);
     const int nslabs = (K + ks_max - 1) / ks_max;
     if (nslabs > kFMaxSlabs) return 1;
     const int ks = (K + nslabs - 1) / nslabs;                  // balanced slabs
-    // one workgroup per compute unit: 256 / nslabs ranges of whole 1024-row passes; the grid is padded to blocks of
-    // 8 ranges (workgroups of ranges that start beyond m return at once)
+    // One workgroup per compute unit and never more workgroups than compute units (with one resident workgroup
+    // per unit a grid of 264 ran 60 % slower than one of 240): 256 / nslabs ranges, in whole blocks of 8 so that
+    // the slabs of a range share an XCD.
     int64_t ranges = (256 / nslabs) / 8 * 8;
     if (ranges < 8) ranges = 256 / nslabs;
     if (ranges < 1) ranges = 1;
     const int64_t by_rows = (m + kFThreads - 1) / kFThreads;
     if (ranges > by_rows) ranges = by_rows;
-    // an odd number of 64-row units per range: the workgroups stream through their ranges in step, and range
-    // starts that are a large power of two apart in bytes land on a few memory channels (measured: 130 us
-    // instead of 85 with 12288-row ranges)
+    // an odd number of 64-row units per range keeps the range starts off a common power-of-two stride
     int64_t units = ((m + ranges - 1) / ranges + 63) / 64;
     units |= 1;
     const int64_t rows_per_range = units * 64;
     ranges = (m + rows_per_range - 1) / rows_per_range;      // every remaining range holds at least one row
     const int64_t ranges_padded = (ranges + 7) / 8 * 8;
-    const size_t need = (size_t)ranges * K * (D + 1) * sizeof(double);
+    const size_t need = (size_t)ranges * K * (window + 1) * sizeof(double);
     if (need > ctx->acc_bytes) {
         if (ctx->acc_blob) {
             if (int rc = check_hip(ctx, hipStreamSynchronize(ctx->stream), "sync before workspace growth")) return rc;
@@ -186,30 +186,25 @@ int accumulate_f64_run(som_ctx* ctx, const float* X, int32_t D, int64_t ldx, con
         ctx->acc_bytes = need;
     }
     double* part = (double*)ctx->acc_blob;
-    const size_t lds = (size_t)ks * row_bytes;
     const dim3 grid((unsigned)(ranges_padded * nslabs));
-    if (idx) {
-        if (int rc = check_hip(ctx,
-                               hipFuncSetAttribute(reinterpret_cast<const void*>(accumulate_f64_kernel<true>),
-                                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)kFLdsBytes),
-                               "raising the dynamic LDS limit"))
-            return rc;
-        hipLaunchKernelGGL(accumulate_f64_kernel<true>, grid, dim3(kFThreads), lds, ctx->stream, X, D, ldx, idx, m, bmu, K, ks,
-                           nslabs, rows_per_range, part);
-    } else {
-        if (int rc = check_hip(ctx,
-                               hipFuncSetAttribute(reinterpret_cast<const void*>(accumulate_f64_kernel<false>),
-                                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)kFLdsBytes),
-                               "raising the dynamic LDS limit"))
-            return rc;
-        hipLaunchKernelGGL(accumulate_f64_kernel<false>, grid, dim3(kFThreads), lds, ctx->stream, X, D, ldx, idx, m, bmu, K, ks,
-                           nslabs, rows_per_range, part);
+    auto kern = idx ? accumulate_f64_kernel<true> : accumulate_f64_kernel<false>;
+    if (int rc = check_hip(ctx,
+                           hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)kFLdsBytes),
+                           "raising the dynamic LDS limit"))
+        return rc;
+    for (int f0 = 0; f0 < D; f0 += window) {
+        const int dw = (D - f0 < window) ? D - f0 : window;
+        const size_t lds = (size_t)ks * (dw + 1) * sizeof(double);
+        hipLaunchKernelGGL(kern, grid, dim3(kFThreads), lds, ctx->stream, X + f0, dw, ldx, idx, m, bmu, K, ks, nslabs,
+                           rows_per_range, part);
+        if (int rc = check_hip(ctx, hipGetLastError(), "accumulate (float64 LDS) launch")) return rc;
+        const int cells = K * (dw + 1);
+        hipLaunchKernelGGL(accumulate_f64_reduce_kernel, dim3((cells + 63) / 64), dim3(256), 0, ctx->stream, part, K, dw,
+                           (int)ranges, zero_first ? 1 : 0, S + f0, D, (f0 == 0) ? n : (unsigned long long*)nullptr);
+        if (int rc = check_hip(ctx, hipGetLastError(), "accumulate (float64 LDS) reduce launch")) return rc;
     }
-    if (int rc = check_hip(ctx, hipGetLastError(), "accumulate (float64 LDS) launch")) return rc;
-    const int cells = K * (D + 1);
-    hipLaunchKernelGGL(accumulate_f64_reduce_kernel, dim3((cells + 63) / 64), dim3(256), 0, ctx->stream, part, K, D,
-                       (int)ranges, zero_first ? 1 : 0, S, n);
-    return check_hip(ctx, hipGetLastError(), "accumulate (float64 LDS) reduce launch");
+    return SOM_OK;
 }
 
 } // namespace som

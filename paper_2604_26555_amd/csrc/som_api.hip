@@ -174,6 +174,13 @@ int som_sync(som_ctx* ctx)
     return check_hip(ctx, hipStreamSynchronize(ctx->stream), "stream synchronize");
 }
 
+int som_set_reproducible(som_ctx* ctx, int on)
+{
+    if (!ctx) return SOM_EINVAL;
+    ctx->reproducible = on ? 1 : 0;
+    return SOM_OK;
+}
+
 int som_set_safeguard(som_ctx* ctx, int mode)
 {
     if (!ctx) return SOM_EINVAL;

@@ -67,6 +67,7 @@ struct som_ctx {
     void* upd_blob = nullptr;      // influence matrix + split-k partials of the update
     size_t upd_bytes = 0;
     int safeguard = 0;             // SOM_SAFEGUARD_*
+    int reproducible = 0;          // prefer the fixed-order accumulation kernel
     double* qe_part = nullptr;     // [kQeSlots][2], zero between calls
     void* topo_blob = nullptr;     // node distances, adjacency matrix and lists of the topology rebuild
     size_t topo_bytes = 0;

@@ -27,7 +27,7 @@ SOM_TOPOLOGY_RNG = 2
 EXPORTS = [
     "som_create", "som_destroy", "som_strerror", "som_last_error", "som_sync", "som_bmu", "som_accumulate",
     "som_neighborhood_update", "som_epoch", "som_epoch_host", "som_profile", "som_profile_read",
-    "som_set_update_rule", "som_topology", "som_set_safeguard",
+    "som_set_update_rule", "som_topology", "som_set_safeguard", "som_set_reproducible",
 ]
 
 
@@ -79,6 +79,8 @@ def load_library(path: str = LIB_PATH) -> C.CDLL:
     lib.som_accumulate.restype = C.c_int
     lib.som_neighborhood_update.argtypes = [vp, vp, vp, vp, i32, i32, f64, C.c_int, f64, vp, vp]
     lib.som_neighborhood_update.restype = C.c_int
+    lib.som_set_reproducible.argtypes = [vp, C.c_int]
+    lib.som_set_reproducible.restype = C.c_int
     lib.som_set_safeguard.argtypes = [vp, C.c_int]
     lib.som_set_safeguard.restype = C.c_int
     lib.som_topology.argtypes = [vp, vp, i32, i32, C.c_int, vp]
@@ -249,6 +251,9 @@ class Som:
                                               _ptr(n_guarded, torch.int32, "n_guarded", self.device))
         self._check(rc, "som_neighborhood_update")
         return W
+
+    def som_set_reproducible(self, on=True):
+        self._check(self.lib.som_set_reproducible(self._h, 1 if on else 0), "som_set_reproducible")
 
     def som_set_safeguard(self, mode):
         if isinstance(mode, str):

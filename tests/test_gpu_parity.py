@@ -148,19 +148,43 @@ def test_bmu_sample_on_a_node(som):
 @pytest.mark.parametrize("m,K,D", [(1, 1, 1), (1000, 100, 8), (50_000, 1024, 50), (30_001, 37, 64), (4096, 2000, 5),
                                    (20_000, 500, 63), (9000, 100, 200), (5000, 3000, 40), (40_000, 2048, 31)])
 def test_accumulate_matches_oracle(som, m, K, D):
+    """Both accumulation kernels: the default one (float64 LDS atomics) and the fixed-order one."""
     X, W = problem(200 + m + K, m, min(K, m), D)
     b = np.random.default_rng(m).integers(0, K, size=m).astype(np.int32)
-    S = torch.full((K, D), 7.0, dtype=torch.float64, device="cuda")
-    n = torch.full((K,), 7, dtype=torch.int64, device="cuda")
-    som.som_accumulate(dev(X), dev(b), K, S, n, zero_first=True)
     S_or, n_or = oracle.accumulate(X, None, b, K)
-    assert (n.cpu().numpy() == n_or).all()
     scale = np.abs(X).max() * np.maximum(n_or, 1)[:, None]
-    assert (np.abs(S.cpu().numpy() - S_or) <= 1e-6 * scale).all()
-    # a second call without clearing adds on top (chunk-wise accumulation of Eq. 3)
-    som.som_accumulate(dev(X), dev(b), K, S, n, zero_first=False)
-    assert (n.cpu().numpy() == 2 * n_or).all()
-    assert (np.abs(S.cpu().numpy() - 2 * S_or) <= 2e-6 * scale).all()
+    for reproducible in (False, True):
+        som.som_set_reproducible(reproducible)
+        try:
+            S = torch.full((K, D), 7.0, dtype=torch.float64, device="cuda")
+            n = torch.full((K,), 7, dtype=torch.int64, device="cuda")
+            som.som_accumulate(dev(X), dev(b), K, S, n, zero_first=True)
+            assert (n.cpu().numpy() == n_or).all()
+            assert (np.abs(S.cpu().numpy() - S_or) <= 1e-6 * scale).all()
+            # a second call without clearing adds on top (chunk-wise accumulation of Eq. 3)
+            som.som_accumulate(dev(X), dev(b), K, S, n, zero_first=False)
+            assert (n.cpu().numpy() == 2 * n_or).all()
+            assert (np.abs(S.cpu().numpy() - 2 * S_or) <= 2e-6 * scale).all()
+        finally:
+            som.som_set_reproducible(False)
+
+
+def test_accumulate_fixed_order_is_bit_reproducible(som):
+    X, _ = problem(31, 200_000, 1024, 50)
+    b = np.random.default_rng(31).integers(0, 1024, size=200_000).astype(np.int32)
+    b[::3] = 5                                                   # a crowded node
+    Xd, bd = dev(X), dev(b)
+    som.som_set_reproducible(True)
+    try:
+        runs = []
+        for _ in range(3):
+            S = torch.empty((1024, 50), dtype=torch.float64, device="cuda")
+            n = torch.empty((1024,), dtype=torch.int64, device="cuda")
+            som.som_accumulate(Xd, bd, 1024, S, n, zero_first=True)
+            runs.append(S.cpu().numpy().copy())
+    finally:
+        som.som_set_reproducible(False)
+    assert np.array_equal(runs[0], runs[1]) and np.array_equal(runs[0], runs[2])
 
 
 def test_accumulate_wide_rows_with_an_index_list(som):
