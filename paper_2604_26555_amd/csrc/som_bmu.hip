@@ -93,13 +93,20 @@ __global__ void __launch_bounds__(256) bmu_prep_kernel(const float* __restrict__
         const int k = e / cols, c = e - k * cols;
         const int ch = c / stride, fl = c - ch * stride;
         // stage column fl = 2 s + g feeds MFMA step s, half-wavefront g.  One chunk (D <= 64): feature fl.  Several
-        // chunks: feature STEPS g + s of the chunk, so that a lane's STEPS features are contiguous in a sample row.
-        const int f = (nch == 1) ? fl : ch * (stride - 1) + (fl & 1) * ((stride - 1) / 2) + (fl >> 1);
-        const bool real = k < K && fl < stride - 1 && f < D;
+        // chunks: the lane's STEPS features are contiguous in a sample row, own range [first, first + STEPS) with
+        // first = CH ch + STEPS g.  Where that range would run past D the lane reads the window [D - STEPS, D)
+        // instead (always whole, always inside the row) and the columns in front of its own range hold zero
+        // weights, so no feature is counted twice.
+        const int steps = (stride - 1) / 2;
+        const int first = ch * (stride - 1) + (fl & 1) * steps;
+        const int window = first < D - steps ? first : D - steps;
+        const int f = (nch == 1) ? fl : window + (fl >> 1);
+        const bool own = fl < stride - 1 && f < D && (nch == 1 || f >= first);
+        const bool real = k < K && own;
         const float v = real ? W[(size_t)k * D + f] : 0.0f;
         const int st = k / kNodesPerStage, r = k % kNodesPerStage;
         stage[((size_t)st * nch + ch) * stage_floats + (size_t)r * stride + fl] = real ? v - centre[f] : 0.0f;
-        if (fl < stride - 1 && f < D) wt[(size_t)f * kpad + k] = v;
+        if (own) wt[(size_t)f * kpad + k] = v;
     }
     if (e < kpad) {
         // squared norm of the centred row exactly as the stage holds it (float32 differences), summed in float64
@@ -166,10 +173,11 @@ __device__ __forceinline__ void group_qe_add(double* __restrict__ part, double q
     }
 }
 
-// Append sample i to the re-decision list for every lane with `push` set: one atomic per wavefront (the list
+// Append sample i (and its score cut) to the re-decision list for every lane with `push` set: one atomic per wavefront (the list
 // length is a single word; one atomic per listed sample serialises on it when a tenth of all samples is listed).
 // Called in converged control flow by all lanes of the wavefront.
-__device__ __forceinline__ void list_push(unsigned int* __restrict__ counter, uint32_t* __restrict__ list, bool push, int64_t i)
+__device__ __forceinline__ void list_push(unsigned int* __restrict__ counter, uint32_t* __restrict__ list,
+                                          float* __restrict__ cutv, bool push, int64_t i, float cut)
 {
     const unsigned long long mask = __ballot(push);
     if (mask == 0ull) return;
@@ -179,7 +187,18 @@ __device__ __forceinline__ void list_push(unsigned int* __restrict__ counter, ui
     if (lane == leader) base = atomicAdd(counter, (unsigned int)__popcll(mask));
     base = __shfl(base, leader);
     const unsigned int below = __builtin_amdgcn_mbcnt_hi((unsigned)(mask >> 32), __builtin_amdgcn_mbcnt_lo((unsigned)mask, 0));
-    if (push) list[base + below] = (uint32_t)i;
+    if (push) {
+        list[base + below] = (uint32_t)i;
+        if (cutv) cutv[base + below] = cut;     // scores at or above this value may belong to the true winner
+    }
+}
+
+// sixteen bytes from a 4-byte aligned address in one load (global memory needs no more than dword alignment)
+__device__ __forceinline__ float4 load4(const float* p)
+{
+    float4 v;
+    __builtin_memcpy(&v, p, sizeof(v));
+    return v;
 }
 
 // plain v_max_f32: the scores are never signalling NaNs worth quieting, and every VALU instruction here is paid
@@ -194,15 +213,19 @@ __device__ __forceinline__ float vmax(float a, float b)
 // ---------------------------------------------------------------------------------------------------------
 // main kernel
 // ---------------------------------------------------------------------------------------------------------
-// two workgroups per compute unit (LDS-bound), i.e. two wavefronts per SIMD: the register budget is 256 VGPRs
-template <int STEPS, int MS>
-__global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 2))) bmu_kernel(const BmuArgs a)
+// One tile = the kWavesPerGroup * MS * 32 samples of a workgroup against all nodes.
+// CAND = false: the search proper (samples wave0 ..., running best / runner-up, results and list at the end).
+// CAND = true: the candidate pass over the first `count` entries of the re-decision list: the same scores are
+// formed again, and instead of the fold every score that reaches the entry's cut is noted (node id into the
+// lane's own slots: lane (j, g) sees the nodes of half g only, so no two lanes share a slot and no atomics are
+// needed).  One compare per score instead of four fold instructions.
+template <int STEPS, int MS, bool CAND>
+__device__ __forceinline__ void bmu_tile(const BmuArgs& a, int64_t tile_index, unsigned int count, float4* lds4)
 {
     constexpr int STRIDE = 2 * STEPS + 1;
     constexpr int STAGE_FLOATS = stage_floats_for(STRIDE);   // whole float4s per thread: no tail handling
     constexpr int STAGE_F4 = STAGE_FLOATS / 4;
     constexpr int PRE = STAGE_F4 / kThreads;
-    extern __shared__ float4 lds4[];
     float* lds = reinterpret_cast<float*>(lds4);
 
     const int tid = threadIdx.x;
@@ -210,7 +233,7 @@ __global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2
     const int wave = tid >> 6;
     const int j = lane & 31;
     const int g = lane >> 5;
-    const int64_t wave0 = ((int64_t)blockIdx.x * kWavesPerGroup + wave) * (MS * 32);
+    const int64_t wave0 = (tile_index * kWavesPerGroup + wave) * (MS * 32);
 
     // centre[2 s + g]: both candidates are read through wave-uniform addresses (scalar loads), the lane picks one
     // (the array is zero-padded to a multiple of 64 entries, so no index needs a bound)
@@ -222,13 +245,21 @@ __global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2
     // ---- this wavefront's samples, kept in registers
     float x[MS][STEPS];
     bool valid[MS];
+    float cut[MS];          // CAND
+    int ncand[MS];          // CAND
     // (Staging the workgroup's rows through LDS with coalesced 16-byte loads was measured against this direct
     // gather and lost by 3 to 10 %: the gather is served by the vector L1, the staging adds two barriers.)
 #pragma unroll
     for (int mb = 0; mb < MS; ++mb) {
-        const int64_t i = wave0 + mb * 32 + j;
-        valid[mb] = i < a.m;
-        const int64_t ii = valid[mb] ? i : a.m - 1;
+        int64_t i = wave0 + mb * 32 + j;
+        const int64_t total = CAND ? (int64_t)count : a.m;
+        valid[mb] = i < total;
+        int64_t ii = valid[mb] ? i : total - 1;
+        if constexpr (CAND) {
+            cut[mb] = valid[mb] ? a.cutv[ii] : NAN;     // no score compares >= NaN
+            ncand[mb] = 0;
+            ii = (int64_t)a.recheck[ii];
+        }
         const int64_t row = a.idx ? (int64_t)a.idx[ii] : ii;
         const float* xr = a.X + row * a.ldx;
 #pragma unroll
@@ -337,10 +368,24 @@ __global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2
                     __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);     // one LDS read
                 }
             }
-            // fold the 16 scores of each block into the running triple: four VALU instructions per score
             const int tile = st * (kNodesPerStage / 32) + nb;
+            if constexpr (CAND) {
 #pragma unroll
-            for (int mb = 0; mb < MS; ++mb) {
+                for (int mb = 0; mb < MS; ++mb) {
+                    uint16_t* slots = a.cand + ((size_t)(wave0 + mb * 32 + j) * 2 + g) * kCandSlots;
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        if (acc[mb][r] >= cut[mb]) {
+                            if (ncand[mb] < kCandSlots - 1)
+                                slots[1 + ncand[mb]] = (uint16_t)(tile * 32 + 8 * (r >> 2) + 4 * g + (r & 3));
+                            ++ncand[mb];
+                        }
+                    }
+                }
+            }
+            // fold the 16 scores of each block into the running triple: four VALU instructions per score
+#pragma unroll
+            for (int mb = 0; mb < (CAND ? 0 : MS); ++mb) {
                 const float before = best[mb];
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
@@ -368,6 +413,13 @@ __global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2
         __syncthreads();
     }
 
+    if constexpr (CAND) {
+#pragma unroll
+        for (int mb = 0; mb < MS; ++mb)
+            if (valid[mb])
+                a.cand[((size_t)(wave0 + mb * 32 + j) * 2 + g) * kCandSlots] = (uint16_t)(ncand[mb] < 0xffff ? ncand[mb] : 0xffff);
+        return;
+    }
     // ---- join the two half-wavefronts, then lane (j, g) finishes block mp + g
     const float wmax2 = __uint_as_float(a.scal[0]);
     const float wmax = sqrtf(wmax2) * 1.000001f;
@@ -433,9 +485,35 @@ __global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2
                 qs2 += (double)r_part;
             }
         }
-        list_push(&a.scal[a.slot], a.recheck, close, i);
+        list_push(&a.scal[a.slot], a.recheck, a.cutv, close, i, r_best - bound);
     }
     if (a.qe) group_qe_add(a.qe_part, qs, qs2);
+}
+
+// two workgroups per compute unit (LDS-bound), i.e. two wavefronts per SIMD: the register budget is 256 VGPRs
+template <int STEPS, int MS>
+__global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 2))) bmu_kernel(const BmuArgs a)
+{
+    extern __shared__ float4 lds4[];
+    bmu_tile<STEPS, MS, false>(a, blockIdx.x, 0u, lds4);
+}
+
+// true when this call's list is long enough for the candidate pass to pay and fits its buffers (device-side: the
+// host does not know the list length)
+__device__ __forceinline__ bool cand_pass_serves(const BmuArgs& a, unsigned int count)
+{
+    return count > a.cand_min && count <= a.cand_cap;
+}
+
+// candidate pass: a fixed grid walks the tiles of the list
+template <int STEPS, int MS>
+__global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 2))) bmu_cand_kernel(const BmuArgs a)
+{
+    extern __shared__ float4 lds4[];
+    const unsigned int count = a.scal[a.slot];
+    if (!cand_pass_serves(a, count)) return;
+    constexpr int64_t per_tile = (int64_t)kWavesPerGroup * MS * 32;
+    for (int64_t t = blockIdx.x; t * per_tile < (int64_t)count; t += gridDim.x) bmu_tile<STEPS, MS, true>(a, t, count, lds4);
 }
 
 // ---------------------------------------------------------------------------------------------------------
@@ -443,8 +521,9 @@ __global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2
 // the accumulators of a stage's four node blocks stay live across the chunks, the samples' features of the
 // current chunk are re-read from memory (they stay cache-resident: one workgroup touches 128 rows).
 // ---------------------------------------------------------------------------------------------------------
-template <int STEPS>
-__global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 2))) bmu_wide_kernel(const BmuArgs a)
+// CAND as in bmu_tile: the candidate pass over the first `count` entries of the re-decision list.
+template <int STEPS, bool CAND>
+__device__ __forceinline__ void bmu_wide_tile(const BmuArgs& a, int64_t tile_index, unsigned int count, float4* lds4)
 {
     static_assert(STEPS % 4 == 0, "a lane's STEPS features are loaded as whole float4s");
     constexpr int CH = 2 * STEPS;                        // features per chunk
@@ -453,13 +532,19 @@ __global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2
     constexpr int STAGE_F4 = STAGE_FLOATS / 4;
     constexpr int PRE = STAGE_F4 / kThreads;
     static_assert(PRE <= 9, "stage copy holds at most nine float4 per thread");
-    extern __shared__ float4 lds4[];
     float* lds = reinterpret_cast<float*>(lds4);
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int j = lane & 31, g = lane >> 5;
-    const int64_t i = ((int64_t)blockIdx.x * kWavesPerGroup + wave) * 32 + j;
-    const bool valid = i < a.m;
-    const int64_t ii = valid ? i : a.m - 1;
+    const int64_t i = (tile_index * kWavesPerGroup + wave) * 32 + j;      // sample position, or list entry (CAND)
+    const int64_t total = CAND ? (int64_t)count : a.m;
+    const bool valid = i < total;
+    int64_t ii = valid ? i : total - 1;
+    float cut = NAN;                                                        // CAND; no score compares >= NaN
+    int ncand = 0;
+    if constexpr (CAND) {
+        if (valid) cut = a.cutv[ii];
+        ii = (int64_t)a.recheck[ii];
+    }
     const int64_t row = a.idx ? (int64_t)a.idx[ii] : ii;
     const float* xr = a.X + row * a.ldx;
 
@@ -480,16 +565,26 @@ __global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2
 
     floatx16 acc[NBS];
     int st = 0, ch = 0;
-    // centred features of the current chunk; centre[] is read through wave-uniform addresses (scalar loads) and is
-    // zero-padded to a multiple of 64 entries
-    // Lane (j, g) holds features 32 g + s (s = 0..31) of the chunk: contiguous, so whole chunks of suitably aligned
-    // rows come in as eight 16-byte loads per lane instead of 32 scattered dwords.
-    const bool wide_loads = (reinterpret_cast<uintptr_t>(a.X) % 16 == 0) && (a.ldx % 4 == 0);
+    // Centred features of the current chunk.  Lane (j, g) holds STEPS contiguous features of the chunk, the window the weight preparation laid the stage
+    // columns out for: [CH ch + STEPS g, + STEPS), moved back to [D - STEPS, D) where it would pass the end of the
+    // row.  Every chunk therefore comes in as STEPS / 4 16-byte loads per lane (4-byte aligned addresses are
+    // enough for them), with no bounds to check and nothing read outside the row.
+    auto window_of = [&](int chunk) {
+        const int first = CH * chunk + STEPS * g;
+        return first < a.D - STEPS ? first : a.D - STEPS;
+    };
     float x[STEPS];
+    {
+        const float* xc = xr + window_of(0);
+        const float* cc = a.centre + window_of(0);
 #pragma unroll
-    for (int s = 0; s < STEPS; ++s) {
-        const int f = STEPS * g + s;
-        x[s] = xr[f < a.D ? f : a.D - 1] - a.centre[f];            // centre[] is zero-padded to whole chunks
+        for (int t = 0; t < STEPS / 4; ++t) {
+            const float4 v = load4(xc + 4 * t), c = load4(cc + 4 * t);
+            x[4 * t + 0] = v.x - c.x;
+            x[4 * t + 1] = v.y - c.y;
+            x[4 * t + 2] = v.z - c.z;
+            x[4 * t + 3] = v.w - c.w;
+        }
     }
     for (int q = 0; q < nq; ++q) {
         const int buf = q & 1;
@@ -508,31 +603,21 @@ __global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2
         float xn[STEPS], cn[STEPS];
         {
             const int chn = (ch + 1 == nch) ? 0 : ch + 1;
-            const float4* cc = reinterpret_cast<const float4*>(a.centre + CH * chn + STEPS * g);
+            const int w0 = window_of(chn);
+            const float* cc = a.centre + w0;
+            const float* xc = xr + w0;
 #pragma unroll
             for (int t = 0; t < STEPS / 4; ++t) {
-                const float4 v = cc[t];
-                cn[4 * t + 0] = v.x;
-                cn[4 * t + 1] = v.y;
-                cn[4 * t + 2] = v.z;
-                cn[4 * t + 3] = v.w;
-            }
-            if (wide_loads && CH * chn + CH <= a.D) {
-                const float4* xc = reinterpret_cast<const float4*>(xr + CH * chn + STEPS * g);
-#pragma unroll
-                for (int t = 0; t < STEPS / 4; ++t) {
-                    const float4 v = xc[t];
-                    xn[4 * t + 0] = v.x;
-                    xn[4 * t + 1] = v.y;
-                    xn[4 * t + 2] = v.z;
-                    xn[4 * t + 3] = v.w;
-                }
-            } else {
-#pragma unroll
-                for (int s = 0; s < STEPS; ++s) {
-                    const int f = CH * chn + STEPS * g + s;
-                    xn[s] = xr[f < a.D ? f : a.D - 1];             // beyond D: meets zero weights
-                }
+                const float4 c = load4(cc + 4 * t);
+                cn[4 * t + 0] = c.x;
+                cn[4 * t + 1] = c.y;
+                cn[4 * t + 2] = c.z;
+                cn[4 * t + 3] = c.w;
+                const float4 v = load4(xc + 4 * t);
+                xn[4 * t + 0] = v.x;
+                xn[4 * t + 1] = v.y;
+                xn[4 * t + 2] = v.z;
+                xn[4 * t + 3] = v.w;
             }
         }
         __builtin_amdgcn_sched_barrier(0);
@@ -564,7 +649,19 @@ __global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2
                 part = __builtin_amdgcn_mfma_f32_32x32x2f32(wrow[2 * s], x[s], part, 0, 0, 0);
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[nb][r] += part[r];
-            if (ch == nch - 1) {
+            if (CAND && ch == nch - 1) {
+                const int tile = st * NBS + nb;
+                uint16_t* slots = a.cand + ((size_t)i * 2 + g) * kCandSlots;
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    if (acc[nb][r] >= cut) {
+                        if (ncand < kCandSlots - 1)
+                            slots[1 + ncand] = (uint16_t)(tile * 32 + 8 * (r >> 2) + 4 * g + (r & 3));
+                        ++ncand;
+                    }
+                }
+            }
+            if (!CAND && ch == nch - 1) {
                 const int tile = st * NBS + nb;
                 const float before = best;
 #pragma unroll
@@ -593,6 +690,10 @@ __global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2
         for (int s = 0; s < STEPS; ++s) x[s] = xn[s] - cn[s];
     }
 
+    if constexpr (CAND) {
+        if (valid) a.cand[((size_t)i * 2 + g) * kCandSlots] = (uint16_t)(ncand < 0xffff ? ncand : 0xffff);
+        return;
+    }
     // ---- join the two half-wavefronts; squared norm and exact winner distance from memory, half the features each
     int node = tsel * 32 + 8 * (rsel >> 2) + 4 * g + (rsel & 3);
     const float ob = __shfl_xor(best, 32), os = __shfl_xor(second, 32);
@@ -630,8 +731,25 @@ __global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2
             qs2 = (double)part;
         }
     }
-    list_push(&a.scal[a.slot], a.recheck, close, i);
+    list_push(&a.scal[a.slot], a.recheck, a.cutv, close, i, bst - bound);
     if (a.qe) group_qe_add(a.qe_part, qs, qs2);
+}
+
+template <int STEPS>
+__global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 2))) bmu_wide_kernel(const BmuArgs a)
+{
+    extern __shared__ float4 lds4[];
+    bmu_wide_tile<STEPS, false>(a, blockIdx.x, 0u, lds4);
+}
+
+template <int STEPS>
+__global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 2))) bmu_wide_cand_kernel(const BmuArgs a)
+{
+    extern __shared__ float4 lds4[];
+    const unsigned int count = a.scal[a.slot];
+    if (!cand_pass_serves(a, count)) return;
+    constexpr int64_t per_tile = (int64_t)kWavesPerGroup * 32;
+    for (int64_t t = blockIdx.x; t * per_tile < (int64_t)count; t += gridDim.x) bmu_wide_tile<STEPS, true>(a, t, count, lds4);
 }
 
 // ---------------------------------------------------------------------------------------------------------
@@ -642,8 +760,70 @@ __global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2
 // plain vector-ALU rate: 2 K D lane-operations per sample (2.6 ns at K = 1024, D = 50 on 256 compute units; 3.8 ns
 // measured with every sample listed).  Larger groups or prefetched weights were measured and change nothing.
 // ---------------------------------------------------------------------------------------------------------
+constexpr uint32_t kCandMin = 24576;            // shortest list the candidate pass serves
+constexpr size_t kCandCapMax = (size_t)1 << 24; // longest one (bounds the slot buffer at 512 MB + 64 MB)
+constexpr int kCandGrid = 2048;
 constexpr int kExactGroup = 8;
 constexpr int kExactNodesPerThread = 4;
+
+// ---------------------------------------------------------------------------------------------------------
+// Direct differences over the nodes the candidate pass noted (the true winner is among them: its score lies
+// within the rounding bound of the best one found).  Sixteen lanes per list entry, each a sixteenth of the
+// features; lowest distance, then lowest node index.  Entries whose slots overflowed (more than seven candidates
+// in one half) or that noted nothing (non-finite scores) go to the second list, which the all-nodes kernel serves.
+// ---------------------------------------------------------------------------------------------------------
+__global__ void __launch_bounds__(256) bmu_cand_exact_kernel(const BmuArgs a)
+{
+    const unsigned int count = a.scal[a.slot];
+    if (!cand_pass_serves(a, count)) return;
+    const int sub = threadIdx.x & 15;
+    constexpr unsigned int per_group = 256 / 16;
+    double qs = 0.0, qs2 = 0.0;
+    for (unsigned int p0 = blockIdx.x * per_group; p0 < count; p0 += gridDim.x * per_group) {
+        const unsigned int p = p0 + (threadIdx.x >> 4);
+        const bool live = p < count;
+        const unsigned int pc = live ? p : count - 1;
+        const int64_t i = (int64_t)a.recheck[pc];
+        const int64_t row = a.idx ? (int64_t)a.idx[i] : i;
+        const float* xr = a.X + row * a.ldx;
+        const uint16_t* slots = a.cand + (size_t)pc * 2 * kCandSlots;
+        const int c0 = slots[0], c1 = slots[kCandSlots];
+        bool served = c0 < kCandSlots && c1 < kCandSlots && c0 + c1 > 0;
+        float bd = INFINITY;
+        int bk = 0x7fffffff;
+        if (served) {
+            for (int t = 0; t < c0 + c1; ++t) {
+                const int k = (t < c0) ? slots[1 + t] : slots[kCandSlots + 1 + t - c0];
+                if (k >= a.K) continue;
+                const float* wr = a.W + (size_t)k * a.D;
+                float d = 0.0f;
+                for (int f = sub; f < a.D; f += 16) {
+                    const float df = xr[f] - wr[f];
+                    d = fmaf(df, df, d);
+                }
+                // the partners of these exchanges sit in the same sixteen lanes, which run this loop together
+                d += __shfl_xor(d, 8);
+                d += __shfl_xor(d, 4);
+                d += __shfl_xor(d, 2);
+                d += __shfl_xor(d, 1);
+                if (d < bd || (d == bd && k < bk)) {
+                    bd = d;
+                    bk = k;
+                }
+            }
+            served = bk < a.K;
+        }
+        const bool mine = live && sub == 0;
+        if (mine && served) {
+            a.bmu[i] = bk;
+            if (a.d2) a.d2[i] = bd;
+            qs += sqrt((double)bd);
+            qs2 += (double)bd;
+        }
+        list_push(&a.scal[a.slot2], a.recheck2, nullptr, mine && !served, i, 0.0f);
+    }
+    if (a.qe) group_qe_add(a.qe_part, qs, qs2);
+}
 
 __global__ void __launch_bounds__(256) bmu_exact_kernel(const BmuArgs a)
 {
@@ -654,10 +834,15 @@ __global__ void __launch_bounds__(256) bmu_exact_kernel(const BmuArgs a)
     const float* __restrict__ wt = a.wt;
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
-    const unsigned int count = a.scal[a.slot];
+    // the whole list, or what the candidate pass left over
+    const unsigned int listed = a.scal[a.slot];
+    const bool by_cand = cand_pass_serves(a, listed);
+    const unsigned int count = by_cand ? a.scal[a.slot2] : listed;
+    const uint32_t* __restrict__ list = by_cand ? a.recheck2 : a.recheck;
     if (blockIdx.x == 0 && tid == 0) {
-        atomicAdd(&a.scal[3], count);   // running total over the calls that share one weight preparation
-        a.scal[3 - a.slot] = 0u;        // the next call counts into the other slot (slots are 1 and 2)
+        atomicAdd(&a.scal[3], listed);  // running total over the calls that share one weight preparation
+        a.scal[3 - a.slot] = 0u;        // the next call counts into the other slots (1 and 2, 4 and 5)
+        a.scal[9 - a.slot2] = 0u;
     }
     double qs = 0.0, qs2 = 0.0;
     for (unsigned int g0 = blockIdx.x * kExactGroup; g0 < count; g0 += gridDim.x * kExactGroup) {
@@ -680,7 +865,7 @@ __global__ void __launch_bounds__(256) bmu_exact_kernel(const BmuArgs a)
                 for (int e = tid; e < kExactGroup * dn; e += 256) {
                     const int s = e / dn, d = e % dn;
                     const unsigned int ge = (g0 + s < count) ? g0 + s : count - 1;
-                    const int64_t i = (int64_t)a.recheck[ge];
+                    const int64_t i = (int64_t)list[ge];
                     const int64_t r = a.idx ? (int64_t)a.idx[i] : i;
                     xs[d * kExactGroup + s] = a.X[r * a.ldx + d0 + d];
                 }
@@ -761,7 +946,7 @@ __global__ void __launch_bounds__(256) bmu_exact_kernel(const BmuArgs a)
                 }
             }
             if (bk >= a.K) bk = 0; // only reachable with non-finite input
-            const int64_t i = (int64_t)a.recheck[g0 + tid];
+            const int64_t i = (int64_t)list[g0 + tid];
             a.bmu[i] = bk;
             if (a.d2) a.d2[i] = bd;
             qs += sqrt((double)bd);
@@ -891,6 +1076,63 @@ static int launch_bmu_wide(som_ctx* ctx, const BmuArgs& a)
     return check_hip(ctx, hipGetLastError(), "bmu (wide) kernel launch");
 }
 
+// grid of the candidate kernels: the tiles of the longest list they may serve, at most kCandGrid workgroups
+static unsigned cand_grid(const BmuArgs& a, int64_t per_tile)
+{
+    const int64_t most = a.m < (int64_t)a.cand_cap ? a.m : (int64_t)a.cand_cap;
+    const int64_t tiles = (most + per_tile - 1) / per_tile;
+    return (unsigned)(tiles < kCandGrid ? tiles : kCandGrid);
+}
+
+template <int STEPS>
+static int launch_bmu_wide_cand(som_ctx* ctx, const BmuArgs& a)
+{
+    constexpr size_t lds_bytes = 2 * (size_t)stage_floats_for(2 * STEPS + 1) * sizeof(float);
+    static bool attr_set = false;
+    auto kern = bmu_wide_cand_kernel<STEPS>;
+    if (!attr_set) {
+        if (int rc = check_hip(ctx,
+                               hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes),
+                               "raising the dynamic LDS limit"))
+            return rc;
+        attr_set = true;
+    }
+    hipLaunchKernelGGL(kern, dim3(cand_grid(a, (int64_t)kWavesPerGroup * 32)), dim3(kThreads), lds_bytes, ctx->stream, a);
+    return check_hip(ctx, hipGetLastError(), "bmu (wide) candidate kernel launch");
+}
+
+template <int STEPS, int MS>
+static int launch_bmu_cand(som_ctx* ctx, const BmuArgs& a)
+{
+    constexpr size_t lds_bytes = 2 * (size_t)stage_floats_for(2 * STEPS + 1) * sizeof(float);
+    static bool attr_set = false;
+    auto kern = bmu_cand_kernel<STEPS, MS>;
+    if (!attr_set) {
+        if (int rc = check_hip(ctx,
+                               hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes),
+                               "raising the dynamic LDS limit"))
+            return rc;
+        attr_set = true;
+    }
+    hipLaunchKernelGGL(kern, dim3(cand_grid(a, (int64_t)kWavesPerGroup * MS * 32)), dim3(kThreads), lds_bytes, ctx->stream,
+                       a);
+    return check_hip(ctx, hipGetLastError(), "bmu candidate kernel launch");
+}
+
+static int dispatch_bmu_cand(som_ctx* ctx, int steps, const BmuArgs& a)
+{
+    switch (steps) {
+    case 4: return launch_bmu_cand<4, 2>(ctx, a);
+    case 8: return launch_bmu_cand<8, 2>(ctx, a);
+    case 16: return launch_bmu_cand<16, 2>(ctx, a);
+    case 25: return launch_bmu_cand<25, 2>(ctx, a);
+    case 32: return launch_bmu_cand<32, 2>(ctx, a);
+    }
+    return fail(ctx, SOM_EINVAL, "no BMU kernel for %d steps", steps);
+}
+
 template <int STEPS, int MS>
 static int launch_bmu(som_ctx* ctx, const BmuArgs& a)
 {
@@ -927,6 +1169,7 @@ static int dispatch_bmu(som_ctx* ctx, int steps, const BmuArgs& a)
 int bmu_run(som_ctx* ctx, BmuPrep& prep, BmuArgs a)
 {
     if (a.m <= 0) return SOM_OK;
+    auto cand_cap_for = [](size_t cap) { return cap < kCandCapMax ? cap : kCandCapMax; };
     if ((size_t)a.m > ctx->recheck_cap) {
         if (ctx->recheck) {
             if (int rc = check_hip(ctx, hipStreamSynchronize(ctx->stream), "sync before workspace growth")) return rc;
@@ -934,11 +1177,14 @@ int bmu_run(som_ctx* ctx, BmuPrep& prep, BmuArgs a)
             ctx->recheck = nullptr;
             ctx->recheck_cap = 0;
         }
-        if (hipMalloc((void**)&ctx->recheck, (size_t)a.m * sizeof(uint32_t)) != hipSuccess) {
+        // sample positions [m], cuts [m], second list [cand_cap], candidate slots [cand_cap][2][kCandSlots]
+        const size_t cap = (size_t)a.m, ccap = cand_cap_for(cap);
+        const size_t bytes = cap * 8 + ccap * (4 + 2 * kCandSlots * sizeof(uint16_t));
+        if (hipMalloc((void**)&ctx->recheck, bytes) != hipSuccess) {
             (void)hipGetLastError();
             return fail(ctx, SOM_ENOMEM, "cannot allocate the %lld-entry recheck list", (long long)a.m);
         }
-        ctx->recheck_cap = (size_t)a.m;
+        ctx->recheck_cap = cap;
     }
     a.kpad = prep.kpad;
     a.stage = prep.stage;
@@ -946,10 +1192,20 @@ int bmu_run(som_ctx* ctx, BmuPrep& prep, BmuArgs a)
     a.centre = prep.centre;
     a.scal = prep.scal;
     a.recheck = ctx->recheck;
+    a.cutv = (float*)(ctx->recheck + ctx->recheck_cap);
+    a.recheck2 = ctx->recheck + 2 * ctx->recheck_cap;
+    a.cand = (uint16_t*)(a.recheck2 + cand_cap_for(ctx->recheck_cap));
+    a.cand_cap = (uint32_t)cand_cap_for(ctx->recheck_cap);
+    // The candidate pass repeats the search for the listed samples at matrix speed (under a nanosecond per sample
+    // at K D = 51200, against 3.8 ns for direct differences over all nodes) but has the latency of a whole tile, so
+    // it only serves lists above a minimum length; node ids are 16-bit there.
+    const bool cand_possible = a.K > 1 && a.K <= 65536 && a.m > (int64_t)kCandMin;
+    a.cand_min = cand_possible ? kCandMin : 0xffffffffu;
     a.qe_part = ctx->qe_part;
     // the list length restarts for every call (chunk): calls alternate between two counters, and each call's
     // exact pass clears the counter of the next one
     a.slot = 1 + (prep.calls & 1);
+    a.slot2 = 4 + (prep.calls & 1);
     ++prep.calls;
     hipEvent_t stop = nullptr;
     if (ctx->profiling) {
@@ -967,6 +1223,13 @@ int bmu_run(som_ctx* ctx, BmuPrep& prep, BmuArgs a)
                           : dispatch_bmu(ctx, prep.steps, a);
     if (stop) (void)hipEventRecord(stop, ctx->stream);
     if (rc) return rc;
+    if (cand_possible) {
+        rc = prep.nch > 1 ? (prep.steps == 28 ? launch_bmu_wide_cand<28>(ctx, a) : launch_bmu_wide_cand<32>(ctx, a))
+                          : dispatch_bmu_cand(ctx, prep.steps, a);
+        if (rc) return rc;
+        hipLaunchKernelGGL(bmu_cand_exact_kernel, dim3(1024), dim3(256), 0, ctx->stream, a);
+        if ((rc = check_hip(ctx, hipGetLastError(), "bmu candidate-distance launch"))) return rc;
+    }
     if (a.K > 1) {
         hipLaunchKernelGGL(bmu_exact_kernel, dim3(1024), dim3(256), 0, ctx->stream, a);
         if ((rc = check_hip(ctx, hipGetLastError(), "bmu exact-pass launch"))) return rc;

@@ -18,7 +18,9 @@ struct BmuPrep {
     float* stage = nullptr;        // [Kpad / 128][nch] blobs: 128 padded weight rows of a chunk, then -|w|^2 / 2
     float* wt = nullptr;           // [D][Kpad] transposed weights (as given, not centred)
     float* centre = nullptr;       // [D] column means of W; stage rows and sample registers hold values minus this
-    unsigned int* scal = nullptr;  // [0] = bits of max_k |w_k - centre|^2, [1], [2] = recheck-list length (alternating calls), [3] = total
+    // [0] = bits of max_k |w_k - centre|^2, [1], [2] = recheck-list length (alternating calls), [3] = total,
+    // [4], [5] = length of the second list (samples whose candidate slots overflowed; alternating calls)
+    unsigned int* scal = nullptr;
     int kpad = 0, steps = 0, stride = 0;
     int nch = 1;                   // feature chunks of 2 * steps features (1 unless D > 64)
     int calls = 0;                 // bmu_run calls served by this preparation (selects the list counter)
@@ -37,6 +39,14 @@ struct BmuArgs {
     unsigned int* scal;      // BmuPrep::scal
     int32_t slot;            // which of scal[1], scal[2] this call counts into
     uint32_t* recheck;       // [m] sample positions to re-decide
+    // Candidate pass (long lists only): the search is repeated for the listed samples, and every node whose score
+    // reaches the sample's cut is noted; direct differences are then taken over those few nodes only.
+    float* cutv;             // [m] per list entry: best score minus the rounding bound
+    uint16_t* cand;          // [cand_cap][2][kCandSlots]: per list entry and half-wavefront, [0] = count, then node ids
+    uint32_t* recheck2;      // [cand_cap] samples left to the all-nodes pass (slots overflowed, or no candidate)
+    int32_t slot2;           // which of scal[4], scal[5] counts recheck2
+    uint32_t cand_min;       // the candidate pass serves list lengths in (cand_min, cand_cap]
+    uint32_t cand_cap;
     int32_t* bmu;            // [m], always written
     float* d2;               // may be null
     double* qe;              // [2], accumulated (caller zeroes); may be null
@@ -44,6 +54,7 @@ struct BmuArgs {
 };
 
 constexpr int kQeSlots = 256;
+constexpr int kCandSlots = 8;         // uint16 per (list entry, half-wavefront): a count and up to seven node ids
 
 } // namespace som
 
@@ -58,7 +69,7 @@ struct som_ctx {
     // BMU workspaces (grown on demand)
     void* prep_blob = nullptr;
     size_t prep_bytes = 0;
-    uint32_t* recheck = nullptr;
+    uint32_t* recheck = nullptr;   // one allocation: sample positions [cap], cuts [cap], second list, candidate slots
     size_t recheck_cap = 0;
     int32_t* bmu_ws = nullptr;     // BMU indices of the epoch drivers (one chunk's worth)
     size_t bmu_elems = 0;

@@ -144,6 +144,54 @@ def test_bmu_sample_on_a_node(som):
     assert (d2.cpu().numpy()[:10] == 0).all() and (b_gpu.cpu().numpy()[:10] == np.arange(10)).all()
 
 
+@pytest.mark.parametrize("D,copies", [(50, 2), (50, 12), (20, 3), (100, 2), (130, 10)])
+def test_bmu_long_recheck_list(som, D, copies):
+    """Every node exists `copies` times, so every sample's best scores tie and the whole call lands on the
+    re-decision list, which is then long enough for the candidate pass: with few copies the candidates' direct
+    differences decide, with many the per-sample slots overflow and the all-nodes pass takes over.  Either way the
+    lowest index of the tied nodes must come out, for D <= 64 and for the feature-chunked kernel."""
+    m, distinct = 60_000, 96
+    gm = GaussianMixture(11 + D + copies, D, 5)
+    X = gm.rows(0, m)
+    base = X[draw_initial_rows(3, m, distinct)]
+    W = np.concatenate([base] * copies)
+    if copies == 3:
+        # a mixed case: a third of the nodes has nine more copies (overflow), samples near the others do not
+        W = np.concatenate([W, np.concatenate([base[:32]] * 9)])
+    d2 = torch.empty(m, dtype=torch.float32, device="cuda")
+    qe = torch.zeros(2, dtype=torch.float64, device="cuda")
+    idx = draw_subset(5, 0, m, 50_000) if D == 20 else None
+    b_gpu, _, _ = som.som_bmu(dev(X), dev(W), d2=d2[:50_000] if idx is not None else d2, qe=qe,
+                              idx=dev(idx.astype(np.int32)) if idx is not None else None)
+    som.som_sync()
+    n = 50_000 if idx is not None else m
+    b, best, _ = check_bmu(b_gpu.cpu().numpy(), d2.cpu().numpy()[:n], X, W, idx)
+    assert (b_gpu.cpu().numpy() < distinct).all()
+    q = qe.cpu().numpy()
+    assert abs(q[0] - np.sqrt(best).sum()) <= REL * np.sqrt(best).sum()
+    assert abs(q[1] - best.sum()) <= REL * best.sum()
+
+
+def test_bmu_long_recheck_list_with_near_copies(som):
+    """Near-copies (relative offsets around 1e-7) instead of exact ones: the scores cannot separate them, the
+    direct differences of the candidate pass must, and a second call on the same context (alternating list
+    counters) must give the same answer."""
+    m, distinct, D = 40_000, 200, 50
+    gm = GaussianMixture(77, D, 4)
+    X = gm.rows(0, m)
+    base = X[draw_initial_rows(4, m, distinct)]
+    rng = np.random.default_rng(5)
+    W = np.concatenate([base, base * (1 + rng.normal(size=base.shape).astype(np.float32) * np.float32(2e-7)),
+                        base + np.float32(1e-6)]).astype(np.float32)
+    Xd, Wd = dev(X), dev(W)
+    d2 = torch.empty(m, dtype=torch.float32, device="cuda")
+    b1, _, _ = som.som_bmu(Xd, Wd, d2=d2)
+    b1 = b1.cpu().numpy()
+    check_bmu(b1, d2.cpu().numpy(), X, W)
+    b2, _, _ = som.som_bmu(Xd, Wd)
+    assert (b2.cpu().numpy() == b1).all()
+
+
 # ------------------------------------------------------------------------------------------- stage 2
 @pytest.mark.parametrize("m,K,D", [(1, 1, 1), (1000, 100, 8), (50_000, 1024, 50), (30_001, 37, 64), (4096, 2000, 5),
                                    (20_000, 500, 63), (9000, 100, 200), (5000, 3000, 40), (40_000, 2048, 31)])
