@@ -201,6 +201,37 @@ __device__ __forceinline__ float4 load4(const float* p)
     return v;
 }
 
+// Up to seven 16-bit node ids and their count in 128 bits of registers.  A hit shifts the ids up by one place (the
+// oldest drops out at the top, the count keeps counting, so an overflow shows): no memory traffic while the scores
+// are being formed, one 16-byte store per lane at the end.
+struct CandSet {
+    unsigned long long lo = 0ull, hi = 0ull;
+    int n = 0;
+    // id = base + off
+    __device__ __forceinline__ void note(int base, int off)
+    {
+        // (The empty statement keeps the branch that skips these instructions when no lane of the wavefront has a
+        // hit, which is four times out of five: without it the compiler runs them under an empty mask, and every
+        // vector instruction here is paid for in matrix time.  Passing the base through it keeps the addition
+        // inside the skipped region as well.)
+        asm volatile("" : "+v"(base));
+        const int id = base + off;
+        hi = (hi << 16) | (lo >> 48);
+        lo = (lo << 16) | (unsigned long long)(unsigned int)id;
+        ++n;
+    }
+    __device__ __forceinline__ ulonglong2 packed() const
+    {
+        const unsigned long long c = (unsigned long long)(n < 0xffff ? n : 0xffff);
+        return make_ulonglong2(lo, (hi & 0xffffffffffffull) | (c << 48));
+    }
+};
+__device__ __forceinline__ int cand_count(const ulonglong2& v) { return (int)(v.y >> 48); }
+__device__ __forceinline__ int cand_id(const ulonglong2& v, int t)
+{
+    return (int)(((t < 4) ? (v.x >> (16 * t)) : (v.y >> (16 * (t - 4)))) & 0xffffull);
+}
+
 // plain v_max_f32: the scores are never signalling NaNs worth quieting, and every VALU instruction here is paid
 // for in matrix time (float32 MFMA and the vector ALU share the same lanes)
 __device__ __forceinline__ float vmax(float a, float b)
@@ -246,7 +277,7 @@ __device__ __forceinline__ void bmu_tile(const BmuArgs& a, int64_t tile_index, u
     float x[MS][STEPS];
     bool valid[MS];
     float cut[MS];          // CAND
-    int ncand[MS];          // CAND
+    CandSet noted[MS];      // CAND
     // (Staging the workgroup's rows through LDS with coalesced 16-byte loads was measured against this direct
     // gather and lost by 3 to 10 %: the gather is served by the vector L1, the staging adds two barriers.)
 #pragma unroll
@@ -257,7 +288,6 @@ __device__ __forceinline__ void bmu_tile(const BmuArgs& a, int64_t tile_index, u
         int64_t ii = valid[mb] ? i : total - 1;
         if constexpr (CAND) {
             cut[mb] = valid[mb] ? a.cutv[ii] : NAN;     // no score compares >= NaN
-            ncand[mb] = 0;
             ii = (int64_t)a.recheck[ii];
         }
         const int64_t row = a.idx ? (int64_t)a.idx[ii] : ii;
@@ -372,15 +402,9 @@ __device__ __forceinline__ void bmu_tile(const BmuArgs& a, int64_t tile_index, u
             if constexpr (CAND) {
 #pragma unroll
                 for (int mb = 0; mb < MS; ++mb) {
-                    uint16_t* slots = a.cand + ((size_t)(wave0 + mb * 32 + j) * 2 + g) * kCandSlots;
 #pragma unroll
-                    for (int r = 0; r < 16; ++r) {
-                        if (acc[mb][r] >= cut[mb]) {
-                            if (ncand[mb] < kCandSlots - 1)
-                                slots[1 + ncand[mb]] = (uint16_t)(tile * 32 + 8 * (r >> 2) + 4 * g + (r & 3));
-                            ++ncand[mb];
-                        }
-                    }
+                    for (int r = 0; r < 16; ++r)
+                        if (acc[mb][r] >= cut[mb]) noted[mb].note(tile * 32 + 4 * g, 8 * (r >> 2) + (r & 3));
                 }
             }
             // fold the 16 scores of each block into the running triple: four VALU instructions per score
@@ -417,7 +441,7 @@ __device__ __forceinline__ void bmu_tile(const BmuArgs& a, int64_t tile_index, u
 #pragma unroll
         for (int mb = 0; mb < MS; ++mb)
             if (valid[mb])
-                a.cand[((size_t)(wave0 + mb * 32 + j) * 2 + g) * kCandSlots] = (uint16_t)(ncand[mb] < 0xffff ? ncand[mb] : 0xffff);
+                a.cand[(size_t)(wave0 + mb * 32 + j) * 2 + g] = noted[mb].packed();
         return;
     }
     // ---- join the two half-wavefronts, then lane (j, g) finishes block mp + g
@@ -540,7 +564,7 @@ __device__ __forceinline__ void bmu_wide_tile(const BmuArgs& a, int64_t tile_ind
     const bool valid = i < total;
     int64_t ii = valid ? i : total - 1;
     float cut = NAN;                                                        // CAND; no score compares >= NaN
-    int ncand = 0;
+    CandSet noted;
     if constexpr (CAND) {
         if (valid) cut = a.cutv[ii];
         ii = (int64_t)a.recheck[ii];
@@ -651,15 +675,9 @@ __device__ __forceinline__ void bmu_wide_tile(const BmuArgs& a, int64_t tile_ind
             for (int r = 0; r < 16; ++r) acc[nb][r] += part[r];
             if (CAND && ch == nch - 1) {
                 const int tile = st * NBS + nb;
-                uint16_t* slots = a.cand + ((size_t)i * 2 + g) * kCandSlots;
 #pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    if (acc[nb][r] >= cut) {
-                        if (ncand < kCandSlots - 1)
-                            slots[1 + ncand] = (uint16_t)(tile * 32 + 8 * (r >> 2) + 4 * g + (r & 3));
-                        ++ncand;
-                    }
-                }
+                for (int r = 0; r < 16; ++r)
+                    if (acc[nb][r] >= cut) noted.note(tile * 32 + 4 * g, 8 * (r >> 2) + (r & 3));
             }
             if (!CAND && ch == nch - 1) {
                 const int tile = st * NBS + nb;
@@ -691,7 +709,7 @@ __device__ __forceinline__ void bmu_wide_tile(const BmuArgs& a, int64_t tile_ind
     }
 
     if constexpr (CAND) {
-        if (valid) a.cand[((size_t)i * 2 + g) * kCandSlots] = (uint16_t)(ncand < 0xffff ? ncand : 0xffff);
+        if (valid) a.cand[(size_t)i * 2 + g] = noted.packed();
         return;
     }
     // ---- join the two half-wavefronts; squared norm and exact winner distance from memory, half the features each
@@ -761,7 +779,7 @@ __global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2
 // measured with every sample listed).  Larger groups or prefetched weights were measured and change nothing.
 // ---------------------------------------------------------------------------------------------------------
 constexpr uint32_t kCandMin = 24576;            // shortest list the candidate pass serves
-constexpr size_t kCandCapMax = (size_t)1 << 24; // longest one (bounds the slot buffer at 512 MB + 64 MB)
+constexpr size_t kCandCapMax = (size_t)1 << 24; // longest one (bounds the candidate buffer at 512 MB + 64 MB)
 constexpr int kCandGrid = 2048;
 constexpr int kExactGroup = 8;
 constexpr int kExactNodesPerThread = 4;
@@ -778,41 +796,75 @@ __global__ void __launch_bounds__(256) bmu_cand_exact_kernel(const BmuArgs a)
     if (!cand_pass_serves(a, count)) return;
     const int sub = threadIdx.x & 15;
     constexpr unsigned int per_group = 256 / 16;
+    constexpr int kMost = 2 * (kCandSlots - 1);        // candidates of one sample at most
     double qs = 0.0, qs2 = 0.0;
     for (unsigned int p0 = blockIdx.x * per_group; p0 < count; p0 += gridDim.x * per_group) {
         const unsigned int p = p0 + (threadIdx.x >> 4);
         const bool live = p < count;
         const unsigned int pc = live ? p : count - 1;
         const int64_t i = (int64_t)a.recheck[pc];
+        const ulonglong2 h0 = a.cand[(size_t)pc * 2], h1 = a.cand[(size_t)pc * 2 + 1];
         const int64_t row = a.idx ? (int64_t)a.idx[i] : i;
         const float* xr = a.X + row * a.ldx;
-        const uint16_t* slots = a.cand + (size_t)pc * 2 * kCandSlots;
-        const int c0 = slots[0], c1 = slots[kCandSlots];
+        const int c0 = cand_count(h0), c1 = cand_count(h1);
         bool served = c0 < kCandSlots && c1 < kCandSlots && c0 + c1 > 0;
+        const int c = served ? c0 + c1 : 0;
+        // Both halves' candidates form one dense list of c places, taken four at a time (most samples have no more):
+        // the loads of a batch (four rows of W, a quarter of 64 features per lane) are issued together, and batches
+        // nobody in the wavefront needs are skipped.
         float bd = INFINITY;
         int bk = 0x7fffffff;
-        if (served) {
-            for (int t = 0; t < c0 + c1; ++t) {
-                const int k = (t < c0) ? slots[1 + t] : slots[kCandSlots + 1 + t - c0];
-                if (k >= a.K) continue;
-                const float* wr = a.W + (size_t)k * a.D;
-                float d = 0.0f;
-                for (int f = sub; f < a.D; f += 16) {
-                    const float df = xr[f] - wr[f];
-                    d = fmaf(df, df, d);
+        constexpr int kBatch = 4;
+        for (int t0 = 0; t0 < kMost; t0 += kBatch) {
+            if (__ballot(c > t0) == 0ull) break;
+            int node[kBatch];
+            float d[kBatch];
+#pragma unroll
+            for (int tt = 0; tt < kBatch; ++tt) {
+                const int t = t0 + tt, u = t - c0;
+                const int k = (t < c0) ? cand_id(h0, t < kCandSlots - 1 ? t : 0)
+                                       : cand_id(h1, u < kCandSlots - 1 ? u : 0);
+                node[tt] = (t < c && k < a.K) ? k : -1;
+                d[tt] = 0.0f;
+            }
+            for (int f0 = 0; f0 < a.D; f0 += 64) {
+                float xv[4], wv[kBatch][4];
+                int fo[4];
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const int f = f0 + 16 * q + sub;
+                    fo[q] = f < a.D ? f : -1;
+                    xv[q] = xr[fo[q] >= 0 ? f : a.D - 1];
                 }
-                // the partners of these exchanges sit in the same sixteen lanes, which run this loop together
-                d += __shfl_xor(d, 8);
-                d += __shfl_xor(d, 4);
-                d += __shfl_xor(d, 2);
-                d += __shfl_xor(d, 1);
-                if (d < bd || (d == bd && k < bk)) {
-                    bd = d;
+#pragma unroll
+                for (int tt = 0; tt < kBatch; ++tt) {
+                    const float* wr = a.W + (size_t)(node[tt] >= 0 ? node[tt] : 0) * a.D;
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) wv[tt][q] = wr[fo[q] >= 0 ? fo[q] : a.D - 1];
+                }
+#pragma unroll
+                for (int tt = 0; tt < kBatch; ++tt)
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        const float df = fo[q] >= 0 ? xv[q] - wv[tt][q] : 0.0f;
+                        d[tt] = fmaf(df, df, d[tt]);
+                    }
+            }
+#pragma unroll
+            for (int tt = 0; tt < kBatch; ++tt) {
+                float v = d[tt];
+                v += __shfl_xor(v, 8);
+                v += __shfl_xor(v, 4);
+                v += __shfl_xor(v, 2);
+                v += __shfl_xor(v, 1);
+                const int k = node[tt];
+                if (k >= 0 && (v < bd || (v == bd && k < bk))) {
+                    bd = v;
                     bk = k;
                 }
             }
-            served = bk < a.K;
         }
+        served = served && bk < a.K;
         const bool mine = live && sub == 0;
         if (mine && served) {
             a.bmu[i] = bk;
@@ -1177,9 +1229,10 @@ int bmu_run(som_ctx* ctx, BmuPrep& prep, BmuArgs a)
             ctx->recheck = nullptr;
             ctx->recheck_cap = 0;
         }
-        // sample positions [m], cuts [m], second list [cand_cap], candidate slots [cand_cap][2][kCandSlots]
-        const size_t cap = (size_t)a.m, ccap = cand_cap_for(cap);
-        const size_t bytes = cap * 8 + ccap * (4 + 2 * kCandSlots * sizeof(uint16_t));
+        // sample positions [cap], cuts [cap], second list [cand_cap], candidate sets [cand_cap][2]; the capacity is a
+        // multiple of four entries so that the 16-byte candidate sets stay aligned
+        const size_t cap = ((size_t)a.m + 3) / 4 * 4, ccap = cand_cap_for(cap);
+        const size_t bytes = cap * 8 + ccap * (4 + 2 * sizeof(ulonglong2));
         if (hipMalloc((void**)&ctx->recheck, bytes) != hipSuccess) {
             (void)hipGetLastError();
             return fail(ctx, SOM_ENOMEM, "cannot allocate the %lld-entry recheck list", (long long)a.m);
@@ -1194,7 +1247,7 @@ int bmu_run(som_ctx* ctx, BmuPrep& prep, BmuArgs a)
     a.recheck = ctx->recheck;
     a.cutv = (float*)(ctx->recheck + ctx->recheck_cap);
     a.recheck2 = ctx->recheck + 2 * ctx->recheck_cap;
-    a.cand = (uint16_t*)(a.recheck2 + cand_cap_for(ctx->recheck_cap));
+    a.cand = (ulonglong2*)(a.recheck2 + cand_cap_for(ctx->recheck_cap));
     a.cand_cap = (uint32_t)cand_cap_for(ctx->recheck_cap);
     // The candidate pass repeats the search for the listed samples at matrix speed (under a nanosecond per sample
     // at K D = 51200, against 3.8 ns for direct differences over all nodes) but has the latency of a whole tile, so
@@ -1227,7 +1280,7 @@ int bmu_run(som_ctx* ctx, BmuPrep& prep, BmuArgs a)
         rc = prep.nch > 1 ? (prep.steps == 28 ? launch_bmu_wide_cand<28>(ctx, a) : launch_bmu_wide_cand<32>(ctx, a))
                           : dispatch_bmu_cand(ctx, prep.steps, a);
         if (rc) return rc;
-        hipLaunchKernelGGL(bmu_cand_exact_kernel, dim3(1024), dim3(256), 0, ctx->stream, a);
+        hipLaunchKernelGGL(bmu_cand_exact_kernel, dim3(2048), dim3(256), 0, ctx->stream, a);
         if ((rc = check_hip(ctx, hipGetLastError(), "bmu candidate-distance launch"))) return rc;
     }
     if (a.K > 1) {

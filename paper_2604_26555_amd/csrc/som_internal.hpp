@@ -42,7 +42,7 @@ struct BmuArgs {
     // Candidate pass (long lists only): the search is repeated for the listed samples, and every node whose score
     // reaches the sample's cut is noted; direct differences are then taken over those few nodes only.
     float* cutv;             // [m] per list entry: best score minus the rounding bound
-    uint16_t* cand;          // [cand_cap][2][kCandSlots]: per list entry and half-wavefront, [0] = count, then node ids
+    ulonglong2* cand;        // [cand_cap][2]: per list entry and half-wavefront, seven 16-bit node ids and their count
     uint32_t* recheck2;      // [cand_cap] samples left to the all-nodes pass (slots overflowed, or no candidate)
     int32_t slot2;           // which of scal[4], scal[5] counts recheck2
     uint32_t cand_min;       // the candidate pass serves list lengths in (cand_min, cand_cap]
@@ -54,7 +54,7 @@ struct BmuArgs {
 };
 
 constexpr int kQeSlots = 256;
-constexpr int kCandSlots = 8;         // uint16 per (list entry, half-wavefront): a count and up to seven node ids
+constexpr int kCandSlots = 8;         // 16-bit places per (list entry, half-wavefront): up to seven node ids and a count
 
 } // namespace som
 
