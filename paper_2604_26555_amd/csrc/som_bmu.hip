@@ -549,7 +549,6 @@ __global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2
 template <int STEPS, bool CAND>
 __device__ __forceinline__ void bmu_wide_tile(const BmuArgs& a, int64_t tile_index, unsigned int count, float4* lds4)
 {
-    static_assert(STEPS % 4 == 0, "a lane's STEPS features are loaded as whole float4s");
     constexpr int CH = 2 * STEPS;                        // features per chunk
     constexpr int STRIDE = 2 * STEPS + 1, NBS = kNodesPerStage / 32;
     constexpr int STAGE_FLOATS = stage_floats_for(STRIDE);
@@ -592,7 +591,7 @@ __device__ __forceinline__ void bmu_wide_tile(const BmuArgs& a, int64_t tile_ind
     // Centred features of the current chunk.  Lane (j, g) holds STEPS contiguous features of the chunk, the window the weight preparation laid the stage
     // columns out for: [CH ch + STEPS g, + STEPS), moved back to [D - STEPS, D) where it would pass the end of the
     // row.  Every chunk therefore comes in as STEPS / 4 16-byte loads per lane (4-byte aligned addresses are
-    // enough for them), with no bounds to check and nothing read outside the row.
+    // enough for them; STEPS = 25 adds one dword), with no bounds to check and nothing read outside the row.
     auto window_of = [&](int chunk) {
         const int first = CH * chunk + STEPS * g;
         return first < a.D - STEPS ? first : a.D - STEPS;
@@ -609,6 +608,8 @@ __device__ __forceinline__ void bmu_wide_tile(const BmuArgs& a, int64_t tile_ind
             x[4 * t + 2] = v.z - c.z;
             x[4 * t + 3] = v.w - c.w;
         }
+#pragma unroll
+        for (int s = STEPS / 4 * 4; s < STEPS; ++s) x[s] = xc[s] - cc[s];
     }
     for (int q = 0; q < nq; ++q) {
         const int buf = q & 1;
@@ -642,6 +643,11 @@ __device__ __forceinline__ void bmu_wide_tile(const BmuArgs& a, int64_t tile_ind
                 xn[4 * t + 1] = v.y;
                 xn[4 * t + 2] = v.z;
                 xn[4 * t + 3] = v.w;
+            }
+#pragma unroll
+            for (int s = STEPS / 4 * 4; s < STEPS; ++s) {
+                cn[s] = cc[s];
+                xn[s] = xc[s];
             }
         }
         __builtin_amdgcn_sched_barrier(0);
@@ -1063,11 +1069,17 @@ int bmu_prepare(som_ctx* ctx, const float* W, int32_t K, int32_t D, BmuPrep* out
         steps = steps_for(D);
         nch = 1;
     } else {
-        // chunk width 56 or 64 features, whichever wastes less (a chunk costs about three MFMA steps of overhead)
-        const int n28 = (D + 55) / 56, n32 = (D + 63) / 64;
-        const bool narrow = n28 * (28 + 3) < n32 * (32 + 3);
-        steps = narrow ? 28 : 32;
-        nch = narrow ? n28 : n32;
+        // chunk width 50, 56 or 64 features, whichever wastes least (a chunk costs about three MFMA steps of
+        // overhead); the wider one on a tie
+        steps = 0;
+        nch = 0;
+        for (int cand : {32, 28, 25}) {
+            const int n = (D + 2 * cand - 1) / (2 * cand);
+            if (steps == 0 || n * (cand + 3) < nch * (steps + 3)) {
+                steps = cand;
+                nch = n;
+            }
+        }
     }
     const int stride = 2 * steps + 1;
     const int kpad = ((K + kNodesPerStage - 1) / kNodesPerStage) * kNodesPerStage;
@@ -1272,12 +1284,16 @@ int bmu_run(som_ctx* ctx, BmuPrep& prep, BmuArgs a)
         stop = ctx->prof_events[ctx->prof_used].second;
         ++ctx->prof_used;
     }
-    int rc = prep.nch > 1 ? (prep.steps == 28 ? launch_bmu_wide<28>(ctx, a) : launch_bmu_wide<32>(ctx, a))
+    int rc = prep.nch > 1 ? (prep.steps == 25   ? launch_bmu_wide<25>(ctx, a)
+                             : prep.steps == 28 ? launch_bmu_wide<28>(ctx, a)
+                                                : launch_bmu_wide<32>(ctx, a))
                           : dispatch_bmu(ctx, prep.steps, a);
     if (stop) (void)hipEventRecord(stop, ctx->stream);
     if (rc) return rc;
     if (cand_possible) {
-        rc = prep.nch > 1 ? (prep.steps == 28 ? launch_bmu_wide_cand<28>(ctx, a) : launch_bmu_wide_cand<32>(ctx, a))
+        rc = prep.nch > 1 ? (prep.steps == 25   ? launch_bmu_wide_cand<25>(ctx, a)
+                             : prep.steps == 28 ? launch_bmu_wide_cand<28>(ctx, a)
+                                                : launch_bmu_wide_cand<32>(ctx, a))
                           : dispatch_bmu_cand(ctx, prep.steps, a);
         if (rc) return rc;
         hipLaunchKernelGGL(bmu_cand_exact_kernel, dim3(2048), dim3(256), 0, ctx->stream, a);

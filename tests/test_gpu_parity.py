@@ -65,7 +65,8 @@ def check_bmu(b_gpu, d2_gpu, X, W, idx=None):
 @pytest.mark.parametrize("m,K,D", [
     (1, 1, 1), (5, 3, 2), (257, 5, 3), (1000, 100, 8), (10_000, 100, 8), (777, 130, 17), (3000, 128, 16),
     (4099, 1024, 50), (600, 300, 64), (2048, 257, 33),
-    (1000, 200, 65), (3000, 1024, 130), (500, 64, 300), (300, 130, 1000),      # feature-chunked kernel (D > 64)
+    (1000, 200, 65), (3000, 1024, 130), (500, 64, 300), (300, 130, 1000),      # feature-chunked kernel (D > 64):
+    (700, 150, 128), (900, 260, 111), (333, 129, 500),                         # chunks of 50, 56 and 64 features
 ])
 def test_bmu_matches_oracle(som, m, K, D):
     X, W = problem(100 + m + K + D, m, K, D)
