@@ -47,3 +47,22 @@ def draw_subset(seed: int, epoch: int, n: int, m: int) -> np.ndarray:
             merged = np.union1d(have, new[keep])
         have = merged
     return have.astype(np.uint32)
+
+
+def standardise(X: np.ndarray) -> np.ndarray:
+    """Feature-wise zero mean and unit variance (float64 statistics, float32 result), the preprocessing of the
+    paper's quality protocol (Section 4.1.1); constant features are only centred."""
+    mean = X.mean(axis=0, dtype=np.float64)
+    std = X.std(axis=0, dtype=np.float64)
+    std[std == 0.0] = 1.0
+    return ((X - mean) / std).astype(np.float32)
+
+
+def train_holdout_split(seed: int, n: int, train_fraction: float = 0.7):
+    """A seeded permutation of [0, n) cut into a training part and a holdout part (70 / 30 by default, Section
+    4.1.1), each returned as a sorted uint32 row list."""
+    if not (0.0 < train_fraction < 1.0) or n < 2:
+        raise ValueError("need 0 < train_fraction < 1 and n >= 2")
+    perm = np.random.default_rng([int(seed), 0x70]).permutation(n)
+    cut = min(max(int(round(n * train_fraction)), 1), n - 1)
+    return np.sort(perm[:cut]).astype(np.uint32), np.sort(perm[cut:]).astype(np.uint32)

@@ -11,7 +11,8 @@ import pytest
 import torch
 
 import oracle
-from synth import GaussianMixture, draw_initial_rows, draw_subset, linear_sigma, make_workload
+from synth import (GaussianMixture, draw_initial_rows, draw_subset, linear_sigma, make_workload, standardise,
+                   train_holdout_split)
 
 pytestmark = pytest.mark.gpu
 
@@ -540,6 +541,37 @@ def test_epochs_cfg0_free_running(som):
     som.som_bmu(Xd, Wd, qe=qe)
     final = oracle.quantization_error(oracle.bmu(X, W)[1])
     assert abs(qe[0].item() / wl.n - final) <= 1e-3 * final
+
+
+def test_holdout_projection_quantisation_errors(som):
+    """The paper's quality endpoints (Section 4.1.2): a map is trained on the 70 % training part of a standardised
+    matrix (the part is presented through its row list), then both parts are projected onto it; QE_T, QE_H and
+    their mean QE_B must equal the oracle's values for the same weights, and training must have lowered both."""
+    wl = make_workload("cfg0", topology="hex")
+    X = standardise(wl.data().rows(0, 30_000))
+    train, hold = train_holdout_split(wl.seed, len(X))
+    assert len(train) == 21_000 and len(np.intersect1d(train, hold)) == 0
+    W0 = X[train[draw_initial_rows(wl.seed, len(train), wl.k)]].copy()
+    G = oracle.graph_distances(wl.topology, lattice=wl.lattice).astype(np.float32)
+    Xd, Wd, Gd = dev(X), dev(W0), dev(G)
+    tr_d, ho_d = dev(train.astype(np.int32)), dev(hold.astype(np.int32))
+
+    def project(rows_d):
+        qe = torch.zeros(2, dtype=torch.float64, device="cuda")
+        som.som_bmu(Xd, Wd, idx=rows_d, qe=qe)
+        return float(qe.cpu()[0]) / rows_d.numel()
+
+    before = (project(tr_d), project(ho_d))
+    for sigma in linear_sigma(wl.sigma[0], wl.sigma[1], 8):
+        som.som_epoch(Xd, Wd, Gd, sigma, idx=tr_d)
+    qe_t, qe_h = project(tr_d), project(ho_d)
+    W = Wd.cpu().numpy()
+    ref_t = oracle.quantization_error(oracle.bmu(X[train.astype(np.int64)], W)[1])
+    ref_h = oracle.quantization_error(oracle.bmu(X[hold.astype(np.int64)], W)[1])
+    assert abs(qe_t - ref_t) <= REL * ref_t and abs(qe_h - ref_h) <= REL * ref_h
+    assert abs(0.5 * (qe_t + qe_h) - 0.5 * (ref_t + ref_h)) <= REL * ref_t
+    assert qe_t < before[0] and qe_h < before[1]
+    assert qe_t <= qe_h * 1.02          # the map fits the part it saw at least as well as the part it did not
 
 
 def test_empty_and_degenerate_epochs(som):
