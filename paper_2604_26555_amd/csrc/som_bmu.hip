@@ -251,7 +251,8 @@ __device__ __forceinline__ float vmax(float a, float b)
 // lane's own slots: lane (j, g) sees the nodes of half g only, so no two lanes share a slot and no atomics are
 // needed).  One compare per score instead of four fold instructions.
 template <int STEPS, int MS, bool CAND>
-__device__ __forceinline__ void bmu_tile(const BmuArgs& a, int64_t tile_index, unsigned int count, float4* lds4)
+__device__ __forceinline__ void bmu_tile(const BmuArgs& a, int64_t first, int64_t tile_index, unsigned int count,
+                                         float4* lds4)
 {
     constexpr int STRIDE = 2 * STEPS + 1;
     constexpr int STAGE_FLOATS = stage_floats_for(STRIDE);   // whole float4s per thread: no tail handling
@@ -264,7 +265,7 @@ __device__ __forceinline__ void bmu_tile(const BmuArgs& a, int64_t tile_index, u
     const int wave = tid >> 6;
     const int j = lane & 31;
     const int g = lane >> 5;
-    const int64_t wave0 = (tile_index * kWavesPerGroup + wave) * (MS * 32);
+    const int64_t wave0 = first + (tile_index * kWavesPerGroup + wave) * (MS * 32);   // first = position of tile 0
 
     // centre[2 s + g]: both candidates are read through wave-uniform addresses (scalar loads), the lane picks one
     // (the array is zero-padded to a multiple of 64 entries, so no index needs a bound)
@@ -519,7 +520,14 @@ template <int STEPS, int MS>
 __global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 2))) bmu_kernel(const BmuArgs a)
 {
     extern __shared__ float4 lds4[];
-    bmu_tile<STEPS, MS, false>(a, blockIdx.x, 0u, lds4);
+    // The first full_tiles workgroups take MS blocks per wavefront; the rest of the grid, the last partial round
+    // of the launch, takes tiles of half that size, which spread more evenly over the compute units.
+    if ((int64_t)blockIdx.x < a.full_tiles) {
+        bmu_tile<STEPS, MS, false>(a, 0, blockIdx.x, 0u, lds4);
+    } else if constexpr (MS > 1) {
+        constexpr int64_t per_full = (int64_t)kWavesPerGroup * MS * 32;
+        bmu_tile<STEPS, MS / 2, false>(a, a.full_tiles * per_full, (int64_t)blockIdx.x - a.full_tiles, 0u, lds4);
+    }
 }
 
 // true when this call's list is long enough for the candidate pass to pay and fits its buffers (device-side: the
@@ -537,7 +545,7 @@ __global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2
     const unsigned int count = a.scal[a.slot];
     if (!cand_pass_serves(a, count)) return;
     constexpr int64_t per_tile = (int64_t)kWavesPerGroup * MS * 32;
-    for (int64_t t = blockIdx.x; t * per_tile < (int64_t)count; t += gridDim.x) bmu_tile<STEPS, MS, true>(a, t, count, lds4);
+    for (int64_t t = blockIdx.x; t * per_tile < (int64_t)count; t += gridDim.x) bmu_tile<STEPS, MS, true>(a, 0, t, count, lds4);
 }
 
 // ---------------------------------------------------------------------------------------------------------
@@ -1212,9 +1220,28 @@ static int launch_bmu(som_ctx* ctx, const BmuArgs& a)
             return rc;
         attr_set = true;
     }
+    // Two workgroups fit a compute unit, so the grid runs in rounds of 2 * units tiles and a unit's time in the
+    // last, partial round goes with the number of sample blocks it gets.  When halving the tiles of that round
+    // lowers the largest share (measured at 10^6 samples on 256 units: 7.63 rounds cost as much as 8), they are
+    // halved.
+    if (ctx->units == 0) {
+        int units = 0;
+        if (hipDeviceGetAttribute(&units, hipDeviceAttributeMultiprocessorCount, ctx->device) != hipSuccess || units < 1)
+            units = 256;
+        ctx->units = units;
+    }
     const int64_t per_group = (int64_t)kWavesPerGroup * MS * 32;
-    const int64_t groups = (a.m + per_group - 1) / per_group;
-    hipLaunchKernelGGL(kern, dim3((unsigned)groups), dim3(kThreads), lds_bytes, ctx->stream, a);
+    const int64_t tiles = (a.m + per_group - 1) / per_group;
+    const int64_t units = ctx->units, rem = tiles % (2 * units);
+    BmuArgs b = a;
+    b.full_tiles = tiles;
+    int64_t groups = tiles;
+    if (MS > 1 && tiles >= 2 * units && rem > 0 && (2 * rem + units - 1) / units < 2 * ((rem + units - 1) / units)) {
+        b.full_tiles = tiles - rem;
+        const int64_t left = a.m - b.full_tiles * per_group, per_half = per_group / 2;
+        groups = b.full_tiles + (left + per_half - 1) / per_half;
+    }
+    hipLaunchKernelGGL(kern, dim3((unsigned)groups), dim3(kThreads), lds_bytes, ctx->stream, b);
     return check_hip(ctx, hipGetLastError(), "bmu kernel launch");
 }
 

@@ -38,6 +38,7 @@ struct BmuArgs {
     const float* centre;     // BmuPrep::centre
     unsigned int* scal;      // BmuPrep::scal
     int32_t slot;            // which of scal[1], scal[2] this call counts into
+    int64_t full_tiles;      // bmu_kernel: workgroups below this number take full tiles, the others half tiles
     uint32_t* recheck;       // [m] sample positions to re-decide
     // Candidate pass (long lists only): the search is repeated for the listed samples, and every node whose score
     // reaches the sample's cut is noted; direct differences are then taken over those few nodes only.
@@ -60,6 +61,7 @@ constexpr int kCandSlots = 8;         // 16-bit places per (list entry, half-wav
 
 struct som_ctx {
     int device = 0;
+    int units = 0;                 // compute units of the device (queried on first use)
     hipStream_t stream = nullptr;
     hipStream_t copy_stream = nullptr;
     char err[512] = {0};

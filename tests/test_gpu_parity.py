@@ -196,7 +196,8 @@ def test_bmu_long_recheck_list_with_near_copies(som):
 
 # ------------------------------------------------------------------------------------------- stage 2
 @pytest.mark.parametrize("m,K,D", [(1, 1, 1), (1000, 100, 8), (50_000, 1024, 50), (30_001, 37, 64), (4096, 2000, 5),
-                                   (20_000, 500, 63), (9000, 100, 200), (5000, 3000, 40), (40_000, 2048, 31)])
+                                   (20_000, 500, 63), (9000, 100, 200), (5000, 3000, 40), (40_000, 2048, 31),
+                                   (3000, 6000, 63)])     # the last one: more node slabs than the LDS paths take
 def test_accumulate_matches_oracle(som, m, K, D):
     """Both accumulation kernels: the default one (float64 LDS atomics) and the fixed-order one."""
     X, W = problem(200 + m + K, m, min(K, m), D)
