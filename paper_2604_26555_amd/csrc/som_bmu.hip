@@ -1054,7 +1054,7 @@ __global__ void __launch_bounds__(kQeSlots) qe_finish_kernel(double* __restrict_
 static int steps_for(int D)
 {
     const int need = (D + 1) / 2;
-    const int avail[] = {4, 8, 16, 25, 32};
+    const int avail[] = {4, 8, 12, 16, 20, 25, 28, 32};   // MFMA steps per block; the smallest that holds D
     for (int s : avail)
         if (need <= s) return s;
     return 0;
@@ -1198,8 +1198,11 @@ static int dispatch_bmu_cand(som_ctx* ctx, int steps, const BmuArgs& a)
     switch (steps) {
     case 4: return launch_bmu_cand<4, 2>(ctx, a);
     case 8: return launch_bmu_cand<8, 2>(ctx, a);
+    case 12: return launch_bmu_cand<12, 2>(ctx, a);
     case 16: return launch_bmu_cand<16, 2>(ctx, a);
+    case 20: return launch_bmu_cand<20, 2>(ctx, a);
     case 25: return launch_bmu_cand<25, 2>(ctx, a);
+    case 28: return launch_bmu_cand<28, 2>(ctx, a);
     case 32: return launch_bmu_cand<32, 2>(ctx, a);
     }
     return fail(ctx, SOM_EINVAL, "no BMU kernel for %d steps", steps);
@@ -1250,8 +1253,11 @@ static int dispatch_bmu(som_ctx* ctx, int steps, const BmuArgs& a)
     switch (steps) {
     case 4: return launch_bmu<4, 2>(ctx, a);
     case 8: return launch_bmu<8, 2>(ctx, a);
+    case 12: return launch_bmu<12, 2>(ctx, a);
     case 16: return launch_bmu<16, 2>(ctx, a);
+    case 20: return launch_bmu<20, 2>(ctx, a);
     case 25: return launch_bmu<25, 2>(ctx, a);
+    case 28: return launch_bmu<28, 2>(ctx, a);
     case 32: return launch_bmu<32, 2>(ctx, a);
     }
     return fail(ctx, SOM_EINVAL, "no BMU kernel for %d steps", steps);

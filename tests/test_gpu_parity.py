@@ -65,7 +65,7 @@ def check_bmu(b_gpu, d2_gpu, X, W, idx=None):
 # ------------------------------------------------------------------------------------------- stage 1
 @pytest.mark.parametrize("m,K,D", [
     (1, 1, 1), (5, 3, 2), (257, 5, 3), (1000, 100, 8), (10_000, 100, 8), (777, 130, 17), (3000, 128, 16),
-    (4099, 1024, 50), (600, 300, 64), (2048, 257, 33),
+    (4099, 1024, 50), (600, 300, 64), (2048, 257, 33), (1500, 300, 24), (2500, 260, 40), (1800, 140, 55),
     (1000, 200, 65), (3000, 1024, 130), (500, 64, 300), (300, 130, 1000),      # feature-chunked kernel (D > 64):
     (700, 150, 128), (900, 260, 111), (333, 129, 500),                         # chunks of 50, 56 and 64 features
 ])
