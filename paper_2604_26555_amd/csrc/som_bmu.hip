@@ -17,10 +17,11 @@
 // Exactness.  Scores are formed on centred values x - c, w - c (c = column means of W: distances are unchanged,
 // magnitudes shrink to the spread of the map).  float32 accumulation leaves an error of at most
 // (roundings) * 2^-24 * (|x - c| max|w - c| + max|w - c|^2 / 2) in a score, so a sample whose best two scores are
-// closer than that worst-case bound is put on a list and re-decided by a second kernel that evaluates
-// sum_d (x_d - w_kd)^2 directly, on the values as given, for every node (lowest index wins ties).  For all other
-// samples the winner's squared distance is recomputed by direct differences as well, so the reported distances
-// never carry the cancellation error of the score form.
+// closer than that worst-case bound is put on a list and re-decided by direct differences sum_d (x_d - w_kd)^2 on
+// the values as given (lowest index wins ties): over every node (bmu_exact_kernel), or, for long lists, over the
+// few nodes whose score lies inside the bound, which a second pass of the search collects (bmu_cand_kernel,
+// bmu_cand_exact_kernel).  For all other samples the winner's squared distance is recomputed by direct differences
+// as well, so the reported distances never carry the cancellation error of the score form.
 #include "som_internal.hpp"
 
 #include <hip/amd_detail/amd_hip_unsafe_atomics.h>
@@ -549,9 +550,9 @@ __global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2
 }
 
 // ---------------------------------------------------------------------------------------------------------
-// the same search for D > 64: features go through in chunks of 64.  A wavefront owns one block of 32 samples;
-// the accumulators of a stage's four node blocks stay live across the chunks, the samples' features of the
-// current chunk are re-read from memory (they stay cache-resident: one workgroup touches 128 rows).
+// the same search for D > 64: features go through in chunks of 50, 56 or 64.  A wavefront owns one block of 32
+// samples; the accumulators of a stage's four node blocks stay live across the chunks, the samples' features of
+// the current chunk are re-read from memory once per stage (one workgroup touches 128 rows).
 // ---------------------------------------------------------------------------------------------------------
 // CAND as in bmu_tile: the candidate pass over the first `count` entries of the re-decision list.
 template <int STEPS, bool CAND>
