@@ -45,9 +45,16 @@ constexpr int stage_floats_for(int stride)
 // Weight preparation: padded rows + half squared norms per (128-node stage, feature chunk), transposed copy,
 // largest squared norm (scal[0], cleared beforehand), and the zeroing of the result words the later kernels count
 // into.  A chunk holds stride - 1 features and one zero column (odd row stride); maps with D <= 64 have a single
-// chunk.  One thread per element of the padded matrix (coalesced reads of W); the first kpad threads also compute
-// their node's norm in float64.
+// chunk.  One thread per element of the padded matrix (coalesced reads of W); the first kpad / 4 wavefronts also
+// compute four nodes' norms each, in float64.
 // ---------------------------------------------------------------------------------------------------------
+__device__ __forceinline__ double wave_sum(double v)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+    return v;
+}
+
 // centre[f] = mean over nodes of W[k][f], f < D; zero up to the next multiple of 64.  Any vector would do (distances do not change when the same vector is
 // taken off samples and weights); the mean keeps |w_k - centre| as small as the spread of the map.
 __global__ void __launch_bounds__(1024) bmu_centre_kernel(const float* __restrict__ W, int K, int D, float* __restrict__ centre,
@@ -107,26 +114,48 @@ __global__ void __launch_bounds__(256) bmu_prep_kernel(const float* __restrict__
         const float v = real ? W[(size_t)k * D + f] : 0.0f;
         const int st = k / kNodesPerStage, r = k % kNodesPerStage;
         stage[((size_t)st * nch + ch) * stage_floats + (size_t)r * stride + fl] = real ? v - centre[f] : 0.0f;
-        if (own) wt[(size_t)f * kpad + k] = v;
     }
-    if (e < kpad) {
-        // squared norm of the centred row exactly as the stage holds it (float32 differences), summed in float64
-        const int k = e;
-        double nrm = 0.0;
-        if (k < K)
-            for (int f = 0; f < D; ++f) {
-                const double v = (double)(W[(size_t)k * D + f] - centre[f]);
-                nrm += v * v;
+    // transposed copy, one thread per element with the node running fastest: coalesced writes (the reads, one row
+    // apart, come from L2; written from the loop above the copy was 50,000 scattered 4-byte stores)
+    if (e < D * kpad) {
+        const int f = e / kpad, kk = e - f * kpad;
+        wt[e] = (kk < K) ? W[(size_t)kk * D + f] : 0.0f;
+    }
+    // squared norm of the centred row exactly as the stage holds it (float32 differences), summed in float64: the
+    // first kpad / 4 wavefronts of the grid take four nodes each (coalesced reads of their rows), and a workgroup
+    // hands its largest norm to scal[0] with one atomic (one per node, all on the same word, took 10 us)
+    __shared__ float wg_up[4];
+    const int wv = e >> 6, lane = e & 63;
+    float up_max = 0.0f;
+    if (wv * 4 < kpad) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const int k = wv * 4 + q;
+            double nrm = 0.0;
+            if (k < K)
+                for (int f = lane; f < D; f += 64) {
+                    const double v = (double)(W[(size_t)k * D + f] - centre[f]);
+                    nrm += v * v;
+                }
+            nrm = wave_sum(nrm);
+            if (lane == 0 && k < kpad) {
+                const int st = k / kNodesPerStage, r = k % kNodesPerStage;
+                const float nh = (k < K) ? (float)(-0.5 * nrm) : -INFINITY;
+                for (int ch = 0; ch < nch; ++ch)
+                    stage[((size_t)st * nch + ch) * stage_floats + (size_t)kNodesPerStage * stride + r] = nh;
+                if (k < K) {
+                    float up = (float)nrm;
+                    if ((double)up < nrm) up = nextafterf(up, INFINITY);
+                    up_max = fmaxf(up_max, up);
+                }
             }
-        const int st = k / kNodesPerStage, r = k % kNodesPerStage;
-        const float nh = (k < K) ? (float)(-0.5 * nrm) : -INFINITY;
-        for (int ch = 0; ch < nch; ++ch)
-            stage[((size_t)st * nch + ch) * stage_floats + (size_t)kNodesPerStage * stride + r] = nh;
-        if (k < K) {
-            float up = (float)nrm;
-            if ((double)up < nrm) up = nextafterf(up, INFINITY);
-            atomicMax(&scal[0], __float_as_uint(up));
         }
+    }
+    if (lane == 0) wg_up[threadIdx.x >> 6] = up_max;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        const float m = fmaxf(fmaxf(wg_up[0], wg_up[1]), fmaxf(wg_up[2], wg_up[3]));
+        if (m > 0.0f) atomicMax(&scal[0], __float_as_uint(m));
     }
 }
 
@@ -139,12 +168,6 @@ __global__ void fill_zero_kernel(uint32_t* p, size_t words)
 // ---------------------------------------------------------------------------------------------------------
 // helpers
 // ---------------------------------------------------------------------------------------------------------
-__device__ __forceinline__ double wave_sum(double v)
-{
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
-    return v;
-}
 
 // Sum of distances and squared distances of a workgroup's samples -> one of kQeSlots partial-sum slots.  Every
 // wavefront adding to the same two words would serialise tens of thousands of atomics on one address; one pair
@@ -1123,7 +1146,10 @@ int bmu_prepare(som_ctx* ctx, const float* W, int32_t K, int32_t D, BmuPrep* out
     out->calls = 0;
     hipLaunchKernelGGL(bmu_centre_kernel, dim3((unsigned)(centre_bytes / 256)), dim3(1024), 0, ctx->stream, W, K, D,
                        out->centre, out->scal);
-    const long long elems = (long long)kpad * nch * stride;
+    // one thread per element of the padded stage matrix and of the transposed copy, one wavefront per four nodes
+    long long elems = (long long)kpad * nch * stride;
+    if (elems < (long long)kpad * 16) elems = (long long)kpad * 16;
+    if (elems < (long long)kpad * D) elems = (long long)kpad * D;
     hipLaunchKernelGGL(bmu_prep_kernel, dim3((unsigned)((elems + 255) / 256)), dim3(256), 0, ctx->stream, W, K, D, kpad,
                        stride, nch, stage_floats_for(stride), out->centre, out->stage, out->wt, out->scal, qe, small);
     return check_hip(ctx, hipGetLastError(), "bmu_prep launch");
