@@ -22,6 +22,8 @@
 
 #include <hip/amd_detail/amd_hip_unsafe_atomics.h>
 
+#include <type_traits>
+
 namespace som {
 
 constexpr int kFThreads = 1024;
@@ -90,34 +92,60 @@ __global__ void __launch_bounds__(kFThreads) accumulate_f64_kernel(const float* 
             const bool in = b >= k0 && b < k0 + kn;
             unsigned long long todo = __ballot(in);                        // wave-uniform: lanes whose row is ours
             const float* xpass = X + (base + q) * ldx;
-            const int nloc = b - k0;
-            int p_last = 0;
+            const int ncell = (b - k0) * DS;                                // this lane's row of P, if its sample is ours
             // Rows are taken off the mask with scalar instructions only (find-first-set, read-lane): no list in
-            // LDS, no wait between a row's decoding and its load, so G row loads are in flight per wavefront.
-            while (todo != 0ull) {
-                float v[G];
-                int cell[G];
-                const float* xrow[G];
-                bool live[G];
+            // LDS, no wait between a row's decoding and its load, so up to G row loads are in flight per wavefront.
+            // The scalar unit is shared by the compute unit's wavefronts and this bookkeeping is what it is busy
+            // with, so whole batches (eight rows, then four) run without per-row conditions, four scalar
+            // instructions a row; what is left of the pass goes through one batch of four places whose empty ones
+            // repeat the last row's load and skip the addition.
+            int left = __popcll(todo);
+            const int f = lane - 1;                                         // lane 0 carries the count
+            const int fcl = f < 0 ? 0 : (f < D ? f : D - 1);
+            auto whole_batch = [&](auto width) {
+                constexpr int GB = decltype(width)::value;
+                float v[GB];
+                int cell[GB];
 #pragma unroll
-                for (int t = 0; t < G; ++t) {
+                for (int t = 0; t < GB; ++t) {
+                    const int p = __builtin_ctzll(todo);                    // todo has at least GB bits set here
+                    asm("s_bitset0_b64 %0, %1" : "+s"(todo) : "s"(p));
+                    // plain variant: 32-bit offset from the pass's first row (63 U rows of ldx floats stay far
+                    // below 2^31)
+                    const float* xrow = GATHER ? X + (int64_t)idx[base + U * p + q] * ldx : xpass + (unsigned)(p * ldxu);
+                    cell[t] = __builtin_amdgcn_readlane(ncell, p);
+                    const float xv = xrow[fcl];
+                    v[t] = (lane == 0) ? 1.0f : xv;
+                }
+                if (lane < DS) {
+#pragma unroll
+                    for (int t = 0; t < GB; ++t) unsafeAtomicAdd(&P[cell[t] + lane], (double)v[t]);
+                }
+                left -= GB;
+            };
+            while (left >= G) whole_batch(std::integral_constant<int, G>{});
+            if (left >= G / 2) whole_batch(std::integral_constant<int, G / 2>{});
+            if (left > 0) {
+                constexpr int GB = G / 2;
+                float v[GB];
+                int cell[GB];
+                bool live[GB];
+                int p_last = 0;
+#pragma unroll
+                for (int t = 0; t < GB; ++t) {
                     live[t] = todo != 0ull;
                     const int p = live[t] ? (int)__ffsll((long long)todo) - 1 : p_last;
                     if (live[t]) {
                         todo &= todo - 1ull;
                         p_last = p;
                     }
-                    // plain variant: 32-bit offset from the pass's first row (63 U rows of ldx floats stay far
-                    // below 2^31)
-                    xrow[t] = GATHER ? X + (int64_t)idx[base + U * p + q] * ldx : xpass + p * ldxu;
-                    cell[t] = __builtin_amdgcn_readlane(nloc, p) * DS;
-                    // one pass of 64 lanes per row: lane 0 carries the count, lane l > 0 feature l - 1
-                    const int f = lane - 1;
-                    const float xv = xrow[t][f < 0 ? 0 : (f < D ? f : D - 1)];
+                    const float* xrow = GATHER ? X + (int64_t)idx[base + U * p + q] * ldx : xpass + (unsigned)(p * ldxu);
+                    cell[t] = __builtin_amdgcn_readlane(ncell, p);
+                    const float xv = xrow[fcl];
                     v[t] = (lane == 0) ? 1.0f : xv;
                 }
 #pragma unroll
-                for (int t = 0; t < G; ++t) {
+                for (int t = 0; t < GB; ++t) {
                     if (live[t]) {
                         if (lane < DS) unsafeAtomicAdd(&P[cell[t] + lane], (double)v[t]);
                     }
