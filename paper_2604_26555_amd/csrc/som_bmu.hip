@@ -496,14 +496,15 @@ __device__ __forceinline__ void bmu_tile(const BmuArgs& a, int64_t first, int64_
             node = node < a.K ? node : a.K - 1;
             // squared norm of the centred sample and squared distance to the winner (both centred the same way),
             // half the features per lane
+            // (the winner's centred weights come from its stage row, which holds them in this lane's order with
+            // zeros beyond D: no centring and no bounds here)
             float xn = 0.f, part = 0.f;
-            const float* wr = a.W + (size_t)node * a.D;
+            const float* wr = a.stage + (size_t)(node / kNodesPerStage) * STAGE_FLOATS +
+                              (size_t)(node % kNodesPerStage) * STRIDE + g;
 #pragma unroll
             for (int s = 0; s < STEPS; ++s) {
-                const int f = 2 * s + g;
-                const float wv = wr[f < a.D ? f : a.D - 1] - centre_of(s);
-                const float xm = (f < a.D) ? x[mb][s] : 0.0f;
-                const float df = (f < a.D) ? x[mb][s] - wv : 0.0f;
+                const float xm = (2 * s + g < a.D) ? x[mb][s] : 0.0f;
+                const float df = xm - wr[2 * s];
                 xn = fmaf(xm, xm, xn);
                 part = fmaf(df, df, part);
             }
