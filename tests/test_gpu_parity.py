@@ -174,6 +174,20 @@ def test_bmu_long_recheck_list(som, D, copies):
     assert abs(q[1] - best.sum()) <= REL * best.sum()
 
 
+def test_bmu_long_recheck_list_on_a_map_too_large_for_16_bit_node_ids(som):
+    """More than 65536 nodes: the candidate pass (16-bit node ids) must stand aside and the all-nodes pass decide
+    the whole list."""
+    m, distinct, D = 26_000, 33_000, 3
+    rng = np.random.default_rng(8)
+    base = rng.normal(size=(distinct, D)).astype(np.float32)
+    W = np.concatenate([base, base])                                   # 66000 nodes, every one twice
+    X = rng.normal(size=(m, D)).astype(np.float32)
+    b_gpu, _, _ = som.som_bmu(dev(X), dev(W))
+    b_gpu = b_gpu.cpu().numpy()
+    check_bmu(b_gpu, None, X, W)
+    assert (b_gpu < distinct).all()
+
+
 def test_bmu_long_recheck_list_with_near_copies(som):
     """Near-copies (relative offsets around 1e-7) instead of exact ones: the scores cannot separate them, the
     direct differences of the candidate pass must, and a second call on the same context (alternating list
