@@ -8,8 +8,8 @@
 //   boruvka_*          spanning tree for K <= 4096: <= log2 K rounds of (cheapest outgoing edge per node over all
 //                      compute units, per-component minimum + merge in one workgroup)
 //   mst_prim_kernel    spanning tree for larger K: Prim's method in one workgroup, K rounds of (arg-min, key update)
-//   rng_block_kernel   a 32 x 32 tile of pairs per workgroup; third nodes staged through LDS 64 at a time;
-//                      pair (p, q) survives unless some r has max(d2[p][r], d2[q][r]) < d2[p][q]
+//   rng_near / rng_prefilter / rng_verify   pair (p, q) survives unless some r has max(d2[p][r], d2[q][r]) <
+//                      d2[p][q]: every pair against 64 nodes near p first, the few pairs left against all nodes
 //   csr_*              degree count, exclusive scan, ascending neighbour lists
 //   bfs_kernel         one workgroup per source, level-synchronous search with the distance row in LDS
 #include "som_internal.hpp"
@@ -251,53 +251,101 @@ __global__ void __launch_bounds__(1024) boruvka_merge_kernel(int K, int* __restr
     if (tid == 0) state[0] = count;
 }
 
-// adjacency matrix A <- relative neighbourhood graph.  Workgroup = 32 x 32 pairs (p in tile bx, q in tile by >= bx;
-// the criterion is symmetric, so the tile below the diagonal is written from the one above).  The scan over third
-// nodes stops as soon as every pair of the tile has found a blocker.
-__global__ void __launch_bounds__(256) rng_block_kernel(const double* __restrict__ d2, int K, unsigned char* __restrict__ A)
+// Relative neighbourhood graph: pair (p, q) is an edge unless some third node r has
+// max(d2[p][r], d2[q][r]) < d2[p][q].  Testing every r for every pair is K^3 / 2 comparisons, and almost every pair
+// is blocked by a node close to one of its ends, so the test runs in three steps, all on the float64 distances:
+//   rng_near_kernel       64 nodes near p for every p (the nearest one of every residue class modulo 64)
+//   rng_prefilter_kernel  every pair against the 64 nodes near its lower end, nearest first; A = 1 where none blocks
+//   rng_verify_kernel     the pairs left (the edges and a few more) against all nodes
+// A blocker found in the second step is a blocker; a pair the second step leaves gets the complete test.  The
+// result is the one the plain triple loop gives.
+constexpr int kNear = 64;
+
+__global__ void __launch_bounds__(256) rng_near_kernel(const double* __restrict__ d2, int K, int* __restrict__ near)
 {
-    if (blockIdx.x > blockIdx.y) return;
-    __shared__ double P[32][65];   // d2[p0 + i][r0 + j]
-    __shared__ double Q[32][65];
-    const int tid = threadIdx.x;
-    const int p0 = blockIdx.x * 32, q0 = blockIdx.y * 32;
-    // thread -> four pairs: p = p0 + (tid / 32) + 8 t, q = q0 + tid % 32
-    const int pi = tid >> 5, qi = tid & 31;
-    double lim[4];
-    bool blocked[4];
-#pragma unroll
-    for (int t = 0; t < 4; ++t) {
-        const int p = p0 + pi + 8 * t, q = q0 + qi;
-        const bool real = p < K && q < K && p != q;
-        lim[t] = real ? d2[(size_t)p * K + q] : 0.0;
-        blocked[t] = !real;                               // nothing to decide for padding and for the diagonal
-    }
-    for (int r0 = 0; r0 < K; r0 += 64) {
-        // also the barrier that frees P and Q; every thread evaluates it the same number of times
-        if (__syncthreads_and(blocked[0] && blocked[1] && blocked[2] && blocked[3])) break;
-        for (int e = tid; e < 32 * 64; e += 256) {
-            const int i = e >> 6, jj = e & 63;
-            const int r = r0 + jj;
-            const bool in = r < K;
-            P[i][jj] = (in && p0 + i < K) ? d2[(size_t)(p0 + i) * K + r] : INFINITY;
-            Q[i][jj] = (in && q0 + i < K) ? d2[(size_t)(q0 + i) * K + r] : INFINITY;
-        }
-        __syncthreads();
-        // r = p and r = q give max = d2[p][q] itself, never strictly smaller: no masking needed
-#pragma unroll 8
-        for (int jj = 0; jj < 64; ++jj) {
-            const double qv = Q[qi][jj];
-#pragma unroll
-            for (int t = 0; t < 4; ++t) blocked[t] = blocked[t] || (fmax(P[pi + 8 * t][jj], qv) < lim[t]);
+    const int lane = threadIdx.x & 63;
+    const int p = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (p >= K) return;
+    const double* row = d2 + (size_t)p * K;
+    double bv = INFINITY;
+    int br = -1;
+    for (int r = lane; r < K; r += kNear) {
+        const double v = row[r];
+        if (r != p && v < bv) {
+            bv = v;
+            br = r;
         }
     }
+    near[(size_t)p * kNear + lane] = br;
+}
+
+// one workgroup per lower end p; thread -> upper ends q = tid, tid + 256, ...
+__global__ void __launch_bounds__(256) rng_prefilter_kernel(const double* __restrict__ d2, int K,
+                                                            const int* __restrict__ near, unsigned char* __restrict__ A)
+{
+    __shared__ int nr_in[kNear], nr[kNear];
+    __shared__ double dpr_in[kNear], dpr[kNear];
+    const int tid = threadIdx.x, p = blockIdx.x;
+    const double* rp = d2 + (size_t)p * K;
+    if (tid < kNear) {
+        const int r = near[(size_t)p * kNear + tid];
+        nr_in[tid] = r;
+        dpr_in[tid] = (r >= 0) ? rp[r] : INFINITY;
+    }
+    __syncthreads();
+    if (tid < kNear) {
+        // nearest first (rank by distance, then by place): the closest nodes block most pairs
+        const double mine = dpr_in[tid];
+        int rank = 0;
+        for (int o = 0; o < kNear; ++o) rank += (dpr_in[o] < mine || (dpr_in[o] == mine && o < tid)) ? 1 : 0;
+        nr[rank] = nr_in[tid];
+        dpr[rank] = mine;
+    }
+    __syncthreads();
+    for (int q = tid; q < K; q += 256) {
+        if (q == p) A[(size_t)p * K + p] = 0;
+        if (q <= p) continue;
+        const double lim = rp[q];
+        bool blocked = false;
+        for (int o = 0; o < kNear && !blocked; ++o) {
+            if (!(dpr[o] < lim)) break;                       // sorted: no later node is closer to p than the pair is long
+            blocked = d2[(size_t)nr[o] * K + q] < lim;
+        }
+        const unsigned char keep = blocked ? 0 : 1;
+        A[(size_t)p * K + q] = keep;
+        A[(size_t)q * K + p] = keep;
+    }
+}
+
+// one workgroup per lower end p; a wavefront takes the surviving pairs of 64 upper ends at a time, all its lanes
+// scan the third nodes of one pair together
+__global__ void __launch_bounds__(256) rng_verify_kernel(const double* __restrict__ d2, int K, unsigned char* __restrict__ A)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, p = blockIdx.x;
+    const double* rp = d2 + (size_t)p * K;
+    for (int qb = wave * 64; qb < K; qb += 256) {
+        const int q = qb + lane;
+        const bool alive = q > p && q < K && A[(size_t)p * K + q] != 0;
+        unsigned long long mask = __ballot(alive);
+        while (mask != 0ull) {
+            const int qq = qb + (int)__ffsll((long long)mask) - 1;
+            mask &= mask - 1ull;
+            const double lim = rp[qq];
+            const double* rq = d2 + (size_t)qq * K;
+            bool found = false;
+            // r = p and r = q give max = d2[p][q] itself, never strictly smaller: no masking needed
+            for (int r0 = 0; r0 < K; r0 += 4 * 64) {
 #pragma unroll
-    for (int t = 0; t < 4; ++t) {
-        const int p = p0 + pi + 8 * t, q = q0 + qi;
-        if (p < K && q < K) {
-            const unsigned char keep = (p != q && !blocked[t]) ? 1 : 0;
-            A[(size_t)p * K + q] = keep;
-            A[(size_t)q * K + p] = keep;
+                for (int u = 0; u < 4; ++u) {
+                    const int r = r0 + 64 * u + lane;
+                    if (r < K) found = found || (fmax(rp[r], rq[r]) < lim);
+                }
+                if (__any(found)) break;
+            }
+            if (__any(found) && lane == 0) {
+                A[(size_t)p * K + qq] = 0;
+                A[(size_t)qq * K + p] = 0;
+            }
         }
     }
 }
@@ -404,7 +452,8 @@ extern "C" int som_topology(som_ctx* ctx, const float* W, int32_t K, int32_t D, 
     if (K > 12000) return fail(ctx, SOM_EINVAL, "K = %d is above the 12000 nodes the graph kernels hold in LDS", K);
     if (int rc = check_hip(ctx, hipSetDevice(ctx->device), "hipSetDevice")) return rc;
     const size_t kk = (size_t)K * K;
-    const size_t need = kk * sizeof(double) + (size_t)K * sizeof(double) + ((size_t)4 * K + 8 + kk) * sizeof(int) + kk + 1024;
+    const size_t need = kk * sizeof(double) + (size_t)K * sizeof(double) + ((size_t)4 * K + 8 + kk) * sizeof(int) + kk + 1024 +
+                        (size_t)K * kNear * sizeof(int);
     if (need > ctx->topo_bytes) {
         if (ctx->topo_blob) {
             if (int rc = check_hip(ctx, hipStreamSynchronize(ctx->stream), "sync before workspace growth")) return rc;
@@ -427,6 +476,7 @@ extern "C" int som_topology(som_ctx* ctx, const float* W, int32_t K, int32_t D, 
     int* state = best_u + K;                             // 4 entries
     int* nbr = state + 4;                                // at most K * K entries
     unsigned char* A = (unsigned char*)(nbr + kk);
+    int* near = (int*)(A + (kk + 1023) / 1024 * 1024);   // K * kNear entries (relative neighbourhood graph only)
     const dim3 tiles((K + 31) / 32, (K + 31) / 32);
     hipLaunchKernelGGL(node_d2_kernel, tiles, dim3(256), 0, ctx->stream, W, K, D, d2);
     if (int rc = check_hip(ctx, hipGetLastError(), "node distance launch")) return rc;
@@ -449,7 +499,9 @@ extern "C" int som_topology(som_ctx* ctx, const float* W, int32_t K, int32_t D, 
         }
         hipLaunchKernelGGL(mst_prim_kernel, dim3(1), dim3(1024), lds, ctx->stream, d2, K, A);
     } else {
-        hipLaunchKernelGGL(rng_block_kernel, tiles, dim3(256), 0, ctx->stream, d2, K, A);
+        hipLaunchKernelGGL(rng_near_kernel, dim3((K + 3) / 4), dim3(256), 0, ctx->stream, d2, K, near);
+        hipLaunchKernelGGL(rng_prefilter_kernel, dim3(K), dim3(256), 0, ctx->stream, d2, K, near, A);
+        hipLaunchKernelGGL(rng_verify_kernel, dim3(K), dim3(256), 0, ctx->stream, d2, K, A);
     }
     if (int rc = check_hip(ctx, hipGetLastError(), "edge kernel launch")) return rc;
     hipLaunchKernelGGL(csr_degree_kernel, dim3((K + 3) / 4), dim3(256), 0, ctx->stream, A, K, deg);
