@@ -11,7 +11,7 @@
 //   rng_near / rng_prefilter / rng_verify   pair (p, q) survives unless some r has max(d2[p][r], d2[q][r]) <
 //                      d2[p][q]: every pair against 64 nodes near p first, the few pairs left against all nodes
 //   csr_*              degree count, exclusive scan, ascending neighbour lists
-//   bfs_kernel         one workgroup per source, level-synchronous search with the distance row in LDS
+//   bfs_kernel         one wavefront per source, frontier queue and distance row in LDS
 #include "som_internal.hpp"
 
 #include <math.h>
@@ -406,35 +406,50 @@ __global__ void __launch_bounds__(256) csr_fill_kernel(const unsigned char* __re
     }
 }
 
-// hop counts from source = blockIdx.x to every node
-__global__ void __launch_bounds__(256) bfs_kernel(const int* __restrict__ off, const int* __restrict__ nbr, int K,
-                                                  float* __restrict__ G)
+// Hop counts from source = blockIdx.x to every node: one wavefront per source, no barriers.  dist[] (int32) and the
+// visiting order (uint16 queue, every node enters once) live in LDS; the frontier is the queue segment
+// [head, tail).  Lanes take one frontier node each and walk its neighbour list in step; a neighbour is claimed with
+// a compare-and-swap on its distance, and the claimed ones of a step are appended through a ballot (the queue
+// position is a wave-uniform register, not a counter in memory).  LDS operations of one wavefront execute in
+// order, so a later step sees the earlier steps' claims and queue entries.
+__global__ void __launch_bounds__(64) bfs_kernel(const int* __restrict__ off, const int* __restrict__ nbr, int K,
+                                                 float* __restrict__ G)
 {
-    extern __shared__ int bfs_dist[];      // [K]
-    __shared__ int changed;
-    const int tid = threadIdx.x, src = blockIdx.x;
-    for (int v = tid; v < K; v += 256) bfs_dist[v] = (v == src) ? 0 : -1;
-    __syncthreads();
-    for (int level = 0; level < K; ++level) {
-        if (tid == 0) changed = 0;
-        __syncthreads();
-        for (int v = tid; v < K; v += 256) {
-            if (bfs_dist[v] == level) {
-                for (int e = off[v]; e < off[v + 1]; ++e) {
-                    const int u = nbr[e];
-                    if (bfs_dist[u] < 0) {           // every writer stores the same value
-                        bfs_dist[u] = level + 1;
-                        changed = 1;
-                    }
+    extern __shared__ int bfs_lds[];
+    int* dist = bfs_lds;                                                       // [K]
+    unsigned short* queue = reinterpret_cast<unsigned short*>(bfs_lds + K);    // [K]
+    const int lane = threadIdx.x, src = blockIdx.x;
+    for (int v = lane; v < K; v += 64) dist[v] = (v == src) ? 0 : -1;
+    if (lane == 0) queue[0] = (unsigned short)src;
+    int head = 0, tail = 1;
+    for (int level = 0; head < tail; ++level) {
+        const int end = tail;
+        for (int base = head; base < end; base += 64) {
+            const int i = base + lane;
+            const bool has = i < end;
+            const int v = has ? (int)queue[i] : 0;
+            int e = has ? off[v] : 0;
+            const int e1 = has ? off[v + 1] : 0;
+            while (__any(e < e1)) {
+                bool won = false;
+                int u = 0;
+                if (e < e1) {
+                    u = nbr[e];
+                    ++e;
+                    won = atomicCAS(&dist[u], -1, level + 1) == -1;
                 }
+                const unsigned long long mask = __ballot(won);
+                if (won) {
+                    const int below = __builtin_amdgcn_mbcnt_hi((unsigned)(mask >> 32), __builtin_amdgcn_mbcnt_lo((unsigned)mask, 0));
+                    queue[tail + below] = (unsigned short)u;
+                }
+                tail += __popcll(mask);
             }
         }
-        __syncthreads();
-        if (!changed) break;
-        __syncthreads();
+        head = end;
     }
-    for (int v = tid; v < K; v += 256) {
-        const int d = bfs_dist[v];
+    for (int v = lane; v < K; v += 64) {
+        const int d = dist[v];
         G[(size_t)src * K + v] = d < 0 ? INFINITY : (float)d;
     }
 }
@@ -508,6 +523,11 @@ extern "C" int som_topology(som_ctx* ctx, const float* W, int32_t K, int32_t D, 
     hipLaunchKernelGGL(csr_scan_kernel, dim3(1), dim3(1024), 0, ctx->stream, deg, K, off);
     hipLaunchKernelGGL(csr_fill_kernel, dim3((K + 3) / 4), dim3(256), 0, ctx->stream, A, K, off, nbr);
     if (int rc = check_hip(ctx, hipGetLastError(), "adjacency launch")) return rc;
-    hipLaunchKernelGGL(bfs_kernel, dim3(K), dim3(256), (size_t)K * sizeof(int), ctx->stream, off, nbr, K, G);
+    // dist[K] int32 + queue[K] uint16 per wavefront (72 KB at the 12000-node limit)
+    const size_t bfs_lds_bytes = ((size_t)K * 6 + 3) / 4 * 4;
+    if (bfs_lds_bytes > 48 * 1024) {
+        if (int rc = check_hip(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(bfs_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, 12000 * 6), "raising the dynamic LDS limit")) return rc;
+    }
+    hipLaunchKernelGGL(bfs_kernel, dim3(K), dim3(64), bfs_lds_bytes, ctx->stream, off, nbr, K, G);
     return check_hip(ctx, hipGetLastError(), "hop-count launch");
 }
