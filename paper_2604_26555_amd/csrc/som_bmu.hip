@@ -35,6 +35,11 @@ typedef float floatx16 __attribute__((ext_vector_type(16)));
 constexpr int kWavesPerGroup = 4;
 constexpr int kThreads = kWavesPerGroup * 64;
 
+constexpr uint32_t kCandMin = 10240;            // shortest list the candidate pass serves
+constexpr uint32_t kCandHalfTiles = 65536;      // up to this length its tiles are halved (one per compute unit and more)
+constexpr size_t kCandCapMax = (size_t)1 << 24; // longest one (bounds the candidate buffer at 512 MB + 64 MB)
+constexpr int kCandGrid = 2048;
+
 // floats of one 128-node stage (padded rows + half squared norms), rounded up to one float4 per thread
 constexpr int stage_floats_for(int stride)
 {
@@ -570,6 +575,15 @@ __global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2
     const unsigned int count = a.scal[a.slot];
     if (!cand_pass_serves(a, count)) return;
     constexpr int64_t per_tile = (int64_t)kWavesPerGroup * MS * 32;
+    if constexpr (MS > 1) {
+        // a list that leaves compute units idle goes through in tiles of half the size: twice as many workgroups,
+        // each done in half the time
+        if (count <= kCandHalfTiles) {
+            for (int64_t t = blockIdx.x; t * (per_tile / 2) < (int64_t)count; t += gridDim.x)
+                bmu_tile<STEPS, MS / 2, true>(a, 0, t, count, lds4);
+            return;
+        }
+    }
     for (int64_t t = blockIdx.x; t * per_tile < (int64_t)count; t += gridDim.x) bmu_tile<STEPS, MS, true>(a, 0, t, count, lds4);
 }
 
@@ -817,9 +831,6 @@ __global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2
 // plain vector-ALU rate: 2 K D lane-operations per sample (2.6 ns at K = 1024, D = 50 on 256 compute units; 3.8 ns
 // measured with every sample listed).  Larger groups or prefetched weights were measured and change nothing.
 // ---------------------------------------------------------------------------------------------------------
-constexpr uint32_t kCandMin = 24576;            // shortest list the candidate pass serves
-constexpr size_t kCandCapMax = (size_t)1 << 24; // longest one (bounds the candidate buffer at 512 MB + 64 MB)
-constexpr int kCandGrid = 2048;
 constexpr int kExactGroup = 8;
 constexpr int kExactNodesPerThread = 4;
 
