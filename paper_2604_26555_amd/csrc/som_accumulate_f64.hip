@@ -9,7 +9,7 @@
 // coalesced 64-lane load (lane 0 adds the count, lane l > 0 feature l - 1), followed by one LDS atomic instruction.
 // Wavefronts work independently: each reads the BMUs of 256 consecutive samples with one 16-byte load per lane (a
 // round ahead), and in four passes of 64 samples takes the rows that belong to the slab off a ballot mask with
-// scalar instructions, eight rows at a time (that many row loads in flight); there is no barrier and no LDS traffic
+// scalar instructions, up to sixteen rows at a time (that many row loads in flight); there is no barrier and no LDS traffic
 // other than the atomics inside the range loop.  Knock-out timings (10^7 rows, 608 us): without the row loads 454,
 // without the atomics 606, with neither 449: what bounds the kernel next to the memory system is the per-row
 // bookkeeping on the scalar unit, which the wavefronts of a compute unit share.
@@ -58,7 +58,7 @@ __global__ void __launch_bounds__(kFThreads) accumulate_f64_kernel(const float* 
     for (int c = tid; c < ks * DS; c += kFThreads) P[c] = 0.0;
     __syncthreads();
 
-    constexpr int G = 8;                                                  // rows in flight per wavefront
+    constexpr int G = 16;                                                 // rows in flight per wavefront
     constexpr int U = 4;                                                  // 64-row passes per load of BMU indices
     // A wavefront takes 64 U consecutive samples at a time: lane l holds the BMUs of samples base + U l .. + U - 1
     // (one 16-byte load, requested a whole round of U passes ahead: with one pass per load the wait for the indices
@@ -96,9 +96,9 @@ __global__ void __launch_bounds__(kFThreads) accumulate_f64_kernel(const float* 
             // Rows are taken off the mask with scalar instructions only (find-first-set, read-lane): no list in
             // LDS, no wait between a row's decoding and its load, so up to G row loads are in flight per wavefront.
             // The scalar unit is shared by the compute unit's wavefronts and this bookkeeping is what it is busy
-            // with, so whole batches (eight rows, then four) run without per-row conditions, four scalar
-            // instructions a row; what is left of the pass goes through one batch of four places whose empty ones
-            // repeat the last row's load and skip the addition.
+            // with, so whole batches (sixteen rows, then eight, then four) run without per-row conditions, three
+            // scalar instructions a row; what is left of the pass goes through one batch of four places whose empty
+            // ones repeat the last row's load and skip the addition.
             int left = __popcll(todo);
             const int f = lane - 1;                                         // lane 0 carries the count
             const int fcl = f < 0 ? 0 : (f < D ? f : D - 1);
@@ -125,8 +125,9 @@ __global__ void __launch_bounds__(kFThreads) accumulate_f64_kernel(const float* 
             };
             while (left >= G) whole_batch(std::integral_constant<int, G>{});
             if (left >= G / 2) whole_batch(std::integral_constant<int, G / 2>{});
+            if (left >= G / 4) whole_batch(std::integral_constant<int, G / 4>{});
             if (left > 0) {
-                constexpr int GB = G / 2;
+                constexpr int GB = G / 4;
                 float v[GB];
                 int cell[GB];
                 bool live[GB];
