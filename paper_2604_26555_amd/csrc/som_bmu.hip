@@ -279,7 +279,9 @@ __device__ __forceinline__ float vmax(float a, float b)
 // formed again, and instead of the fold every score that reaches the entry's cut is noted (node id into the
 // lane's own slots: lane (j, g) sees the nodes of half g only, so no two lanes share a slot and no atomics are
 // needed).  One compare per score instead of four fold instructions.
-template <int STEPS, int MS, bool CAND>
+// PAD = true: the last stage ends in whole blocks of padding nodes (K is at least 32 short of a multiple of 128),
+// which are skipped; a variant of its own so that the stage body of the other maps stays one basic block.
+template <int STEPS, int MS, bool CAND, bool PAD = false>
 __device__ __forceinline__ void bmu_tile(const BmuArgs& a, int64_t first, int64_t tile_index, unsigned int count,
                                          float4* lds4)
 {
@@ -402,6 +404,9 @@ __device__ __forceinline__ void bmu_tile(const BmuArgs& a, int64_t first, int64_
 #pragma unroll
         for (int nb = 0; nb < kNodesPerStage / 32; ++nb) {
             constexpr int NB = kNodesPerStage / 32;
+            if constexpr (PAD) {
+                if (st * kNodesPerStage + nb * 32 >= a.K) break;           // padding from here to the end of the stage
+            }
             const int nx = (nb + 1 < NB) ? nb + 1 : nb;                    // the last block re-reads itself (unused)
             const float* wnext = wbuf + (nx * 32 + j) * STRIDE + g;
             const float4* nhnext = reinterpret_cast<const float4*>(nbuf + nx * 32 + 4 * g);
@@ -546,17 +551,17 @@ __device__ __forceinline__ void bmu_tile(const BmuArgs& a, int64_t first, int64_
 }
 
 // two workgroups per compute unit (LDS-bound), i.e. two wavefronts per SIMD: the register budget is 256 VGPRs
-template <int STEPS, int MS>
+template <int STEPS, int MS, bool PAD>
 __global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 2))) bmu_kernel(const BmuArgs a)
 {
     extern __shared__ float4 lds4[];
     // The first full_tiles workgroups take MS blocks per wavefront; the rest of the grid, the last partial round
     // of the launch, takes tiles of half that size, which spread more evenly over the compute units.
     if ((int64_t)blockIdx.x < a.full_tiles) {
-        bmu_tile<STEPS, MS, false>(a, 0, blockIdx.x, 0u, lds4);
+        bmu_tile<STEPS, MS, false, PAD>(a, 0, blockIdx.x, 0u, lds4);
     } else if constexpr (MS > 1) {
         constexpr int64_t per_full = (int64_t)kWavesPerGroup * MS * 32;
-        bmu_tile<STEPS, MS / 2, false>(a, a.full_tiles * per_full, (int64_t)blockIdx.x - a.full_tiles, 0u, lds4);
+        bmu_tile<STEPS, MS / 2, false, PAD>(a, a.full_tiles * per_full, (int64_t)blockIdx.x - a.full_tiles, 0u, lds4);
     }
 }
 
@@ -1252,15 +1257,17 @@ static int launch_bmu(som_ctx* ctx, const BmuArgs& a)
 {
     constexpr int STRIDE = 2 * STEPS + 1;
     constexpr size_t lds_bytes = 2 * (size_t)stage_floats_for(STRIDE) * sizeof(float);
-    static bool attr_set = false;
-    auto kern = bmu_kernel<STEPS, MS>;
-    if (!attr_set) {
+    // maps that end in whole blocks of padding nodes take the variant that skips them
+    const bool pad = a.kpad - a.K >= 32;
+    static bool attr_set[2] = {false, false};
+    auto kern = pad ? bmu_kernel<STEPS, MS, true> : bmu_kernel<STEPS, MS, false>;
+    if (!attr_set[pad]) {
         if (int rc = check_hip(ctx,
                                hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes),
                                "raising the dynamic LDS limit"))
             return rc;
-        attr_set = true;
+        attr_set[pad] = true;
     }
     // Two workgroups fit a compute unit, so the grid runs in rounds of 2 * units tiles and a unit's time in the
     // last, partial round goes with the number of sample blocks it gets.  When halving the tiles of that round
