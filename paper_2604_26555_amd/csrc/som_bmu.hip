@@ -705,6 +705,15 @@ __device__ __forceinline__ void bmu_wide_tile(const BmuArgs& a, int64_t tile_ind
         __builtin_amdgcn_sched_barrier(0);
         const float* wbuf = lds + buf * STAGE_FLOATS;
         const float* nbuf = wbuf + kNodesPerStage * STRIDE;
+        // As in bmu_kernel the LDS reads of node block nb + 1 are written into the MFMA sequence of block nb (one
+        // read per MFMA) where the registers allow it (STEPS <= 28); only the first block of a chunk waits for LDS.
+        constexpr bool PIPE = STEPS <= 28;
+        float wa[PIPE ? STEPS : 1];
+        if constexpr (PIPE) {
+            const float* wrow = wbuf + j * STRIDE + g;
+#pragma unroll
+            for (int s = 0; s < STEPS; ++s) wa[s] = wrow[2 * s];
+        }
 #pragma unroll
         for (int nb = 0; nb < NBS; ++nb) {
             if (ch == 0) {
@@ -726,9 +735,27 @@ __device__ __forceinline__ void bmu_wide_tile(const BmuArgs& a, int64_t tile_ind
             floatx16 part;
 #pragma unroll
             for (int r = 0; r < 16; ++r) part[r] = 0.0f;
+            if constexpr (PIPE) {
+                const float* wnext = wrow + 32 * STRIDE;
+                float wn[STEPS];
 #pragma unroll
-            for (int s = 0; s < STEPS; ++s)
-                part = __builtin_amdgcn_mfma_f32_32x32x2f32(wrow[2 * s], x[s], part, 0, 0, 0);
+                for (int s = 0; s < STEPS; ++s) {
+                    part = __builtin_amdgcn_mfma_f32_32x32x2f32(wa[s], x[s], part, 0, 0, 0);
+                    if (nb + 1 < NBS) {
+                        wn[s] = wnext[2 * s];
+                        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);     // one MFMA
+                        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);     // one LDS read
+                    }
+                }
+                if (nb + 1 < NBS) {
+#pragma unroll
+                    for (int s = 0; s < STEPS; ++s) wa[s] = wn[s];
+                }
+            } else {
+#pragma unroll
+                for (int s = 0; s < STEPS; ++s)
+                    part = __builtin_amdgcn_mfma_f32_32x32x2f32(wrow[2 * s], x[s], part, 0, 0, 0);
+            }
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[nb][r] += part[r];
             if (CAND && ch == nch - 1) {
