@@ -209,6 +209,44 @@ def test_bmu_long_recheck_list_with_near_copies(som):
     assert (b2.cpu().numpy() == b1).all()
 
 
+def test_bmu_and_accumulate_on_seeded_random_shapes(som):
+    """Thirty shapes drawn with a fixed seed from awkward values (D around the kernels' chunk widths, K around the
+    stage and block sizes, ragged m, duplicated nodes for long re-decision lists, row lists, padded row strides):
+    BMUs, distances, quantisation-error sums, counts and sums against the oracle."""
+    rng = np.random.default_rng(20260)
+    dims = [1, 2, 3, 5, 8, 17, 24, 33, 40, 50, 55, 63, 64, 65, 66, 75, 99, 100, 101, 113, 128, 129, 150, 200, 257]
+    nodes = [1, 2, 31, 33, 64, 96, 97, 100, 128, 129, 160, 200, 256, 400, 576, 900, 1024]
+    rows = [1, 31, 257, 1000, 4097, 12000, 30000]
+    for it in range(30):
+        D, K, m = int(rng.choice(dims)), int(rng.choice(nodes)), int(rng.choice(rows))
+        dup, use_idx, pad = rng.random() < 0.3, rng.random() < 0.4, int(rng.integers(0, 4))
+        N = 2 * m if use_idx else m
+        X = GaussianMixture(1000 + it, D, 4).rows(0, N)
+        W = GaussianMixture(2000 + it, D, 4).rows(0, K) if K > N else X[rng.choice(N, K, replace=False)].copy()
+        if dup and K >= 4:
+            W[K // 2:] = W[:K - K // 2]
+        buf = np.full((N, D + pad), 1e9, dtype=np.float32)
+        buf[:, :D] = X
+        Xd = dev(buf)[:, :D]
+        idx = draw_subset(it, 0, N, m) if use_idx else None
+        idx_d = dev(idx.astype(np.int32)) if use_idx else None
+        d2 = torch.empty(m, dtype=torch.float32, device="cuda")
+        qe = torch.zeros(2, dtype=torch.float64, device="cuda")
+        print(f"shape {it}: m={m} K={K} D={D} duplicates={dup} row_list={use_idx} stride={D + pad}", flush=True)
+        b_gpu, _, _ = som.som_bmu(Xd, dev(W), idx=idx_d, d2=d2, qe=qe)
+        som.som_sync()
+        b_np = b_gpu.cpu().numpy()
+        _, best, _ = check_bmu(b_np, d2.cpu().numpy(), X, W, idx)
+        q = qe.cpu().numpy()
+        assert abs(q[0] - np.sqrt(best).sum()) <= REL * max(np.sqrt(best).sum(), 1e-30)
+        S = torch.empty((K, D), dtype=torch.float64, device="cuda")
+        n = torch.empty((K,), dtype=torch.int64, device="cuda")
+        som.som_accumulate(Xd, b_gpu, K, S, n, idx=idx_d, zero_first=True)
+        S_or, n_or = oracle.accumulate(X, idx, b_np, K)
+        assert np.array_equal(n.cpu().numpy(), n_or)
+        np.testing.assert_allclose(S.cpu().numpy(), S_or, rtol=1e-9, atol=1e-6 * max(1.0, float(np.abs(X).max())))
+
+
 # ------------------------------------------------------------------------------------------- stage 2
 @pytest.mark.parametrize("m,K,D", [(1, 1, 1), (1000, 100, 8), (50_000, 1024, 50), (30_001, 37, 64), (4096, 2000, 5),
                                    (20_000, 500, 63), (9000, 100, 200), (5000, 3000, 40), (40_000, 2048, 31),
