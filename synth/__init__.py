@@ -6,9 +6,9 @@ no neighbourhood function, no update) so that the oracle and the HIP path stay i
 """
 from .mixtures import GaussianMixture, Uniform01, uniform01_rows
 from .configs import WORKLOADS, Workload, make_workload
-from .draws import linear_sigma, draw_initial_rows, draw_subset, standardise, train_holdout_split
+from .draws import linear_sigma, exponential_sigma, draw_initial_rows, draw_subset, standardise, train_holdout_split
 
 __all__ = [
     "GaussianMixture", "Uniform01", "uniform01_rows", "WORKLOADS", "Workload", "make_workload",
-    "linear_sigma", "draw_initial_rows", "draw_subset", "standardise", "train_holdout_split",
+    "linear_sigma", "exponential_sigma", "draw_initial_rows", "draw_subset", "standardise", "train_holdout_split",
 ]

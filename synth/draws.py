@@ -13,6 +13,17 @@ def linear_sigma(a: float, b: float, n_epochs: int) -> np.ndarray:
     return a + (b - a) * np.arange(n_epochs, dtype=np.float64) / (n_epochs - 1)
 
 
+def exponential_sigma(a: float, b: float, n_epochs: int) -> np.ndarray:
+    """Radius per epoch, geometric from ``a`` (epoch 0) to ``b`` (last epoch): a * (b / a) ** (e / (E - 1)).
+    A second decay type next to the linear one (the paper tunes the decay type without listing the choices); the
+    radius is an argument of the library either way."""
+    if n_epochs < 1 or a <= 0 or b <= 0:
+        raise ValueError("need n_epochs >= 1 and positive radii")
+    if n_epochs == 1:
+        return np.array([float(a)])
+    return a * (b / a) ** (np.arange(n_epochs, dtype=np.float64) / (n_epochs - 1))
+
+
 def draw_initial_rows(seed: int, n: int, k: int) -> np.ndarray:
     """``k`` distinct row numbers in [0, n): the rows whose values become the initial node weights."""
     if k > n:

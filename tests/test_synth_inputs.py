@@ -1,7 +1,8 @@
 """The seeded input generators: reproducible, of the stated shape, and free of the method's arithmetic."""
 import numpy as np
 
-from synth import (draw_initial_rows, draw_subset, linear_sigma, make_workload, standardise, train_holdout_split)
+from synth import (draw_initial_rows, draw_subset, exponential_sigma, linear_sigma, make_workload, standardise,
+                   train_holdout_split)
 
 
 def test_draws_are_reproducible_and_well_formed():
@@ -12,6 +13,8 @@ def test_draws_are_reproducible_and_well_formed():
     assert len(np.unique(rows)) == 100 and rows.max() < 1000
     sig = linear_sigma(16.0, 1.0, 20)
     assert sig[0] == 16.0 and sig[-1] == 1.0 and np.allclose(np.diff(sig), -15.0 / 19)
+    geo = exponential_sigma(16.0, 1.0, 5)
+    assert np.allclose(geo, [16.0, 8.0, 4.0, 2.0, 1.0]) and exponential_sigma(3.0, 1.0, 1)[0] == 3.0
 
 
 def test_train_holdout_split_partitions_the_rows():
