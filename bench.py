@@ -113,9 +113,33 @@ def main() -> int:
         Xw.flush()
         del Xw
         X = np.load(mmap_path, mmap_mode="r")
+    elif not args.stream and wl.n * wl.d * 4 > (48 << 30):
+        # Too large to hold twice on the host: the matrix is generated in pieces (the generators are seeded per
+        # block of rows, so the data do not depend on how they are cut) and goes to the device piece by piece; a
+        # 10^9 x 50 matrix (200 GB, the upper end of the paper's sample axis) stays resident in the 288 GB of HBM.
+        from concurrent.futures import ThreadPoolExecutor
+        X = None
+        Xd = torch.empty((wl.n, wl.d), dtype=torch.float32, device="cuda")
+        piece = 1 << 24
+        gen = wl.data()
+        starts = list(range(0, wl.n, piece))
+        with ThreadPoolExecutor(max_workers=8) as pool:
+            pending = []
+            for i, lo in enumerate(starts):
+                pending.append((lo, pool.submit(gen.rows, lo, min(wl.n, lo + piece))))
+                if len(pending) >= 8 or i + 1 == len(starts):
+                    for plo, fut in pending:
+                        blk = fut.result()
+                        Xd[plo:plo + len(blk)].copy_(torch.from_numpy(blk))
+                    pending = []
+                    print(f"[bench] {min(wl.n, lo + piece)} rows on the device after {time.time() - t0:.0f}s", file=sys.stderr, flush=True)
     else:
         X = wl.data().rows(0, wl.n)
-    W0 = np.ascontiguousarray(X[draw_initial_rows(wl.seed, wl.n, wl.k)])
+    init_rows = draw_initial_rows(wl.seed, wl.n, wl.k)
+    if X is not None:
+        W0 = np.ascontiguousarray(X[init_rows])
+    else:
+        W0 = Xd[torch.from_numpy(init_rows).cuda()].cpu().numpy()
     sig = linear_sigma(wl.sigma[0], wl.sigma[1], max(args.steps, 1))
     print(f"[bench] generated {wl.name}: {wl.n} x {wl.d} in {time.time() - t0:.1f}s", file=sys.stderr, flush=True)
 
@@ -127,7 +151,8 @@ def main() -> int:
             if mmap_path:
                 del X
                 os.remove(mmap_path)
-    Xd = torch.from_numpy(X).cuda()
+    if X is not None:
+        Xd = torch.from_numpy(X).cuda()
     Wd = torch.from_numpy(W0).cuda()
     lattice_G = None
     if wl.topology in ("rect", "hex"):
@@ -233,11 +258,12 @@ def main() -> int:
         import oracle
         n_cpu = min(args.cpu_rows, wl.n)
         G_or = oracle.graph_distances(wl.topology, W=W0, lattice=wl.lattice)
+        Xc = X[:n_cpu] if X is not None else wl.data().rows(0, n_cpu)
         # whole epochs of the oracle, each from the previous one's weights, until about ten seconds have passed
         tc = time.perf_counter()
         Wc, n_ep = W0, 0
         while n_ep < len(sig) and (n_ep == 0 or time.perf_counter() - tc < 10.0):
-            Wc = oracle.epoch_grouped(X[:n_cpu], None, Wc, G_or, float(sig[n_ep]))["W"].astype(np.float32)
+            Wc = oracle.epoch_grouped(Xc, None, Wc, G_or, float(sig[n_ep]))["W"].astype(np.float32)
             n_ep += 1
         dt = time.perf_counter() - tc
         try:
