@@ -76,6 +76,8 @@ def main() -> int:
                          "(uniform data, Section 4.2.1), to be varied with --rows / --features / --grid")
     ap.add_argument("--features", type=int, default=None, help="override the feature count D (scale workload)")
     ap.add_argument("--grid", type=int, default=None, help="override the lattice side length, K = side^2 (scale workload)")
+    ap.add_argument("--topology", default=None, choices=["rect", "hex", "mst", "rng"],
+                    help="override the workload's map topology (mst and rng are rebuilt on the device every epoch)")
     ap.add_argument("--stream", default=None, choices=["pinned", "pageable", "mmap"],
                     help="keep X in host memory (or, mmap, in a memory-mapped file written to --mmap-dir first) and run "
                          "som_epoch_host (the chunked loading path) instead")
@@ -102,6 +104,8 @@ def main() -> int:
         over["d"] = args.features
     if args.grid:
         over.update(k=args.grid * args.grid, lattice=(args.grid, args.grid), sigma=(args.grid / 2.0, 1.0))
+    if args.topology:
+        over["topology"] = args.topology
     wl = make_workload(args.workload, n=args.rows, **over)
     t0 = time.time()
     mmap_path = None
