@@ -181,6 +181,14 @@ int som_set_reproducible(som_ctx* ctx, int on)
     return SOM_OK;
 }
 
+int som_set_search(som_ctx* ctx, int mode)
+{
+    if (!ctx) return SOM_EINVAL;
+    if (mode != SOM_SEARCH_AUTO && mode != SOM_SEARCH_FLOAT32) return fail(ctx, SOM_EINVAL, "unknown search mode %d", mode);
+    ctx->search = mode;
+    return SOM_OK;
+}
+
 int som_set_safeguard(som_ctx* ctx, int mode)
 {
     if (!ctx) return SOM_EINVAL;

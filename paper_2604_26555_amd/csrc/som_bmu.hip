@@ -593,6 +593,373 @@ __global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2
 }
 
 // ---------------------------------------------------------------------------------------------------------
+// The same search with the contraction on the bf16 matrix pipe (4 <= D <= 64).
+//
+// A float32 value v is cut into two bf16 parts, hi = bf16(v) and lo = bf16(v - hi) (both rounded to nearest, the
+// difference is exact in float32), so that |v - hi - lo| <= 2^-18 |v|.  A score then takes three bf16 MFMAs per 16
+// features (v_mfma_f32_32x32x16_bf16, products exact, float32 accumulation):
+//     x . w  ~  xh . wh + xl . wh + xh . wl,
+// the dropped parts together below 3 * 2^-18 |x| |w|.  The bf16 pipe runs these three in 96 cycles where the
+// float32 MFMAs of the same 16 features take 512, and unlike those it leaves half of the vector issue slots to the
+// fold, which runs beside it.  Nothing else changes: the error bound is wider (the split, and 16 additions per MFMA
+// counted at one float32 unit each since the pipe's internal rounding is not documented), samples inside it go on
+// the same list and are decided by the same direct differences, so the results are those of the float32 search.
+//
+// Layout.  Lane (j, g) of a wavefront holds, for k-block kb, the eight features of slot groups q = 4 kb + 2 g and
+// q + 1, group q being the window [min(4 q, D - 4), + 4) of the row: always whole and inside the row, so a group is
+// one 16-byte load; where the window is shifted back the stage rows hold zero weights in front of the group's own
+// features, and no feature is counted twice.  A stage row is [kb][g][hi x 8 | lo x 8] bf16 plus 16 bytes of padding
+// (row stride 64 KB + 16 bytes: the 16-byte reads of sixteen consecutive rows fall into distinct banks), followed
+// by the stage's 128 half squared norms in float32.
+// The fold keeps the position inside a block in the low four bits of the score (one and-or instead of a compare
+// and a select; 16 units of the last place are part of the bound), so padding nodes carry a large finite negative
+// norm here instead of -inf.
+// ---------------------------------------------------------------------------------------------------------
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+
+constexpr int split_row_bytes(int kb) { return kb * 64 + 16; }
+constexpr int split_stage_f4(int kb)
+{
+    return ((kNodesPerStage * split_row_bytes(kb) + kNodesPerStage * 4) / 16 + kThreads - 1) / kThreads * kThreads;
+}
+constexpr float kSplitPadNorm = -3.0e38f;
+constexpr int kSplitMS = 2;
+
+__device__ __forceinline__ void split8(const float (&v)[8], bf16x8& hi, bf16x8& lo)
+{
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        hi[i] = (__bf16)v[i];
+        lo[i] = (__bf16)(v[i] - (float)hi[i]);
+    }
+}
+
+// first feature of slot group q (four consecutive features)
+__device__ __forceinline__ int split_window(int q, int D) { return 4 * q < D - 4 ? 4 * q : D - 4; }
+
+// stage16 from W: one thread per (node, slot); the first kpad threads also copy the half squared norms from the
+// float32 stage (written by bmu_prep_kernel, which runs before this one on the same stream)
+__global__ void __launch_bounds__(256) bmu_prep_split_kernel(const float* __restrict__ W, int K, int D, int kpad, int kb_count,
+                                                             const float* __restrict__ centre,
+                                                             const float* __restrict__ stage, int stride, int stage_floats,
+                                                             char* __restrict__ stage16, int row_bytes, int stage16_bytes)
+{
+    const int e = blockIdx.x * 256 + threadIdx.x;
+    const int slots = kb_count * 16;
+    if (e < kpad * slots) {
+        const int k = e / slots, sl = e - k * slots;
+        const int kb = sl >> 4, g = (sl >> 3) & 1, t = sl & 7;
+        const int q = 4 * kb + 2 * g + (t >> 2);
+        const int f = split_window(q, D) + (t & 3);
+        const bool real = k < K && f >= 4 * q;                       // f < D always
+        const float v = real ? W[(size_t)k * D + f] - centre[f] : 0.0f;
+        const __bf16 hi = (__bf16)v;
+        const __bf16 lo = (__bf16)(v - (float)hi);
+        char* row = stage16 + (size_t)(k / kNodesPerStage) * stage16_bytes + (size_t)(k % kNodesPerStage) * row_bytes;
+        __bf16* cell = reinterpret_cast<__bf16*>(row + kb * 64 + g * 32) + t;
+        cell[0] = hi;
+        cell[8] = lo;
+    }
+    if (e < kpad) {
+        const int st = e / kNodesPerStage, r = e % kNodesPerStage;
+        float nh = stage[(size_t)st * stage_floats + (size_t)kNodesPerStage * stride + r];
+        if (!(nh > kSplitPadNorm)) nh = kSplitPadNorm;
+        reinterpret_cast<float*>(stage16 + (size_t)st * stage16_bytes + (size_t)kNodesPerStage * row_bytes)[r] = nh;
+    }
+}
+
+template <int KB, int MS, bool PAD>
+__device__ __forceinline__ void bmu_split_tile(const BmuArgs& a, int64_t first, int64_t tile_index, float4* lds4)
+{
+    constexpr int RS = split_row_bytes(KB);
+    constexpr int STAGE_F4 = split_stage_f4(KB);
+    constexpr int PRE = STAGE_F4 / kThreads;
+    const char* ldsb = reinterpret_cast<const char*>(lds4);
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    const int j = lane & 31;
+    const int g = lane >> 5;
+    const int64_t wave0 = first + (tile_index * kWavesPerGroup + wave) * (MS * 32);
+
+    // ---- this wavefront's samples: centred, cut into bf16 parts, kept in registers
+    bf16x8 xh[MS][KB], xl[MS][KB];
+    bool valid[MS];
+    const float* xrow[MS];
+    {
+        int start[KB][2];
+        float cen[KB][8];
+#pragma unroll
+        for (int kb = 0; kb < KB; ++kb)
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                start[kb][h] = split_window(4 * kb + 2 * g + h, a.D);
+                const float4 c4 = load4(a.centre + start[kb][h]);
+                cen[kb][4 * h + 0] = c4.x;
+                cen[kb][4 * h + 1] = c4.y;
+                cen[kb][4 * h + 2] = c4.z;
+                cen[kb][4 * h + 3] = c4.w;
+            }
+#pragma unroll
+        for (int mb = 0; mb < MS; ++mb) {
+            const int64_t i = wave0 + mb * 32 + j;
+            valid[mb] = i < a.m;
+            const int64_t ii = valid[mb] ? i : a.m - 1;
+            const int64_t row = a.idx ? (int64_t)a.idx[ii] : ii;
+            xrow[mb] = a.X + row * a.ldx;
+            float4 raw[KB][2];
+#pragma unroll
+            for (int kb = 0; kb < KB; ++kb)
+#pragma unroll
+                for (int h = 0; h < 2; ++h) raw[kb][h] = load4(xrow[mb] + start[kb][h]);
+#pragma unroll
+            for (int kb = 0; kb < KB; ++kb) {
+                float v[8];
+#pragma unroll
+                for (int h = 0; h < 2; ++h) {
+                    v[4 * h + 0] = raw[kb][h].x - cen[kb][4 * h + 0];
+                    v[4 * h + 1] = raw[kb][h].y - cen[kb][4 * h + 1];
+                    v[4 * h + 2] = raw[kb][h].z - cen[kb][4 * h + 2];
+                    v[4 * h + 3] = raw[kb][h].w - cen[kb][4 * h + 3];
+                }
+                split8(v, xh[mb][kb], xl[mb][kb]);
+            }
+        }
+    }
+
+    // running best / runner-up scores of this lane's half of the rows (position in the block in the low four bits
+    // of the score) and the block the best one came from
+    float best[MS], second[MS], before[MS];
+    int tsel[MS];
+#pragma unroll
+    for (int mb = 0; mb < MS; ++mb) {
+        best[mb] = -INFINITY;
+        second[mb] = -INFINITY;
+        before[mb] = -INFINITY;
+        tsel[mb] = 0;
+    }
+    // one fold step: score r of sample block mb of the node block `tile`; three vector instructions, plus two per
+    // block for the block number
+    auto fold_step = [&](const floatx16 (&acc)[MS], int step, int tile) {
+        const int mb = step >> 4, r = step & 15;
+        if (r == 0) before[mb] = best[mb];
+        const float v = __uint_as_float((__float_as_uint(acc[mb][r]) & 0xfffffff0u) | (unsigned)r);
+        second[mb] = __builtin_amdgcn_fmed3f(best[mb], second[mb], v);
+        best[mb] = vmax(best[mb], v);
+        if (r == 15) tsel[mb] = (best[mb] > before[mb]) ? tile : tsel[mb];
+    };
+
+    // ---- stream the nodes through LDS
+    const int nstages = a.kpad / kNodesPerStage;
+    const float4* src4 = reinterpret_cast<const float4*>(a.stage16);
+    {
+#pragma unroll
+        for (int p = 0; p < PRE; ++p) lds4[tid + p * kThreads] = src4[tid + p * kThreads];
+    }
+    __syncthreads();
+
+    // The scores of a node block are folded while the matrix pipe works on the next block: two sets of accumulators
+    // take turns, and the fold's instructions are written between the MFMAs (the pipe is busy 32 cycles per MFMA,
+    // of which the issue of the MFMA itself takes 16 on the vector port).  The very first block folds a set that
+    // holds the padding value, which any real score replaces.
+    floatx16 accA[MS], accB[MS];
+#pragma unroll
+    for (int mb = 0; mb < MS; ++mb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) accB[mb][r] = kSplitPadNorm;
+
+    constexpr int GROUPS = 3 * KB;             // groups of MS MFMAs per node block
+    constexpr int STEPS_ALL = 16 * MS;         // fold steps per node block
+    auto block = [&](floatx16 (&cur)[MS], const floatx16 (&prev)[MS], bf16x8 (&wh)[KB], bf16x8 (&wl)[KB], floatx16& c,
+                     const char* wnext, const float4* nhnext, bool more, int tile) {
+#pragma unroll
+        for (int kb = 0; kb < KB; ++kb) {
+#pragma unroll
+            for (int term = 0; term < 3; ++term) {
+                const int grp = 3 * kb + term;
+                const bf16x8 wa = (term == 2) ? wl[kb] : wh[kb];
+#pragma unroll
+                for (int mb = 0; mb < MS; ++mb) {
+                    cur[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wa, (term == 1) ? xl[mb][kb] : xh[mb][kb],
+                                                                      grp == 0 ? c : cur[mb], 0, 0, 0);
+                    // this MFMA's share of the previous block's fold, fenced so that it stays behind it
+                    const int m = grp * MS + mb;
+                    const int s0 = m * STEPS_ALL / (GROUPS * MS), s1 = (m + 1) * STEPS_ALL / (GROUPS * MS);
+#pragma unroll
+                    for (int sidx = s0; sidx < s1; ++sidx) fold_step(prev, sidx, tile - 1);
+                    if (mb + 1 < MS) __builtin_amdgcn_sched_barrier(0);
+                }
+                // LDS reads of the next block, into the registers this group has just finished with
+                if (more) {
+                    if (grp == 0) {
+#pragma unroll
+                        for (int q = 0; q < 4; ++q) {
+                            const float4 t = nhnext[2 * q];
+                            c[4 * q + 0] = t.x;
+                            c[4 * q + 1] = t.y;
+                            c[4 * q + 2] = t.z;
+                            c[4 * q + 3] = t.w;
+                        }
+                    }
+                    if (term == 2) {
+                        wh[kb] = *reinterpret_cast<const bf16x8*>(wnext + kb * 64);
+                        wl[kb] = *reinterpret_cast<const bf16x8*>(wnext + kb * 64 + 16);
+                    }
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+    };
+
+    for (int st = 0; st < nstages; ++st) {
+        const int buf = st & 1;
+        // next stage: global -> registers now, registers -> LDS after this stage's arithmetic (the last iteration
+        // reloads its own stage into the idle buffer, which keeps the loop branch-free)
+        float4 pre0, pre1, pre2, pre3, pre4, pre5, pre6, pre7, pre8;
+        static_assert(PRE <= 9, "stage copy holds at most nine float4 per thread");
+        {
+            const int nxt = (st + 1 < nstages) ? st + 1 : st;
+            const float4* s4 = src4 + (size_t)nxt * STAGE_F4 + tid;
+#define SOM_PRE_LOAD(i) if constexpr (PRE > i) pre##i = s4[i * kThreads];
+            SOM_PRE_LOAD(0) SOM_PRE_LOAD(1) SOM_PRE_LOAD(2) SOM_PRE_LOAD(3) SOM_PRE_LOAD(4)
+            SOM_PRE_LOAD(5) SOM_PRE_LOAD(6) SOM_PRE_LOAD(7) SOM_PRE_LOAD(8)
+#undef SOM_PRE_LOAD
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        const char* wbuf = ldsb + (size_t)buf * STAGE_F4 * 16;
+        const float* nbuf = reinterpret_cast<const float*>(wbuf + kNodesPerStage * RS);
+
+        bf16x8 wh[KB], wl[KB];
+        floatx16 c;
+        {
+            const char* wrow = wbuf + j * RS + g * 32;
+#pragma unroll
+            for (int kb = 0; kb < KB; ++kb) {
+                wh[kb] = *reinterpret_cast<const bf16x8*>(wrow + kb * 64);
+                wl[kb] = *reinterpret_cast<const bf16x8*>(wrow + kb * 64 + 16);
+            }
+            const float4* nh = reinterpret_cast<const float4*>(nbuf + 4 * g);
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const float4 t = nh[2 * q];
+                c[4 * q + 0] = t.x;
+                c[4 * q + 1] = t.y;
+                c[4 * q + 2] = t.z;
+                c[4 * q + 3] = t.w;
+            }
+        }
+        constexpr int NB = kNodesPerStage / 32;
+        static_assert(NB % 2 == 0, "the two accumulator sets take turns within a stage");
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb) {
+            const int nx = (nb + 1 < NB) ? nb + 1 : nb;
+            const char* wnext = wbuf + (nx * 32 + j) * RS + g * 32;
+            const float4* nhnext = reinterpret_cast<const float4*>(nbuf + nx * 32 + 4 * g);
+            const int tile = st * NB + nb;
+            if (nb & 1)
+                block(accB, accA, wh, wl, c, wnext, nhnext, nb + 1 < NB, tile);
+            else
+                block(accA, accB, wh, wl, c, wnext, nhnext, nb + 1 < NB, tile);
+        }
+
+        {
+            float4* d4 = lds4 + (buf ^ 1) * STAGE_F4 + tid;
+#define SOM_PRE_STORE(i) if constexpr (PRE > i) d4[i * kThreads] = pre##i;
+            SOM_PRE_STORE(0) SOM_PRE_STORE(1) SOM_PRE_STORE(2) SOM_PRE_STORE(3) SOM_PRE_STORE(4)
+            SOM_PRE_STORE(5) SOM_PRE_STORE(6) SOM_PRE_STORE(7) SOM_PRE_STORE(8)
+#undef SOM_PRE_STORE
+        }
+        __syncthreads();
+    }
+    // the last block's scores
+#pragma unroll
+    for (int sidx = 0; sidx < STEPS_ALL; ++sidx) fold_step(accB, sidx, nstages * (kNodesPerStage / 32) - 1);
+
+    // ---- join the two half-wavefronts, then lane (j, g) finishes block mp + g
+    const float wmax2 = __uint_as_float(a.scal[0]);
+    const float wmax = sqrtf(wmax2) * 1.000001f;
+    // Difference of two scores: the split leaves 3 * 2^-18 (1 + 2^-7) per score, every MFMA adds 16 products (one
+    // float32 unit, 2^-23, each: the pipe's internal rounding is not specified) to an accumulator, the position
+    // bits take 16 units of the last place, -|w|^2/2 and the two centrings as in the float32 kernel.
+    const float rel = 2.0f * (3.0f * 3.8146973e-06f * 1.0078125f + (float)(48 * KB + 1) * 1.1920929e-07f + 1.9073486e-06f) +
+                      12.0f * 5.9604645e-08f;
+    const int stage_floats = stage_floats_for(a.stride);
+    double qs = 0.0, qs2 = 0.0;
+#pragma unroll
+    for (int mp = 0; mp < MS; mp += 2) {
+        float r_best = 0.f, r_second = 0.f, r_xn = 0.f, r_part = 0.f;
+        int r_node = 0;
+        bool r_valid = false;
+#pragma unroll
+        for (int q = 0; q < 2; ++q) {
+            const int mb = mp + q;
+            if (mb >= MS) break;
+            const int rsel = (int)(__float_as_uint(best[mb]) & 15u);
+            int node = tsel[mb] * 32 + 8 * (rsel >> 2) + 4 * g + (rsel & 3);
+            const float ob = __shfl_xor(best[mb], 32);
+            const float os = __shfl_xor(second[mb], 32);
+            const int on = __shfl_xor(node, 32);
+            const float sec = fmaxf(fmaxf(second[mb], os), fminf(best[mb], ob));
+            const bool other = (ob > best[mb]) || (ob == best[mb] && on < node);
+            const float bst = other ? ob : best[mb];
+            node = other ? on : node;
+            node = node < a.K ? node : a.K - 1;
+            // squared norm of the centred sample and squared distance to the winner by direct differences on the
+            // float32 values, half the features per lane (the row is read again: it is still in the cache; the
+            // winner's centred weights come from the float32 stage rows)
+            float xn = 0.f, part = 0.f;
+            const float* wr = a.stage + (size_t)(node / kNodesPerStage) * stage_floats +
+                              (size_t)(node % kNodesPerStage) * a.stride;
+#pragma unroll 4
+            for (int f = g; f < a.D; f += 2) {
+                const float xm = xrow[mb][f] - a.centre[f];
+                const float df = xm - wr[f];
+                xn = fmaf(xm, xm, xn);
+                part = fmaf(df, df, part);
+            }
+            xn += __shfl_xor(xn, 32);
+            part += __shfl_xor(part, 32);
+            if (q == g) {
+                r_best = bst;
+                r_second = sec;
+                r_node = node;
+                r_xn = xn;
+                r_part = part;
+                r_valid = valid[mb];
+            }
+        }
+        const int64_t i = wave0 + (mp + g) * 32 + j;
+        const float xl2 = sqrtf(r_xn);
+        const float bound = (xl2 * wmax + 0.5f * wmax2) * rel;
+        const float tiny = (xl2 + wmax) * (xl2 + wmax) * 3.8146973e-06f;
+        const bool close = r_valid && a.K > 1 && (!((r_best - r_second) > bound) || r_part < tiny);
+        if (r_valid) {
+            a.bmu[i] = r_node;
+            if (a.d2) a.d2[i] = r_part;
+            if (!close) {
+                qs += sqrt((double)r_part);
+                qs2 += (double)r_part;
+            }
+        }
+        list_push(&a.scal[a.slot], a.recheck, a.cutv, close, i, r_best - bound);
+    }
+    if (a.qe) group_qe_add(a.qe_part, qs, qs2);
+}
+
+template <int KB, int MS, bool PAD>
+__global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 2))) bmu_split_kernel(const BmuArgs a)
+{
+    extern __shared__ float4 lds4[];
+    if ((int64_t)blockIdx.x < a.full_tiles) {
+        bmu_split_tile<KB, MS, PAD>(a, 0, blockIdx.x, lds4);
+    } else if constexpr (MS > 1) {
+        constexpr int64_t per_full = (int64_t)kWavesPerGroup * MS * 32;
+        bmu_split_tile<KB, MS / 2, PAD>(a, a.full_tiles * per_full, (int64_t)blockIdx.x - a.full_tiles, lds4);
+    }
+}
+
+// ---------------------------------------------------------------------------------------------------------
 // the same search for D > 64: features go through in chunks of 50, 56 or 64.  A wavefront owns one block of 32
 // samples; the accumulators of a stage's four node blocks stay live across the chunks, the samples' features of
 // the current chunk are re-read from memory once per stage (one workgroup touches 128 rows).
@@ -1164,7 +1531,11 @@ int bmu_prepare(som_ctx* ctx, const float* W, int32_t K, int32_t D, BmuPrep* out
     // the centre vector is zero-padded to whole chunks (and to the 64 entries the resident kernel reads)
     const size_t centre_floats = (size_t)(nch > 1 ? nch * 2 * steps : 64);
     const size_t centre_bytes = ((centre_floats > (size_t)D ? centre_floats : (size_t)D) * sizeof(float) + 255) / 256 * 256;
-    const size_t need = stage_bytes + wt_bytes + centre_bytes + 256;
+    // rows for the bf16 matrix pipe where the split search applies
+    const int kb = (nch == 1 && D >= 4 && ctx->search != SOM_SEARCH_FLOAT32) ? (D + 15) / 16 : 0;
+    const size_t stage16_one = kb ? (size_t)(kb == 1 ? split_stage_f4(1) : kb == 2 ? split_stage_f4(2) : kb == 3 ? split_stage_f4(3) : split_stage_f4(4)) * 16 : 0;
+    const size_t stage16_bytes = (size_t)(kpad / kNodesPerStage) * stage16_one;
+    const size_t need = stage_bytes + wt_bytes + centre_bytes + stage16_bytes + 256;
     if (need > ctx->prep_bytes) {
         if (ctx->prep_blob) {
             if (int rc = check_hip(ctx, hipStreamSynchronize(ctx->stream), "sync before workspace growth")) return rc;
@@ -1183,6 +1554,8 @@ int bmu_prepare(som_ctx* ctx, const float* W, int32_t K, int32_t D, BmuPrep* out
     out->stage = (float*)(base + 256);
     out->wt = (float*)(base + 256 + stage_bytes);
     out->centre = (float*)(base + 256 + stage_bytes + wt_bytes);
+    out->stage16 = kb ? (void*)(base + 256 + stage_bytes + wt_bytes + centre_bytes) : nullptr;
+    out->kb = kb;
     out->kpad = kpad;
     out->steps = steps;
     out->stride = stride;
@@ -1196,7 +1569,14 @@ int bmu_prepare(som_ctx* ctx, const float* W, int32_t K, int32_t D, BmuPrep* out
     if (elems < (long long)kpad * D) elems = (long long)kpad * D;
     hipLaunchKernelGGL(bmu_prep_kernel, dim3((unsigned)((elems + 255) / 256)), dim3(256), 0, ctx->stream, W, K, D, kpad,
                        stride, nch, stage_floats_for(stride), out->centre, out->stage, out->wt, out->scal, qe, small);
-    return check_hip(ctx, hipGetLastError(), "bmu_prep launch");
+    if (int rc = check_hip(ctx, hipGetLastError(), "bmu_prep launch")) return rc;
+    if (kb) {
+        hipLaunchKernelGGL(bmu_prep_split_kernel, dim3((unsigned)(((long long)kpad * kb * 16 + 255) / 256)), dim3(256), 0,
+                           ctx->stream, W, K, D, kpad, kb, out->centre, out->stage, stride, stage_floats_for(stride),
+                           (char*)out->stage16, split_row_bytes(kb), (int)stage16_one);
+        return check_hip(ctx, hipGetLastError(), "bmu_prep_split launch");
+    }
+    return SOM_OK;
 }
 
 template <int STEPS>
@@ -1321,6 +1701,54 @@ static int launch_bmu(som_ctx* ctx, const BmuArgs& a)
     return check_hip(ctx, hipGetLastError(), "bmu kernel launch");
 }
 
+template <int KB, int MS>
+static int launch_bmu_split(som_ctx* ctx, const BmuArgs& a)
+{
+    constexpr size_t lds_bytes = 2 * (size_t)split_stage_f4(KB) * 16;
+    const bool pad = a.kpad - a.K >= 32;
+    static bool attr_set[2] = {false, false};
+    auto kern = pad ? bmu_split_kernel<KB, MS, true> : bmu_split_kernel<KB, MS, false>;
+    if (!attr_set[pad]) {
+        if (int rc = check_hip(ctx,
+                               hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes),
+                               "raising the dynamic LDS limit"))
+            return rc;
+        attr_set[pad] = true;
+    }
+    if (ctx->units == 0) {
+        int units = 0;
+        if (hipDeviceGetAttribute(&units, hipDeviceAttributeMultiprocessorCount, ctx->device) != hipSuccess || units < 1)
+            units = 256;
+        ctx->units = units;
+    }
+    // full tiles, and half tiles for the last partial round where that lowers the largest share (as launch_bmu)
+    const int64_t per_group = (int64_t)kWavesPerGroup * MS * 32;
+    const int64_t tiles = (a.m + per_group - 1) / per_group;
+    const int64_t units = ctx->units, rem = tiles % (2 * units);
+    BmuArgs b = a;
+    b.full_tiles = tiles;
+    int64_t groups = tiles;
+    if (MS > 1 && tiles >= 2 * units && rem > 0 && (2 * rem + units - 1) / units < 2 * ((rem + units - 1) / units)) {
+        b.full_tiles = tiles - rem;
+        const int64_t left = a.m - b.full_tiles * per_group, per_half = per_group / 2;
+        groups = b.full_tiles + (left + per_half - 1) / per_half;
+    }
+    hipLaunchKernelGGL(kern, dim3((unsigned)groups), dim3(kThreads), lds_bytes, ctx->stream, b);
+    return check_hip(ctx, hipGetLastError(), "bmu split kernel launch");
+}
+
+static int dispatch_bmu_split(som_ctx* ctx, int kb, const BmuArgs& a)
+{
+    switch (kb) {
+    case 1: return launch_bmu_split<1, kSplitMS>(ctx, a);
+    case 2: return launch_bmu_split<2, kSplitMS>(ctx, a);
+    case 3: return launch_bmu_split<3, kSplitMS>(ctx, a);
+    case 4: return launch_bmu_split<4, kSplitMS>(ctx, a);
+    }
+    return fail(ctx, SOM_EINVAL, "no split BMU kernel for %d blocks", kb);
+}
+
 static int dispatch_bmu(som_ctx* ctx, int steps, const BmuArgs& a)
 {
     switch (steps) {
@@ -1359,6 +1787,8 @@ int bmu_run(som_ctx* ctx, BmuPrep& prep, BmuArgs a)
     }
     a.kpad = prep.kpad;
     a.stage = prep.stage;
+    a.stride = prep.stride;
+    a.stage16 = prep.stage16;
     a.wt = prep.wt;
     a.centre = prep.centre;
     a.scal = prep.scal;
@@ -1393,7 +1823,7 @@ int bmu_run(som_ctx* ctx, BmuPrep& prep, BmuArgs a)
     int rc = prep.nch > 1 ? (prep.steps == 25   ? launch_bmu_wide<25>(ctx, a)
                              : prep.steps == 28 ? launch_bmu_wide<28>(ctx, a)
                                                 : launch_bmu_wide<32>(ctx, a))
-                          : dispatch_bmu(ctx, prep.steps, a);
+                          : (prep.stage16 ? dispatch_bmu_split(ctx, prep.kb, a) : dispatch_bmu(ctx, prep.steps, a));
     if (stop) (void)hipEventRecord(stop, ctx->stream);
     if (rc) return rc;
     if (cand_possible) {

@@ -16,6 +16,8 @@ constexpr int kMaxStepsResident = 32; // BMU kernel keeps a sample's features in
 
 struct BmuPrep {
     float* stage = nullptr;        // [Kpad / 128][nch] blobs: 128 padded weight rows of a chunk, then -|w|^2 / 2
+    void* stage16 = nullptr;       // bf16 hi/lo stage rows of the split search (4 <= D <= 64), else null
+    int kb = 0;                    // 16-feature blocks of a stage16 row
     float* wt = nullptr;           // [D][Kpad] transposed weights (as given, not centred)
     float* centre = nullptr;       // [D] column means of W; stage rows and sample registers hold values minus this
     // [0] = bits of max_k |w_k - centre|^2, [1], [2] = recheck-list length (alternating calls), [3] = total,
@@ -34,6 +36,8 @@ struct BmuArgs {
     int32_t D, K, kpad;
     const float* W;          // caller's dense K x D weights (exact distances)
     const float* stage;      // BmuPrep::stage
+    int32_t stride;          // BmuPrep::stride (floats per row of the float32 stage)
+    const void* stage16;     // BmuPrep::stage16 (null: float32 search)
     const float* wt;         // BmuPrep::wt
     const float* centre;     // BmuPrep::centre
     unsigned int* scal;      // BmuPrep::scal
@@ -81,6 +85,7 @@ struct som_ctx {
     size_t upd_bytes = 0;
     int safeguard = 0;             // SOM_SAFEGUARD_*
     int reproducible = 0;          // prefer the fixed-order accumulation kernel
+    int search = 0;                // SOM_SEARCH_*
     double* qe_part = nullptr;     // [kQeSlots][2], zero between calls
     void* topo_blob = nullptr;     // node distances, adjacency matrix and lists of the topology rebuild
     size_t topo_bytes = 0;

@@ -21,13 +21,15 @@ SOM_OK, SOM_EINVAL, SOM_ENOMEM, SOM_EHIP, SOM_EIO, SOM_ESTATE = 0, -1, -2, -3, -
 SOM_KERNEL_GAUSSIAN = 0
 SOM_SAFEGUARD_THRESHOLD = 0
 SOM_SAFEGUARD_SHIFT = 1
+SOM_SEARCH_AUTO = 0
+SOM_SEARCH_FLOAT32 = 1
 SOM_TOPOLOGY_MST = 1
 SOM_TOPOLOGY_RNG = 2
 
 EXPORTS = [
     "som_create", "som_destroy", "som_strerror", "som_last_error", "som_sync", "som_bmu", "som_accumulate",
     "som_neighborhood_update", "som_epoch", "som_epoch_host", "som_profile", "som_profile_read",
-    "som_set_update_rule", "som_topology", "som_set_safeguard", "som_set_reproducible",
+    "som_set_update_rule", "som_topology", "som_set_safeguard", "som_set_reproducible", "som_set_search",
 ]
 
 
@@ -81,6 +83,8 @@ def load_library(path: str = LIB_PATH) -> C.CDLL:
     lib.som_neighborhood_update.restype = C.c_int
     lib.som_set_reproducible.argtypes = [vp, C.c_int]
     lib.som_set_reproducible.restype = C.c_int
+    lib.som_set_search.argtypes = [vp, C.c_int]
+    lib.som_set_search.restype = C.c_int
     lib.som_set_safeguard.argtypes = [vp, C.c_int]
     lib.som_set_safeguard.restype = C.c_int
     lib.som_topology.argtypes = [vp, vp, i32, i32, C.c_int, vp]
@@ -254,6 +258,11 @@ class Som:
 
     def som_set_reproducible(self, on=True):
         self._check(self.lib.som_set_reproducible(self._h, 1 if on else 0), "som_set_reproducible")
+
+    def som_set_search(self, mode):
+        if isinstance(mode, str):
+            mode = {"auto": SOM_SEARCH_AUTO, "float32": SOM_SEARCH_FLOAT32}[mode]
+        self._check(self.lib.som_set_search(self._h, int(mode)), "som_set_search")
 
     def som_set_safeguard(self, mode):
         if isinstance(mode, str):
