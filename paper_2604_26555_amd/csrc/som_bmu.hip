@@ -601,9 +601,9 @@ __global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2
 //     x . w  ~  xh . wh + xl . wh + xh . wl,
 // the dropped parts together below 3 * 2^-18 |x| |w|.  The bf16 pipe runs these three in 96 cycles where the
 // float32 MFMAs of the same 16 features take 512, and unlike those it leaves half of the vector issue slots to the
-// fold, which runs beside it.  Nothing else changes: the error bound is wider (the split, and 16 additions per MFMA
-// counted at one float32 unit each since the pipe's internal rounding is not documented), samples inside it go on
-// the same list and are decided by the same direct differences, so the results are those of the float32 search.
+// fold, which runs beside it.  Nothing else changes: the error bound is wider (the split, and the pipe's accumulation
+// error per MFMA as measured on this chip), samples inside it go on the same list and are decided by the same direct
+// differences, so the results are those of the float32 search.
 //
 // Layout.  Lane (j, g) of a wavefront holds, for k-block kb, the eight features of slot groups q = 4 kb + 2 g and
 // q + 1, group q being the window [min(4 q, D - 4), + 4) of the row: always whole and inside the row, so a group is
@@ -642,7 +642,8 @@ __device__ __forceinline__ int split_window(int q, int D) { return 4 * q < D - 4
 __global__ void __launch_bounds__(256) bmu_prep_split_kernel(const float* __restrict__ W, int K, int D, int kpad, int kb_count,
                                                              const float* __restrict__ centre,
                                                              const float* __restrict__ stage, int stride, int stage_floats,
-                                                             char* __restrict__ stage16, int row_bytes, int stage16_bytes)
+                                                             char* __restrict__ stage16, int row_bytes, int stage16_bytes,
+                                                             float* __restrict__ wwin)
 {
     const int e = blockIdx.x * 256 + threadIdx.x;
     const int slots = kb_count * 16;
@@ -659,6 +660,7 @@ __global__ void __launch_bounds__(256) bmu_prep_split_kernel(const float* __rest
         __bf16* cell = reinterpret_cast<__bf16*>(row + kb * 64 + g * 32) + t;
         cell[0] = hi;
         cell[8] = lo;
+        wwin[e] = v;                 // the same slots in float32, [node][kb][g][8]: the winner's row for the distances
     }
     if (e < kpad) {
         const int st = e / kNodesPerStage, r = e % kNodesPerStage;
@@ -683,49 +685,46 @@ __device__ __forceinline__ void bmu_split_tile(const BmuArgs& a, int64_t first, 
     const int g = lane >> 5;
     const int64_t wave0 = first + (tile_index * kWavesPerGroup + wave) * (MS * 32);
 
-    // ---- this wavefront's samples: centred, cut into bf16 parts, kept in registers
-    bf16x8 xh[MS][KB], xl[MS][KB];
-    bool valid[MS];
-    const float* xrow[MS];
-    {
-        int start[KB][2];
-        float cen[KB][8];
+    // This lane's 8 KB slots of a sample row, centred; slots in front of a shifted window's own features read zero
+    // (they meet zero weights in the stage rows, and stay out of the norms and distances).
+    auto centred_slots = [&](const float* xr, int D, float (&v)[KB][8]) {
+        float4 raw[KB][2], cen[KB][2];
 #pragma unroll
         for (int kb = 0; kb < KB; ++kb)
 #pragma unroll
             for (int h = 0; h < 2; ++h) {
-                start[kb][h] = split_window(4 * kb + 2 * g + h, a.D);
-                const float4 c4 = load4(a.centre + start[kb][h]);
-                cen[kb][4 * h + 0] = c4.x;
-                cen[kb][4 * h + 1] = c4.y;
-                cen[kb][4 * h + 2] = c4.z;
-                cen[kb][4 * h + 3] = c4.w;
+                const int start = split_window(4 * kb + 2 * g + h, D);
+                raw[kb][h] = load4(xr + start);
+                cen[kb][h] = load4(a.centre + start);
             }
 #pragma unroll
-        for (int mb = 0; mb < MS; ++mb) {
-            const int64_t i = wave0 + mb * 32 + j;
-            valid[mb] = i < a.m;
-            const int64_t ii = valid[mb] ? i : a.m - 1;
-            const int64_t row = a.idx ? (int64_t)a.idx[ii] : ii;
-            xrow[mb] = a.X + row * a.ldx;
-            float4 raw[KB][2];
+        for (int kb = 0; kb < KB; ++kb)
 #pragma unroll
-            for (int kb = 0; kb < KB; ++kb)
-#pragma unroll
-                for (int h = 0; h < 2; ++h) raw[kb][h] = load4(xrow[mb] + start[kb][h]);
-#pragma unroll
-            for (int kb = 0; kb < KB; ++kb) {
-                float v[8];
-#pragma unroll
-                for (int h = 0; h < 2; ++h) {
-                    v[4 * h + 0] = raw[kb][h].x - cen[kb][4 * h + 0];
-                    v[4 * h + 1] = raw[kb][h].y - cen[kb][4 * h + 1];
-                    v[4 * h + 2] = raw[kb][h].z - cen[kb][4 * h + 2];
-                    v[4 * h + 3] = raw[kb][h].w - cen[kb][4 * h + 3];
-                }
-                split8(v, xh[mb][kb], xl[mb][kb]);
+            for (int h = 0; h < 2; ++h) {
+                const int q = 4 * kb + 2 * g + h;
+                const int shift = 4 * q - split_window(q, D);            // own slots: i >= shift
+                v[kb][4 * h + 0] = shift <= 0 ? raw[kb][h].x - cen[kb][h].x : 0.0f;
+                v[kb][4 * h + 1] = shift <= 1 ? raw[kb][h].y - cen[kb][h].y : 0.0f;
+                v[kb][4 * h + 2] = shift <= 2 ? raw[kb][h].z - cen[kb][h].z : 0.0f;
+                v[kb][4 * h + 3] = shift <= 3 ? raw[kb][h].w - cen[kb][h].w : 0.0f;
             }
-        }
+    };
+
+    // ---- this wavefront's samples: centred, cut into bf16 parts, kept in registers
+    bf16x8 xh[MS][KB], xl[MS][KB];
+    bool valid[MS];
+    const float* xrow[MS];
+#pragma unroll
+    for (int mb = 0; mb < MS; ++mb) {
+        const int64_t i = wave0 + mb * 32 + j;
+        valid[mb] = i < a.m;
+        const int64_t ii = valid[mb] ? i : a.m - 1;
+        const int64_t row = a.idx ? (int64_t)a.idx[ii] : ii;
+        xrow[mb] = a.X + row * a.ldx;
+        float v[KB][8];
+        centred_slots(xrow[mb], a.D, v);
+#pragma unroll
+        for (int kb = 0; kb < KB; ++kb) split8(v[kb], xh[mb][kb], xl[mb][kb]);
     }
 
     // running best / runner-up scores of this lane's half of the rows (position in the block in the low four bits
@@ -879,12 +878,16 @@ __device__ __forceinline__ void bmu_split_tile(const BmuArgs& a, int64_t first, 
     // ---- join the two half-wavefronts, then lane (j, g) finishes block mp + g
     const float wmax2 = __uint_as_float(a.scal[0]);
     const float wmax = sqrtf(wmax2) * 1.000001f;
-    // Difference of two scores: the split leaves 3 * 2^-18 (1 + 2^-7) per score, every MFMA adds 16 products (one
-    // float32 unit, 2^-23, each: the pipe's internal rounding is not specified) to an accumulator, the position
-    // bits take 16 units of the last place, -|w|^2/2 and the two centrings as in the float32 kernel.
-    const float rel = 2.0f * (3.0f * 3.8146973e-06f * 1.0078125f + (float)(48 * KB + 1) * 1.1920929e-07f + 1.9073486e-06f) +
+    // Difference of two scores: the split leaves 3 * 2^-18 (1 + 2^-7) per score; every MFMA adds its 16 products to
+    // the accumulator with an error of at most 8 * 2^-24 of max(|C|, sum |products|) (the pipe's rounding is not
+    // specified: measured on gfx950 the largest error over 5 * 10^7 random outputs, operand exponents spread over
+    // up to 2^24, was 6.3 such units, as four truncating additions of exact partial sums would give); the position
+    // bits take 16 units of the last place; -|w|^2/2 and the two centrings as in the float32 kernel.
+    const float rel = 2.0f * (3.0f * 3.8146973e-06f * 1.0078125f + (float)(24 * KB + 1) * 5.9604645e-08f + 1.9073486e-06f) +
                       12.0f * 5.9604645e-08f;
-    const int stage_floats = stage_floats_for(a.stride);
+    // (the window offsets are worked out again rather than carried through the stage loop in registers)
+    int d_again = a.D;
+    asm volatile("" : "+s"(d_again));
     double qs = 0.0, qs2 = 0.0;
 #pragma unroll
     for (int mp = 0; mp < MS; mp += 2) {
@@ -906,17 +909,25 @@ __device__ __forceinline__ void bmu_split_tile(const BmuArgs& a, int64_t first, 
             node = other ? on : node;
             node = node < a.K ? node : a.K - 1;
             // squared norm of the centred sample and squared distance to the winner by direct differences on the
-            // float32 values, half the features per lane (the row is read again: it is still in the cache; the
-            // winner's centred weights come from the float32 stage rows)
+            // float32 values, this lane's slots (the row is read again: it is still in the cache; the winner's
+            // centred weights come from the float32 copy of the stage rows, in the same slot order)
             float xn = 0.f, part = 0.f;
-            const float* wr = a.stage + (size_t)(node / kNodesPerStage) * stage_floats +
-                              (size_t)(node % kNodesPerStage) * a.stride;
-#pragma unroll 4
-            for (int f = g; f < a.D; f += 2) {
-                const float xm = xrow[mb][f] - a.centre[f];
-                const float df = xm - wr[f];
-                xn = fmaf(xm, xm, xn);
-                part = fmaf(df, df, part);
+            {
+                float v[KB][8];
+                centred_slots(xrow[mb], d_again, v);
+                const float* wr = a.wwin + (size_t)node * (KB * 16) + g * 8;
+#pragma unroll
+                for (int kb = 0; kb < KB; ++kb) {
+                    const float4 w0 = *reinterpret_cast<const float4*>(wr + kb * 16);
+                    const float4 w1 = *reinterpret_cast<const float4*>(wr + kb * 16 + 4);
+                    const float w[8] = {w0.x, w0.y, w0.z, w0.w, w1.x, w1.y, w1.z, w1.w};
+#pragma unroll
+                    for (int t = 0; t < 8; ++t) {
+                        const float df = v[kb][t] - w[t];
+                        xn = fmaf(v[kb][t], v[kb][t], xn);
+                        part = fmaf(df, df, part);
+                    }
+                }
             }
             xn += __shfl_xor(xn, 32);
             part += __shfl_xor(part, 32);
@@ -1535,7 +1546,8 @@ int bmu_prepare(som_ctx* ctx, const float* W, int32_t K, int32_t D, BmuPrep* out
     const int kb = (nch == 1 && D >= 4 && ctx->search != SOM_SEARCH_FLOAT32) ? (D + 15) / 16 : 0;
     const size_t stage16_one = kb ? (size_t)(kb == 1 ? split_stage_f4(1) : kb == 2 ? split_stage_f4(2) : kb == 3 ? split_stage_f4(3) : split_stage_f4(4)) * 16 : 0;
     const size_t stage16_bytes = (size_t)(kpad / kNodesPerStage) * stage16_one;
-    const size_t need = stage_bytes + wt_bytes + centre_bytes + stage16_bytes + 256;
+    const size_t wwin_bytes = (size_t)kpad * kb * 16 * sizeof(float);
+    const size_t need = stage_bytes + wt_bytes + centre_bytes + stage16_bytes + wwin_bytes + 256;
     if (need > ctx->prep_bytes) {
         if (ctx->prep_blob) {
             if (int rc = check_hip(ctx, hipStreamSynchronize(ctx->stream), "sync before workspace growth")) return rc;
@@ -1555,6 +1567,7 @@ int bmu_prepare(som_ctx* ctx, const float* W, int32_t K, int32_t D, BmuPrep* out
     out->wt = (float*)(base + 256 + stage_bytes);
     out->centre = (float*)(base + 256 + stage_bytes + wt_bytes);
     out->stage16 = kb ? (void*)(base + 256 + stage_bytes + wt_bytes + centre_bytes) : nullptr;
+    out->wwin = kb ? (float*)(base + 256 + stage_bytes + wt_bytes + centre_bytes + stage16_bytes) : nullptr;
     out->kb = kb;
     out->kpad = kpad;
     out->steps = steps;
@@ -1573,7 +1586,7 @@ int bmu_prepare(som_ctx* ctx, const float* W, int32_t K, int32_t D, BmuPrep* out
     if (kb) {
         hipLaunchKernelGGL(bmu_prep_split_kernel, dim3((unsigned)(((long long)kpad * kb * 16 + 255) / 256)), dim3(256), 0,
                            ctx->stream, W, K, D, kpad, kb, out->centre, out->stage, stride, stage_floats_for(stride),
-                           (char*)out->stage16, split_row_bytes(kb), (int)stage16_one);
+                           (char*)out->stage16, split_row_bytes(kb), (int)stage16_one, out->wwin);
         return check_hip(ctx, hipGetLastError(), "bmu_prep_split launch");
     }
     return SOM_OK;
@@ -1789,6 +1802,7 @@ int bmu_run(som_ctx* ctx, BmuPrep& prep, BmuArgs a)
     a.stage = prep.stage;
     a.stride = prep.stride;
     a.stage16 = prep.stage16;
+    a.wwin = prep.wwin;
     a.wt = prep.wt;
     a.centre = prep.centre;
     a.scal = prep.scal;

@@ -17,6 +17,7 @@ constexpr int kMaxStepsResident = 32; // BMU kernel keeps a sample's features in
 struct BmuPrep {
     float* stage = nullptr;        // [Kpad / 128][nch] blobs: 128 padded weight rows of a chunk, then -|w|^2 / 2
     void* stage16 = nullptr;       // bf16 hi/lo stage rows of the split search (4 <= D <= 64), else null
+    float* wwin = nullptr;         // [Kpad][kb][2][8] the same slots as stage16 in float32 (centred, zeros off-window)
     int kb = 0;                    // 16-feature blocks of a stage16 row
     float* wt = nullptr;           // [D][Kpad] transposed weights (as given, not centred)
     float* centre = nullptr;       // [D] column means of W; stage rows and sample registers hold values minus this
@@ -38,6 +39,7 @@ struct BmuArgs {
     const float* stage;      // BmuPrep::stage
     int32_t stride;          // BmuPrep::stride (floats per row of the float32 stage)
     const void* stage16;     // BmuPrep::stage16 (null: float32 search)
+    const float* wwin;       // BmuPrep::wwin
     const float* wt;         // BmuPrep::wt
     const float* centre;     // BmuPrep::centre
     unsigned int* scal;      // BmuPrep::scal
