@@ -17,6 +17,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 PEAK_FP32_MFMA_TFLOPS = 157.3      # MI355X dense float32 matrix peak
+PEAK_BF16_MFMA_TFLOPS = 2500.0     # MI355X dense bf16 matrix peak
 METRIC = "samples/sec per batch-SOM epoch (BMU+update), 1024 nodes x 50 features"
 
 
@@ -76,6 +77,9 @@ def main() -> int:
                          "(uniform data, Section 4.2.1), to be varied with --rows / --features / --grid")
     ap.add_argument("--features", type=int, default=None, help="override the feature count D (scale workload)")
     ap.add_argument("--grid", type=int, default=None, help="override the lattice side length, K = side^2 (scale workload)")
+    ap.add_argument("--search", default="auto", choices=["auto", "float32"],
+                    help="BMU score arithmetic: auto = bf16 parts on the bf16 matrix pipe for 4 <= D <= 64, float32 MFMA "
+                         "otherwise; float32 = float32 MFMA for every shape (same results either way)")
     ap.add_argument("--topology", default=None, choices=["rect", "hex", "mst", "rng"],
                     help="override the workload's map topology (mst and rng are rebuilt on the device every epoch)")
     ap.add_argument("--stream", default=None, choices=["pinned", "pageable", "mmap"],
@@ -85,6 +89,8 @@ def main() -> int:
     ap.add_argument("--chunk-rows", type=int, default=4_000_000)
     ap.add_argument("--rows", type=int, default=None, help="override the workload's sample count")
     ap.add_argument("--cpu-rows", type=int, default=1_000_000, help="rows of the workload the CPU oracle is timed on")
+    ap.add_argument("--no-float32-reference", action="store_true",
+                    help="skip the extra epochs that time the float32 search for the roofline's reference entry")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain device-to-device copy of X (known size) for scaling hardware counters")
@@ -148,6 +154,7 @@ def main() -> int:
     print(f"[bench] generated {wl.name}: {wl.n} x {wl.d} in {time.time() - t0:.1f}s", file=sys.stderr, flush=True)
 
     som = pkg.Som(0)
+    som.som_set_search(args.search)
     if args.stream:
         try:
             return stream_bench(args, wl, X, W0, sig, som, pkg, torch)
@@ -201,6 +208,51 @@ def main() -> int:
     avg_kernel_ms = float(np.mean(kernel_ms)) if kernel_ms else float("nan")
     flops = 2.0 * m * wl.k * wl.d                          # algorithmic: 2 K D per presented sample
     achieved = flops / (avg_kernel_ms * 1e-3) / 1e12 if kernel_ms else float("nan")
+    # which matrix pipe the dominant kernel runs on decides the peak it is priced against
+    split = args.search == "auto" and 4 <= wl.d <= 64
+    if split:
+        kb, kpad = (wl.d + 15) // 16, (wl.k + 127) // 128 * 128
+        issued = 3 * 2.0 * m * kpad * 16 * kb              # three bf16 MFMA products per float32 product, padded shape
+        roof = {"bound": "mfma", "kernel": "bmu_split_kernel (scores from bf16 parts on the bf16 matrix pipe + arg-max)",
+                "achieved": achieved, "peak": PEAK_BF16_MFMA_TFLOPS, "unit": "TFLOP/s",
+                "frac": achieved / PEAK_BF16_MFMA_TFLOPS if kernel_ms else None,
+                "issued": issued / (avg_kernel_ms * 1e-3) / 1e12 if kernel_ms else None,
+                "issued_frac": issued / (avg_kernel_ms * 1e-3) / 1e12 / PEAK_BF16_MFMA_TFLOPS if kernel_ms else None,
+                "note": "achieved = algorithmic 2 m K D float32 flops per launch; issued = the bf16 MFMA flops the kernel "
+                        "executes for them (3 products of bf16 parts per float32 product, K and D padded to 128 and 16)"}
+    else:
+        roof = {"bound": "mfma", "kernel": "bmu_kernel (fused float32 score contraction + arg-max)",
+                "achieved": achieved, "peak": PEAK_FP32_MFMA_TFLOPS, "unit": "TFLOP/s",
+                "frac": achieved / PEAK_FP32_MFMA_TFLOPS if kernel_ms else None}
+    roof.update({"avg_kernel_ms": avg_kernel_ms, "launches": len(kernel_ms)})
+    # the float32 search on the same workload, for reference (same results; its own kernel, its own peak)
+    if split and not args.no_float32_reference and flops * (args.warmup + args.steps) < 2e15:
+        som.som_set_search("float32")
+        W_keep = Wd.clone()
+        Wd.copy_(torch.from_numpy(W0))
+        for e in range(min(args.warmup, 10)):
+            epoch(e)
+        som.som_sync()
+        Wd.copy_(torch.from_numpy(W0))
+        n_ref = min(args.steps, 10)
+        som.som_profile(True)
+        torch.cuda.synchronize()
+        ts = time.perf_counter()
+        for e in range(n_ref):
+            epoch(e)
+        som.som_sync()
+        torch.cuda.synchronize()
+        ref_s = time.perf_counter() - ts
+        ref_ms = som.som_profile_read()
+        som.som_profile(False)
+        som.som_set_search(args.search)
+        Wd.copy_(W_keep)
+        if ref_ms:
+            k_ms = float(np.mean(ref_ms))
+            roof["float32_search"] = {"kernel": "bmu_kernel (float32 MFMA)", "ms_per_step": 1e3 * ref_s / max(n_ref, 1),
+                                      "avg_kernel_ms": k_ms, "achieved": flops / (k_ms * 1e-3) / 1e12,
+                                      "peak": PEAK_FP32_MFMA_TFLOPS, "frac": flops / (k_ms * 1e-3) / 1e12 / PEAK_FP32_MFMA_TFLOPS,
+                                      "steps": n_ref}
     traffic = None
     # measured off-line with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (scaled by a plain copy); see profiles/
     pmc = os.path.join(ROOT, "profiles", f"epoch_{wl.name}_hbm_traffic.md")
@@ -208,6 +260,7 @@ def main() -> int:
         for line in open(pmc):
             if line.startswith("traffic_bytes_per_launch_bmu_kernel:"):
                 traffic = float(line.split(":")[1])
+    roof["traffic"] = traffic
 
     if args.copy_calibration:
         Xcopy = torch.empty_like(Xd)
@@ -250,11 +303,9 @@ def main() -> int:
                                f"{'' if m_sel == wl.n else f' ({m_sel} drawn per epoch)'}, "
                                f"sigma {wl.sigma[0]}->{wl.sigma[1]} over {args.steps} epochs",
                    "samples": wl.n, "presented_per_epoch": m_sel, "features": wl.d, "nodes": wl.k, "topology": wl.topology,
-                   "final_qe": final_qe, "topology_rebuilt_on_device_each_epoch": lattice_G is None},
-        "roofline": {"bound": "mfma", "kernel": "bmu_kernel (fused score contraction + arg-max)",
-                     "achieved": achieved, "peak": PEAK_FP32_MFMA_TFLOPS, "unit": "TFLOP/s",
-                     "frac": achieved / PEAK_FP32_MFMA_TFLOPS if kernel_ms else None,
-                     "avg_kernel_ms": avg_kernel_ms, "launches": len(kernel_ms), "traffic": traffic},
+                   "final_qe": final_qe, "topology_rebuilt_on_device_each_epoch": lattice_G is None,
+                   "search": "bf16 parts on the bf16 matrix pipe, re-decision in float32" if split else "float32 MFMA"},
+        "roofline": roof,
         "stages": stages,
     }
 

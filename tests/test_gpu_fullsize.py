@@ -42,15 +42,18 @@ def trained(som, wl, Xd, W0, epochs):
     return Wd, G, sig
 
 
+@pytest.mark.parametrize("search", ["auto", "float32"])
 @pytest.mark.parametrize("epochs", [0, 3, 12])
-def test_full_size_bmu_sampled_against_brute_force(som, cfg1, epochs):
+def test_full_size_bmu_sampled_against_brute_force(som, cfg1, epochs, search):
     wl, X, W0 = cfg1
     Xd = torch.from_numpy(X).cuda()
     Wd, _, _ = trained(som, wl, Xd, W0, epochs)
+    som.som_set_search(search)       # bf16 parts on the matrix pipe (the benchmark's configuration), or float32 MFMA
     W = Wd.cpu().numpy()
     d2 = torch.empty(wl.n, dtype=torch.float32, device="cuda")
     qe = torch.zeros(2, dtype=torch.float64, device="cuda")
     b_gpu, _, _ = som.som_bmu(Xd, Wd, d2=d2, qe=qe)
+    som.som_set_search("auto")
     b_gpu, d2 = b_gpu.cpu().numpy(), d2.cpu().numpy()
     rows = np.sort(np.random.default_rng(77 + epochs).choice(wl.n, 4000, replace=False))
     rows = np.unique(np.concatenate([rows, [0, 255, 256, wl.n - 65, wl.n - 1]]))      # tile edges and the ragged tail

@@ -28,6 +28,14 @@ def som():
     s.close()
 
 
+@pytest.fixture(params=["auto", "float32"])
+def search(request, som):
+    """Both score pipes: bf16 parts on the matrix pipe where the shape allows it (auto), float32 MFMA everywhere."""
+    som.som_set_search(request.param)
+    yield request.param
+    som.som_set_search("auto")
+
+
 def dev(a, dtype=None):
     t = torch.from_numpy(np.ascontiguousarray(a))
     if dtype is not None:
@@ -69,8 +77,10 @@ def check_bmu(b_gpu, d2_gpu, X, W, idx=None):
     (4099, 1024, 50), (600, 300, 64), (2048, 257, 33), (1500, 300, 24), (2500, 260, 40), (1800, 140, 55),
     (1000, 200, 65), (3000, 1024, 130), (500, 64, 300), (300, 130, 1000),      # feature-chunked kernel (D > 64):
     (700, 150, 128), (900, 260, 111), (333, 129, 500),                         # chunks of 50, 56 and 64 features
+    (900, 70, 4), (900, 70, 5), (1200, 130, 7), (800, 200, 15), (800, 200, 16), (700, 300, 31), (700, 129, 32),
+    (600, 260, 47), (600, 260, 48), (500, 100, 49), (500, 100, 63),            # 16-feature blocks, shifted windows
 ])
-def test_bmu_matches_oracle(som, m, K, D):
+def test_bmu_matches_oracle(som, search, m, K, D):
     X, W = problem(100 + m + K + D, m, K, D)
     d2 = torch.empty(m, dtype=torch.float32, device="cuda")
     qe = torch.full((2,), -1.0, dtype=torch.float64, device="cuda")
@@ -82,14 +92,14 @@ def test_bmu_matches_oracle(som, m, K, D):
     assert abs(q[1] - best.sum()) <= REL * max(best.sum(), 1e-30)
 
 
-def test_bmu_exact_ties_and_duplicates(som):
+def test_bmu_exact_ties_and_duplicates(som, search):
     W = np.array([[1.0, 0.0], [-1.0, 0.0], [0.0, 1.0], [0.0, -1.0], [0.0, 1.0]], dtype=np.float32)
     X = np.array([[0.0, 0.0], [0.0, 0.5], [0.25, 0.25], [-3.0, 0.0]], dtype=np.float32)
     b_gpu, _, _ = som.som_bmu(dev(X), dev(W))
     assert b_gpu.cpu().tolist() == oracle.bmu(X, W)[0].tolist() == [0, 2, 0, 1]
 
 
-def test_bmu_index_list_and_leading_dimension(som):
+def test_bmu_index_list_and_leading_dimension(som, search):
     X, W = problem(7, 5000, 64, 10)
     pad = np.full((5000, 13), 1e9, dtype=np.float32)       # garbage beyond D must never be read as features
     pad[:, :10] = X
@@ -100,7 +110,7 @@ def test_bmu_index_list_and_leading_dimension(som):
     check_bmu(b_gpu.cpu().numpy(), d2.cpu().numpy(), X, W, idx)
 
 
-def test_bmu_large_norm_small_gap(som):
+def test_bmu_large_norm_small_gap(som, search):
     # clusters far from the origin: |x|^2 ~ 1e5 while neighbouring nodes differ by ~1e-2 in squared distance,
     # so the float32 score form alone could not decide; the direct re-decision has to
     rng = np.random.default_rng(3)
@@ -126,7 +136,7 @@ def test_bmu_wide_rows_that_are_not_16_byte_aligned(som):
 
 
 @pytest.mark.parametrize("D", [20, 200])
-def test_bmu_far_from_the_origin(som, D):
+def test_bmu_far_from_the_origin(som, search, D):
     """Data and weights sit at 1000 +- 0.01 per coordinate: |x|^2 is 10^6 D while neighbouring nodes differ by about
     1e-4 in squared distance.  Only the centred score form (and the exact re-decision behind it) can tell them apart."""
     rng = np.random.default_rng(D)
@@ -136,7 +146,7 @@ def test_bmu_far_from_the_origin(som, D):
     check_bmu(b_gpu.cpu().numpy(), None, X, W)
 
 
-def test_bmu_sample_on_a_node(som):
+def test_bmu_sample_on_a_node(som, search):
     """Samples that coincide with a node (distance exactly zero) or sit next to one far from the origin."""
     rng = np.random.default_rng(9)
     W = (50.0 + rng.normal(size=(64, 30))).astype(np.float32)
@@ -147,8 +157,41 @@ def test_bmu_sample_on_a_node(som):
     assert (d2.cpu().numpy()[:10] == 0).all() and (b_gpu.cpu().numpy()[:10] == np.arange(10)).all()
 
 
+@pytest.mark.parametrize("scale", [1e-12, 1e-3, 1e6, 1e12])
+def test_bmu_at_extreme_scales(som, search, scale):
+    """The same problem multiplied by a power of ten: scores scale with its square, the decisions must not change."""
+    X, W = problem(4242, 5000, 300, 50)
+    X, W = (X * np.float32(scale)).astype(np.float32), (W * np.float32(scale)).astype(np.float32)
+    d2 = torch.empty(len(X), dtype=torch.float32, device="cuda")
+    b_gpu, _, _ = som.som_bmu(dev(X), dev(W), d2=d2)
+    b, best, second = oracle.bmu(X, W)
+    mask = oracle.near_tie_mask(best, second)
+    assert ((b_gpu.cpu().numpy() == b) | mask).all()
+    same = b_gpu.cpu().numpy() == b
+    np.testing.assert_allclose(d2.cpu().numpy()[same], best[same], rtol=REL, atol=0.0)
+
+
+def test_bmu_both_searches_agree(som):
+    """The bf16-parts search and the float32 search return the same units and distances wherever the oracle's best two
+    distances are not a near tie (the re-decision by direct differences is shared, only the band differs)."""
+    X, W = problem(99, 200_000, 1024, 50)
+    Xd, Wd = dev(X), dev(W)
+    out = {}
+    for mode in ("auto", "float32"):
+        som.som_set_search(mode)
+        d2 = torch.empty(len(X), dtype=torch.float32, device="cuda")
+        b, _, _ = som.som_bmu(Xd, Wd, d2=d2)
+        out[mode] = (b.cpu().numpy(), d2.cpu().numpy())
+    som.som_set_search("auto")
+    _, best, second = oracle.bmu(X, W)
+    mask = oracle.near_tie_mask(best, second)
+    agree = out["auto"][0] == out["float32"][0]
+    assert (agree | mask).all()
+    np.testing.assert_allclose(out["auto"][1][agree], out["float32"][1][agree], rtol=1e-5, atol=0.0)
+
+
 @pytest.mark.parametrize("D,copies", [(50, 2), (50, 12), (20, 3), (100, 2), (130, 10)])
-def test_bmu_long_recheck_list(som, D, copies):
+def test_bmu_long_recheck_list(som, search, D, copies):
     """Every node exists `copies` times, so every sample's best scores tie and the whole call lands on the
     re-decision list, which is then long enough for the candidate pass: with few copies the candidates' direct
     differences decide, with many the per-sample slots overflow and the all-nodes pass takes over.  Either way the
@@ -189,7 +232,7 @@ def test_bmu_long_recheck_list_on_a_map_too_large_for_16_bit_node_ids(som):
     assert (b_gpu < distinct).all()
 
 
-def test_bmu_long_recheck_list_with_near_copies(som):
+def test_bmu_long_recheck_list_with_near_copies(som, search):
     """Near-copies (relative offsets around 1e-7) instead of exact ones: the scores cannot separate them, the
     direct differences of the candidate pass must, and a second call on the same context (alternating list
     counters) must give the same answer."""
@@ -209,7 +252,7 @@ def test_bmu_long_recheck_list_with_near_copies(som):
     assert (b2.cpu().numpy() == b1).all()
 
 
-def test_bmu_and_accumulate_on_seeded_random_shapes(som):
+def test_bmu_and_accumulate_on_seeded_random_shapes(som, search):
     """Thirty shapes drawn with a fixed seed from awkward values (D around the kernels' chunk widths, K around the
     stage and block sizes, ragged m, duplicated nodes for long re-decision lists, row lists, padded row strides):
     BMUs, distances, quantisation-error sums, counts and sums against the oracle."""
