@@ -811,10 +811,40 @@ __device__ __forceinline__ void bmu_split_tile(const BmuArgs& a, int64_t first, 
         }
     };
 
+    // The first node block's operands; every later block's are read while the block before it is on the matrix pipe.
+    bf16x8 wh[KB], wl[KB];
+    floatx16 c;
+    {
+        const char* wrow = ldsb + j * RS + g * 32;
+#pragma unroll
+        for (int kb = 0; kb < KB; ++kb) {
+            wh[kb] = *reinterpret_cast<const bf16x8*>(wrow + kb * 64);
+            wl[kb] = *reinterpret_cast<const bf16x8*>(wrow + kb * 64 + 16);
+        }
+        const float4* nh = reinterpret_cast<const float4*>(ldsb + kNodesPerStage * RS) + g;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const float4 t = nh[2 * q];
+            c[4 * q + 0] = t.x;
+            c[4 * q + 1] = t.y;
+            c[4 * q + 2] = t.z;
+            c[4 * q + 3] = t.w;
+        }
+    }
+    // One stage: the next stage travels global -> registers at the start and registers -> the idle LDS buffer after
+    // the second block; the stage's only barrier stands in front of its last block, whose spare LDS slots then read
+    // the first block of the next stage.  (With the barrier at the end of the stage a wavefront stood still for an
+    // LDS write, the barrier and an LDS read once per stage; alone on its SIMD, while the unit's other workgroup
+    // loads or stores its samples, that cost a fifth of its time.)  Why this is safe: a buffer's last reads, the
+    // operands of its stage's last block, are issued during the block before that barrier and waited for before
+    // it, so once a wavefront is past the barrier of stage s the buffer of stage s is free for stage s + 2, which
+    // nobody writes before the middle of stage s + 1; and the barrier of stage s stands between every wavefront's
+    // writes of stage s + 1 and the first reads of it.
+    constexpr int NB = kNodesPerStage / 32;
+    static_assert(NB == 4, "two blocks, the LDS writes, one block, the barrier, one block");
     for (int st = 0; st < nstages; ++st) {
         const int buf = st & 1;
-        // next stage: global -> registers now, registers -> LDS after this stage's arithmetic (the last iteration
-        // reloads its own stage into the idle buffer, which keeps the loop branch-free)
+        // (the last iteration reloads its own stage into the idle buffer, which keeps the loop branch-free)
         float4 pre0, pre1, pre2, pre3, pre4, pre5, pre6, pre7, pre8;
         static_assert(PRE <= 9, "stage copy holds at most nine float4 per thread");
         {
@@ -827,41 +857,14 @@ __device__ __forceinline__ void bmu_split_tile(const BmuArgs& a, int64_t first, 
         }
         __builtin_amdgcn_sched_barrier(0);
         const char* wbuf = ldsb + (size_t)buf * STAGE_F4 * 16;
-        const float* nbuf = reinterpret_cast<const float*>(wbuf + kNodesPerStage * RS);
-
-        bf16x8 wh[KB], wl[KB];
-        floatx16 c;
-        {
-            const char* wrow = wbuf + j * RS + g * 32;
-#pragma unroll
-            for (int kb = 0; kb < KB; ++kb) {
-                wh[kb] = *reinterpret_cast<const bf16x8*>(wrow + kb * 64);
-                wl[kb] = *reinterpret_cast<const bf16x8*>(wrow + kb * 64 + 16);
-            }
-            const float4* nh = reinterpret_cast<const float4*>(nbuf + 4 * g);
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const float4 t = nh[2 * q];
-                c[4 * q + 0] = t.x;
-                c[4 * q + 1] = t.y;
-                c[4 * q + 2] = t.z;
-                c[4 * q + 3] = t.w;
-            }
-        }
-        constexpr int NB = kNodesPerStage / 32;
-        static_assert(NB % 2 == 0, "the two accumulator sets take turns within a stage");
-#pragma unroll
-        for (int nb = 0; nb < NB; ++nb) {
-            const int nx = (nb + 1 < NB) ? nb + 1 : nb;
-            const char* wnext = wbuf + (nx * 32 + j) * RS + g * 32;
-            const float4* nhnext = reinterpret_cast<const float4*>(nbuf + nx * 32 + 4 * g);
-            const int tile = st * NB + nb;
-            if (nb & 1)
-                block(accB, accA, wh, wl, c, wnext, nhnext, nb + 1 < NB, tile);
-            else
-                block(accA, accB, wh, wl, c, wnext, nhnext, nb + 1 < NB, tile);
-        }
-
+        const char* obuf = ldsb + (size_t)(buf ^ 1) * STAGE_F4 * 16;
+        auto rows_of = [&](const char* base, int nb) { return base + (nb * 32 + j) * RS + g * 32; };
+        auto norms_of = [&](const char* base, int nb) {
+            return reinterpret_cast<const float4*>(base + kNodesPerStage * RS + nb * 32 * 4) + g;
+        };
+        const int tile = st * NB;
+        block(accA, accB, wh, wl, c, rows_of(wbuf, 1), norms_of(wbuf, 1), true, tile);
+        block(accB, accA, wh, wl, c, rows_of(wbuf, 2), norms_of(wbuf, 2), true, tile + 1);
         {
             float4* d4 = lds4 + (buf ^ 1) * STAGE_F4 + tid;
 #define SOM_PRE_STORE(i) if constexpr (PRE > i) d4[i * kThreads] = pre##i;
@@ -869,7 +872,10 @@ __device__ __forceinline__ void bmu_split_tile(const BmuArgs& a, int64_t first, 
             SOM_PRE_STORE(5) SOM_PRE_STORE(6) SOM_PRE_STORE(7) SOM_PRE_STORE(8)
 #undef SOM_PRE_STORE
         }
+        __builtin_amdgcn_sched_barrier(0);
+        block(accA, accB, wh, wl, c, rows_of(wbuf, 3), norms_of(wbuf, 3), true, tile + 2);
         __syncthreads();
+        block(accB, accA, wh, wl, c, rows_of(obuf, 0), norms_of(obuf, 0), true, tile + 3);
     }
     // the last block's scores
 #pragma unroll
