@@ -623,6 +623,7 @@ constexpr int split_stage_f4(int kb)
     return ((kNodesPerStage * split_row_bytes(kb) + kNodesPerStage * 4) / 16 + kThreads - 1) / kThreads * kThreads;
 }
 constexpr float kSplitPadNorm = -3.0e38f;
+constexpr int kSplitMinNodes = 384;            // SOM_SEARCH_AUTO: smaller maps use the float32 search
 constexpr int kSplitMS = 2;
 
 __device__ __forceinline__ void split8(const float (&v)[8], bf16x8& hi, bf16x8& lo)
@@ -670,8 +671,11 @@ __global__ void __launch_bounds__(256) bmu_prep_split_kernel(const float* __rest
     }
 }
 
-template <int KB, int MS, bool PAD>
-__device__ __forceinline__ void bmu_split_tile(const BmuArgs& a, int64_t first, int64_t tile_index, float4* lds4)
+// CAND = true: the candidate pass over the first `count` entries of the re-decision list (as in bmu_tile): the same
+// scores are formed again, bit for bit, and every node whose score reaches the entry's cut is noted.
+template <int KB, int MS, bool CAND>
+__device__ __forceinline__ void bmu_split_tile(const BmuArgs& a, int64_t first, int64_t tile_index, unsigned int count,
+                                               float4* lds4)
 {
     constexpr int RS = split_row_bytes(KB);
     constexpr int STAGE_F4 = split_stage_f4(KB);
@@ -714,11 +718,18 @@ __device__ __forceinline__ void bmu_split_tile(const BmuArgs& a, int64_t first, 
     bf16x8 xh[MS][KB], xl[MS][KB];
     bool valid[MS];
     const float* xrow[MS];
+    float cut[MS];          // CAND
+    CandSet noted[MS];      // CAND
 #pragma unroll
     for (int mb = 0; mb < MS; ++mb) {
         const int64_t i = wave0 + mb * 32 + j;
-        valid[mb] = i < a.m;
-        const int64_t ii = valid[mb] ? i : a.m - 1;
+        const int64_t total = CAND ? (int64_t)count : a.m;
+        valid[mb] = i < total;
+        int64_t ii = valid[mb] ? i : total - 1;
+        if constexpr (CAND) {
+            cut[mb] = valid[mb] ? a.cutv[ii] : NAN;     // no score compares >= NaN
+            ii = (int64_t)a.recheck[ii];
+        }
         const int64_t row = a.idx ? (int64_t)a.idx[ii] : ii;
         xrow[mb] = a.X + row * a.ldx;
         float v[KB][8];
@@ -742,6 +753,11 @@ __device__ __forceinline__ void bmu_split_tile(const BmuArgs& a, int64_t first, 
     // block for the block number
     auto fold_step = [&](const floatx16 (&acc)[MS], int step, int tile) {
         const int mb = step >> 4, r = step & 15;
+        if constexpr (CAND) {
+            // (the set that the very first block "folds" holds the padding value, which reaches no cut)
+            if (acc[mb][r] >= cut[mb]) noted[mb].note(tile * 32 + 4 * g, 8 * (r >> 2) + (r & 3));
+            return;
+        }
         if (r == 0) before[mb] = best[mb];
         const float v = __uint_as_float((__float_as_uint(acc[mb][r]) & 0xfffffff0u) | (unsigned)r);
         second[mb] = __builtin_amdgcn_fmed3f(best[mb], second[mb], v);
@@ -881,6 +897,12 @@ __device__ __forceinline__ void bmu_split_tile(const BmuArgs& a, int64_t first, 
 #pragma unroll
     for (int sidx = 0; sidx < STEPS_ALL; ++sidx) fold_step(accB, sidx, nstages * (kNodesPerStage / 32) - 1);
 
+    if constexpr (CAND) {
+#pragma unroll
+        for (int mb = 0; mb < MS; ++mb)
+            if (valid[mb]) a.cand[(size_t)(wave0 + mb * 32 + j) * 2 + g] = noted[mb].packed();
+        return;
+    }
     // ---- join the two half-wavefronts, then lane (j, g) finishes block mp + g
     const float wmax2 = __uint_as_float(a.scal[0]);
     const float wmax = sqrtf(wmax2) * 1.000001f;
@@ -969,11 +991,29 @@ __global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2
 {
     extern __shared__ float4 lds4[];
     if ((int64_t)blockIdx.x < a.full_tiles) {
-        bmu_split_tile<KB, MS, PAD>(a, 0, blockIdx.x, lds4);
+        bmu_split_tile<KB, MS, false>(a, 0, blockIdx.x, 0u, lds4);
     } else if constexpr (MS > 1) {
         constexpr int64_t per_full = (int64_t)kWavesPerGroup * MS * 32;
-        bmu_split_tile<KB, MS / 2, PAD>(a, a.full_tiles * per_full, (int64_t)blockIdx.x - a.full_tiles, lds4);
+        bmu_split_tile<KB, MS / 2, false>(a, a.full_tiles * per_full, (int64_t)blockIdx.x - a.full_tiles, 0u, lds4);
     }
+}
+
+// candidate pass of the split search: a fixed grid walks the tiles of the list (as bmu_cand_kernel)
+template <int KB, int MS>
+__global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 2))) bmu_split_cand_kernel(const BmuArgs a)
+{
+    extern __shared__ float4 lds4[];
+    const unsigned int count = a.scal[a.slot];
+    if (!cand_pass_serves(a, count)) return;
+    constexpr int64_t per_tile = (int64_t)kWavesPerGroup * MS * 32;
+    if constexpr (MS > 1) {
+        if (count <= kCandHalfTiles) {
+            for (int64_t t = blockIdx.x; t * (per_tile / 2) < (int64_t)count; t += gridDim.x)
+                bmu_split_tile<KB, MS / 2, true>(a, 0, t, count, lds4);
+            return;
+        }
+    }
+    for (int64_t t = blockIdx.x; t * per_tile < (int64_t)count; t += gridDim.x) bmu_split_tile<KB, MS, true>(a, 0, t, count, lds4);
 }
 
 // ---------------------------------------------------------------------------------------------------------
@@ -1549,7 +1589,9 @@ int bmu_prepare(som_ctx* ctx, const float* W, int32_t K, int32_t D, BmuPrep* out
     const size_t centre_floats = (size_t)(nch > 1 ? nch * 2 * steps : 64);
     const size_t centre_bytes = ((centre_floats > (size_t)D ? centre_floats : (size_t)D) * sizeof(float) + 255) / 256 * 256;
     // rows for the bf16 matrix pipe where the split search applies
-    const int kb = (nch == 1 && D >= 4 && ctx->search != SOM_SEARCH_FLOAT32) ? (D + 15) / 16 : 0;
+    // (small maps stay with the float32 search: a tile is mostly prologue and epilogue there, and the split search's
+    // are the longer ones; measured at 10^7 x 50: 256 nodes 3.5 ms against 4.5, 576 nodes 5.7 against 5.1)
+    const int kb = (nch == 1 && D >= 4 && K > kSplitMinNodes && ctx->search != SOM_SEARCH_FLOAT32) ? (D + 15) / 16 : 0;
     const size_t stage16_one = kb ? (size_t)(kb == 1 ? split_stage_f4(1) : kb == 2 ? split_stage_f4(2) : kb == 3 ? split_stage_f4(3) : split_stage_f4(4)) * 16 : 0;
     const size_t stage16_bytes = (size_t)(kpad / kNodesPerStage) * stage16_one;
     const size_t wwin_bytes = (size_t)kpad * kb * 16 * sizeof(float);
@@ -1757,6 +1799,36 @@ static int launch_bmu_split(som_ctx* ctx, const BmuArgs& a)
     return check_hip(ctx, hipGetLastError(), "bmu split kernel launch");
 }
 
+template <int KB, int MS>
+static int launch_bmu_split_cand(som_ctx* ctx, const BmuArgs& a)
+{
+    constexpr size_t lds_bytes = 2 * (size_t)split_stage_f4(KB) * 16;
+    static bool attr_set = false;
+    auto kern = bmu_split_cand_kernel<KB, MS>;
+    if (!attr_set) {
+        if (int rc = check_hip(ctx,
+                               hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes),
+                               "raising the dynamic LDS limit"))
+            return rc;
+        attr_set = true;
+    }
+    hipLaunchKernelGGL(kern, dim3(cand_grid(a, (int64_t)kWavesPerGroup * MS * 32)), dim3(kThreads), lds_bytes, ctx->stream,
+                       a);
+    return check_hip(ctx, hipGetLastError(), "bmu split candidate kernel launch");
+}
+
+static int dispatch_bmu_split_cand(som_ctx* ctx, int kb, const BmuArgs& a)
+{
+    switch (kb) {
+    case 1: return launch_bmu_split_cand<1, kSplitMS>(ctx, a);
+    case 2: return launch_bmu_split_cand<2, kSplitMS>(ctx, a);
+    case 3: return launch_bmu_split_cand<3, kSplitMS>(ctx, a);
+    case 4: return launch_bmu_split_cand<4, kSplitMS>(ctx, a);
+    }
+    return fail(ctx, SOM_EINVAL, "no split candidate kernel for %d blocks", kb);
+}
+
 static int dispatch_bmu_split(som_ctx* ctx, int kb, const BmuArgs& a)
 {
     switch (kb) {
@@ -1850,7 +1922,7 @@ int bmu_run(som_ctx* ctx, BmuPrep& prep, BmuArgs a)
         rc = prep.nch > 1 ? (prep.steps == 25   ? launch_bmu_wide_cand<25>(ctx, a)
                              : prep.steps == 28 ? launch_bmu_wide_cand<28>(ctx, a)
                                                 : launch_bmu_wide_cand<32>(ctx, a))
-                          : dispatch_bmu_cand(ctx, prep.steps, a);
+                          : (prep.stage16 ? dispatch_bmu_split_cand(ctx, prep.kb, a) : dispatch_bmu_cand(ctx, prep.steps, a));
         if (rc) return rc;
         hipLaunchKernelGGL(bmu_cand_exact_kernel, dim3(2048), dim3(256), 0, ctx->stream, a);
         if ((rc = check_hip(ctx, hipGetLastError(), "bmu candidate-distance launch"))) return rc;
