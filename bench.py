@@ -209,7 +209,7 @@ def main() -> int:
     flops = 2.0 * m * wl.k * wl.d                          # algorithmic: 2 K D per presented sample
     achieved = flops / (avg_kernel_ms * 1e-3) / 1e12 if kernel_ms else float("nan")
     # which matrix pipe the dominant kernel runs on decides the peak it is priced against
-    split = args.search == "auto" and 4 <= wl.d <= 64
+    split = args.search == "auto" and 4 <= wl.d <= 64 and wl.k > 384     # (the library keeps small maps on float32)
     if split:
         kb, kpad = (wl.d + 15) // 16, (wl.k + 127) // 128 * 128
         issued = 3 * 2.0 * m * kpad * 16 * kb              # three bf16 MFMA products per float32 product, padded shape
