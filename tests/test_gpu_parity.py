@@ -759,6 +759,7 @@ def test_argument_errors_are_reported_not_fatal(som):
     assert lib.som_topology(h, p(Wd), 4, 3, 1, None) == SOM_EINVAL
     assert lib.som_topology(h, p(Wd), 20000, 3, 1, p(Gout)) == SOM_EINVAL                              # above the node limit
     assert lib.som_set_safeguard(h, 9) == SOM_EINVAL
+    assert lib.som_set_search(h, 2) == SOM_EINVAL
     assert lib.som_set_update_rule(h, 0.0, 0.0, None) == SOM_EINVAL                                    # eta out of (0, 1]
     assert lib.som_set_update_rule(h, 1.0, 0.5, None) == SOM_EINVAL                                    # momentum needs a velocity
     assert (Wd.cpu().numpy() == W).all()            # rejected calls leave W alone
