@@ -1856,7 +1856,30 @@ static int dispatch_bmu(som_ctx* ctx, int steps, const BmuArgs& a)
     return fail(ctx, SOM_EINVAL, "no BMU kernel for %d steps", steps);
 }
 
+static int bmu_run_pass(som_ctx* ctx, BmuPrep& prep, BmuArgs a);
+
+// The rows go through in passes of at most 2^27: the re-decision workspace then stays near 1.7 GB whatever m is,
+// and a pass's list stays within what the candidate pass can hold (2^24 entries, an eighth of a pass) — one call over
+// 10^9 rows listed more than that and fell back to direct differences over all nodes for every listed sample.
 int bmu_run(som_ctx* ctx, BmuPrep& prep, BmuArgs a)
+{
+    constexpr int64_t kRowsPerPass = (int64_t)1 << 27;
+    const int64_t m = a.m;
+    for (int64_t off = 0; off < m; off += kRowsPerPass) {
+        BmuArgs b = a;
+        b.m = m - off < kRowsPerPass ? m - off : kRowsPerPass;
+        if (a.idx)
+            b.idx = a.idx + off;
+        else
+            b.X = a.X + off * a.ldx;
+        b.bmu = a.bmu + off;
+        if (a.d2) b.d2 = a.d2 + off;
+        if (int rc = bmu_run_pass(ctx, prep, b)) return rc;
+    }
+    return SOM_OK;
+}
+
+static int bmu_run_pass(som_ctx* ctx, BmuPrep& prep, BmuArgs a)
 {
     if (a.m <= 0) return SOM_OK;
     auto cand_cap_for = [](size_t cap) { return cap < kCandCapMax ? cap : kCandCapMax; };

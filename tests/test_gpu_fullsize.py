@@ -102,3 +102,38 @@ def test_full_size_accumulate_properties_and_epoch(som, cfg1):
     assert (np.abs(Wd.cpu().numpy() - ref["W"]) <= 1e-4 * scale).all()
     assert abs(st.qe - oracle.quantization_error(best)) <= 1e-4 * oracle.quantization_error(best)
     assert st.n_empty == int((ref["n"] == 0).sum()) and st.m == wl.n
+
+
+def test_bmu_over_more_rows_than_one_pass(som):
+    """More than 2^27 rows (the library's BMU search takes them in passes of that size): sampled rows, among them
+    the ones either side of the pass boundary, against the brute-force oracle; sums over all rows."""
+    from concurrent.futures import ThreadPoolExecutor
+    from synth import Uniform01
+    m, D, K = (1 << 27) + 100_003, 4, 500
+    gen = Uniform01(4711, D)
+    Xd = torch.empty((m, D), dtype=torch.float32, device="cuda")
+    piece = 1 << 24
+    with ThreadPoolExecutor(8) as pool:
+        for lo, rows in zip(range(0, m, piece), pool.map(lambda lo: gen.rows(lo, min(m, lo + piece)), range(0, m, piece))):
+            Xd[lo:lo + len(rows)].copy_(torch.from_numpy(rows))
+    W = gen.rows(m, m + K).copy()
+    Wd = torch.from_numpy(W).cuda()
+    d2 = torch.empty(m, dtype=torch.float32, device="cuda")
+    qe = torch.zeros(2, dtype=torch.float64, device="cuda")
+    b_gpu, _, _ = som.som_bmu(Xd, Wd, d2=d2, qe=qe)
+    som.som_sync()
+    edge = 1 << 27
+    rows = np.unique(np.concatenate([np.random.default_rng(3).choice(m, 5000, replace=False),
+                                     [0, edge - 257, edge - 1, edge, edge + 1, edge + 255, edge + 256, m - 1]]))
+    rows_d = torch.from_numpy(rows).cuda()
+    Xs = Xd[rows_d].cpu().numpy()
+    b, best, second = oracle.bmu(Xs, W)
+    mask = oracle.near_tie_mask(best, second)
+    got = b_gpu[rows_d].cpu().numpy()
+    assert ((got == b) | mask).all()
+    same = got == b
+    np.testing.assert_allclose(d2[rows_d].cpu().numpy()[same], best[same], rtol=1e-4, atol=1e-12)
+    assert int(b_gpu.min()) >= 0 and int(b_gpu.max()) < K
+    q = qe.cpu().numpy()
+    assert abs(q[1] - float(d2.double().sum())) <= 1e-6 * q[1]
+    assert abs(q[0] - float(d2.double().sqrt().sum())) <= 1e-6 * q[0]
