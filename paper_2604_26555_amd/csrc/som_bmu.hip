@@ -593,15 +593,15 @@ __global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2
 }
 
 // ---------------------------------------------------------------------------------------------------------
-// The same search with the contraction on the bf16 matrix pipe (4 <= D <= 64).
+// The same search with the contraction on the bf16 matrix pipe (4 <= D <= 64; chosen for maps above 384 nodes).
 //
 // A float32 value v is cut into two bf16 parts, hi = bf16(v) and lo = bf16(v - hi) (both rounded to nearest, the
 // difference is exact in float32), so that |v - hi - lo| <= 2^-18 |v|.  A score then takes three bf16 MFMAs per 16
 // features (v_mfma_f32_32x32x16_bf16, products exact, float32 accumulation):
 //     x . w  ~  xh . wh + xl . wh + xh . wl,
 // the dropped parts together below 3 * 2^-18 |x| |w|.  The bf16 pipe runs these three in 96 cycles where the
-// float32 MFMAs of the same 16 features take 512, and unlike those it leaves half of the vector issue slots to the
-// fold, which runs beside it.  Nothing else changes: the error bound is wider (the split, and the pipe's accumulation
+// float32 MFMAs of the same 16 features take 512, and unlike those it leaves three quarters of the vector issue
+// slots to the fold, which runs beside it (csrc/probe_matrix_pipe.hip measures both).  Nothing else changes: the error bound is wider (the split, and the pipe's accumulation
 // error per MFMA as measured on this chip), samples inside it go on the same list and are decided by the same direct
 // differences, so the results are those of the float32 search.
 //
@@ -609,7 +609,7 @@ __global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2
 // q + 1, group q being the window [min(4 q, D - 4), + 4) of the row: always whole and inside the row, so a group is
 // one 16-byte load; where the window is shifted back the stage rows hold zero weights in front of the group's own
 // features, and no feature is counted twice.  A stage row is [kb][g][hi x 8 | lo x 8] bf16 plus 16 bytes of padding
-// (row stride 64 KB + 16 bytes: the 16-byte reads of sixteen consecutive rows fall into distinct banks), followed
+// (row stride 64 * blocks + 16 bytes: the 16-byte reads of sixteen consecutive rows fall into distinct banks), followed
 // by the stage's 128 half squared norms in float32.
 // The fold keeps the position inside a block in the low four bits of the score (one and-or instead of a compare
 // and a select; 16 units of the last place are part of the bound), so padding nodes carry a large finite negative
@@ -987,7 +987,8 @@ __device__ __forceinline__ void bmu_split_tile(const BmuArgs& a, int64_t first, 
     if (a.qe) group_qe_add(a.qe_part, qs, qs2);
 }
 
-template <int KB, int MS, bool PAD>
+// full tiles for the workgroups below a.full_tiles, half tiles for the last partial round (as bmu_kernel)
+template <int KB, int MS>
 __global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 2))) bmu_split_kernel(const BmuArgs a)
 {
     extern __shared__ float4 lds4[];
@@ -1767,16 +1768,15 @@ template <int KB, int MS>
 static int launch_bmu_split(som_ctx* ctx, const BmuArgs& a)
 {
     constexpr size_t lds_bytes = 2 * (size_t)split_stage_f4(KB) * 16;
-    const bool pad = a.kpad - a.K >= 32;
-    static bool attr_set[2] = {false, false};
-    auto kern = pad ? bmu_split_kernel<KB, MS, true> : bmu_split_kernel<KB, MS, false>;
-    if (!attr_set[pad]) {
+    static bool attr_set = false;
+    auto kern = bmu_split_kernel<KB, MS>;
+    if (!attr_set) {
         if (int rc = check_hip(ctx,
                                hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes),
                                "raising the dynamic LDS limit"))
             return rc;
-        attr_set[pad] = true;
+        attr_set = true;
     }
     if (ctx->units == 0) {
         int units = 0;
