@@ -920,7 +920,7 @@ __device__ __forceinline__ void bmu_split_tile(const BmuArgs& a, int64_t first, 
     double qs = 0.0, qs2 = 0.0;
 #pragma unroll
     for (int mp = 0; mp < MS; mp += 2) {
-        float r_best = 0.f, r_second = 0.f, r_xn = 0.f, r_part = 0.f;
+        float r_best = 0.f, r_second = 0.f, r_xn = 0.f, r_part = 0.f, r_wn = 0.f;
         int r_node = 0;
         bool r_valid = false;
 #pragma unroll
@@ -940,7 +940,7 @@ __device__ __forceinline__ void bmu_split_tile(const BmuArgs& a, int64_t first, 
             // squared norm of the centred sample and squared distance to the winner by direct differences on the
             // float32 values, this lane's slots (the row is read again: it is still in the cache; the winner's
             // centred weights come from the float32 copy of the stage rows, in the same slot order)
-            float xn = 0.f, part = 0.f;
+            float xn = 0.f, part = 0.f, wn = 0.f;
             {
                 float v[KB][8];
                 centred_slots(xrow[mb], d_again, v);
@@ -955,23 +955,29 @@ __device__ __forceinline__ void bmu_split_tile(const BmuArgs& a, int64_t first, 
                         const float df = v[kb][t] - w[t];
                         xn = fmaf(v[kb][t], v[kb][t], xn);
                         part = fmaf(df, df, part);
+                        wn = fmaf(w[t], w[t], wn);
                     }
                 }
             }
             xn += __shfl_xor(xn, 32);
             part += __shfl_xor(part, 32);
+            wn += __shfl_xor(wn, 32);
             if (q == g) {
                 r_best = bst;
                 r_second = sec;
                 r_node = node;
                 r_xn = xn;
                 r_part = part;
+                r_wn = wn;
                 r_valid = valid[mb];
             }
         }
         const int64_t i = wave0 + (mp + g) * 32 + j;
         const float xl2 = sqrtf(r_xn);
-        const float bound = (xl2 * wmax + 0.5f * wmax2) * rel;
+        // The winner's score errs by at most rel / 2 of its own magnitude bound, |x||w_b| + |w_b|^2 / 2 with the
+        // winner's own norm; any other node's by at most rel / 2 of the bound with the largest norm.
+        const float wb = fminf(sqrtf(r_wn) * 1.00001f, wmax);
+        const float bound = 0.5f * rel * ((xl2 * wb + 0.5f * wb * wb) + (xl2 * wmax + 0.5f * wmax2));
         const float tiny = (xl2 + wmax) * (xl2 + wmax) * 3.8146973e-06f;
         const bool close = r_valid && a.K > 1 && (!((r_best - r_second) > bound) || r_part < tiny);
         if (r_valid) {
