@@ -210,11 +210,13 @@ def main() -> int:
     flops = 2.0 * m * wl.k * wl.d                          # algorithmic: 2 K D per presented sample
     achieved = flops / (avg_kernel_ms * 1e-3) / 1e12 if kernel_ms else float("nan")
     # which matrix pipe the dominant kernel runs on decides the peak it is priced against
-    split = args.search == "auto" and 4 <= wl.d <= 64 and wl.k > 384     # (the library keeps small maps on float32)
+    split = args.search == "auto" and wl.d >= 4 and wl.k > 384     # (the library keeps small maps on float32)
     if split:
-        kb, kpad = (wl.d + 15) // 16, (wl.k + 127) // 128 * 128
-        issued = 3 * 2.0 * m * kpad * 16 * kb              # three bf16 MFMA products per float32 product, padded shape
-        roof = {"bound": "mfma", "kernel": "bmu_split_kernel (scores from bf16 parts on the bf16 matrix pipe + arg-max)",
+        # padded shape: 16-feature blocks up to D = 64, chunks of 64 features above; 128-node stages
+        dpad, kpad = ((wl.d + 15) // 16 * 16) if wl.d <= 64 else ((wl.d + 63) // 64 * 64), (wl.k + 127) // 128 * 128
+        issued = 3 * 2.0 * m * kpad * dpad                 # three bf16 MFMA products per float32 product, padded shape
+        roof = {"bound": "mfma", "kernel": ("bmu_split_kernel" if wl.d <= 64 else "bmu_split_convert_kernel + bmu_split_wide_kernel") +
+                          " (scores from bf16 parts on the bf16 matrix pipe + arg-max)",
                 "achieved": achieved, "peak": PEAK_BF16_MFMA_TFLOPS, "unit": "TFLOP/s",
                 "frac": achieved / PEAK_BF16_MFMA_TFLOPS if kernel_ms else None,
                 "issued": issued / (avg_kernel_ms * 1e-3) / 1e12 if kernel_ms else None,

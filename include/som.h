@@ -167,10 +167,11 @@ int som_set_reproducible(som_ctx* ctx, int on);
  * Which matrix pipe forms the scores of the best-matching-unit search (Section 3.3.1: b(x); not an operation of
  * the paper).  The results are the same either way: every sample whose best two scores lie inside the worst-case
  * rounding bound of the arithmetic in use is re-decided by direct float32 differences.
- *   SOM_SEARCH_AUTO (default)  for 4 <= D <= 64 and K > 384 the samples and weights are cut into two bf16 parts each
+ *   SOM_SEARCH_AUTO (default)  for D >= 4 and K > 384 the samples and weights are cut into two bf16 parts each
  *                              and a score is the sum of three bf16 MFMA products (error below 2^-15 of
- *                              |x||w| + |w|^2/2 for a difference of two scores); other shapes use the float32
- *                              MFMA search;
+ *                              |x||w| + |w|^2/2 for a difference of two scores); for D > 64 the samples' parts
+ *                              are written once per call into a library-owned workspace of up to 16 GB (rows go
+ *                              through in passes that fit it); other shapes use the float32 MFMA search;
  *   SOM_SEARCH_FLOAT32         float32 MFMA for every shape.
  * Applies to every later som_bmu / som_epoch / som_epoch_host on this context.
  */

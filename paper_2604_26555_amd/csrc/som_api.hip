@@ -153,6 +153,7 @@ void som_destroy(som_ctx* c)
     if (c->recheck) (void)hipFree(c->recheck);
     if (c->bmu_ws) (void)hipFree(c->bmu_ws);
     if (c->acc_blob) (void)hipFree(c->acc_blob);
+    if (c->parts_blob) (void)hipFree(c->parts_blob);
     if (c->upd_blob) (void)hipFree(c->upd_blob);
     if (c->topo_blob) (void)hipFree(c->topo_blob);
     if (c->S) (void)hipFree(c->S);

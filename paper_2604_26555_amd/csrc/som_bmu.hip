@@ -593,7 +593,8 @@ __global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2
 }
 
 // ---------------------------------------------------------------------------------------------------------
-// The same search with the contraction on the bf16 matrix pipe (4 <= D <= 64; chosen for maps above 384 nodes).
+// The same search with the contraction on the bf16 matrix pipe (this kernel: 4 <= D <= 64, bmu_split_wide_kernel
+// below: D > 64; chosen for maps above 384 nodes).
 //
 // A float32 value v is cut into two bf16 parts, hi = bf16(v) and lo = bf16(v - hi) (both rounded to nearest, the
 // difference is exact in float32), so that |v - hi - lo| <= 2^-18 |v|.  A score then takes three bf16 MFMAs per 16
@@ -624,6 +625,7 @@ constexpr int split_stage_f4(int kb)
 }
 constexpr float kSplitPadNorm = -3.0e38f;
 constexpr int kSplitMinNodes = 384;            // SOM_SEARCH_AUTO: smaller maps use the float32 search
+constexpr size_t kPartsBytes = (size_t)16 << 30;   // workspace of the samples' bf16 parts (D > 64), per pass
 constexpr int kSplitMS = 2;
 
 __device__ __forceinline__ void split8(const float (&v)[8], bf16x8& hi, bf16x8& lo)
@@ -638,36 +640,41 @@ __device__ __forceinline__ void split8(const float (&v)[8], bf16x8& hi, bf16x8& 
 // first feature of slot group q (four consecutive features)
 __device__ __forceinline__ int split_window(int q, int D) { return 4 * q < D - 4 ? 4 * q : D - 4; }
 
-// stage16 from W: one thread per (node, slot); the first kpad threads also copy the half squared norms from the
-// float32 stage (written by bmu_prep_kernel, which runs before this one on the same stream)
+// stage16 from W: one thread per (node, slot), chunks of kb_count 16-feature blocks (one chunk for D <= 64, chunks of
+// 64 features above); the first kpad threads also copy the half squared norms from the float32 stage (written by
+// bmu_prep_kernel, which runs before this one on the same stream; nch32 = its chunks per stage)
 __global__ void __launch_bounds__(256) bmu_prep_split_kernel(const float* __restrict__ W, int K, int D, int kpad, int kb_count,
-                                                             const float* __restrict__ centre,
+                                                             int nch16, const float* __restrict__ centre,
                                                              const float* __restrict__ stage, int stride, int stage_floats,
-                                                             char* __restrict__ stage16, int row_bytes, int stage16_bytes,
-                                                             float* __restrict__ wwin)
+                                                             int nch32, char* __restrict__ stage16, int row_bytes,
+                                                             int stage16_bytes, float* __restrict__ wwin)
 {
     const int e = blockIdx.x * 256 + threadIdx.x;
-    const int slots = kb_count * 16;
+    const int per_chunk = kb_count * 16, slots = nch16 * per_chunk;
     if (e < kpad * slots) {
         const int k = e / slots, sl = e - k * slots;
-        const int kb = sl >> 4, g = (sl >> 3) & 1, t = sl & 7;
-        const int q = 4 * kb + 2 * g + (t >> 2);
-        const int f = split_window(q, D) + (t & 3);
-        const bool real = k < K && f >= 4 * q;                       // f < D always
+        const int chunk = sl / per_chunk, within = sl - chunk * per_chunk;
+        const int kb = within >> 4, g = (within >> 3) & 1, t = within & 7;
+        const int f0 = 64 * chunk + 4 * (4 * kb + 2 * g + (t >> 2));      // the slot group's own first feature
+        const int f = (f0 < D - 4 ? f0 : D - 4) + (t & 3);               // its window, always inside the row
+        const bool real = k < K && f >= f0;
         const float v = real ? W[(size_t)k * D + f] - centre[f] : 0.0f;
         const __bf16 hi = (__bf16)v;
         const __bf16 lo = (__bf16)(v - (float)hi);
-        char* row = stage16 + (size_t)(k / kNodesPerStage) * stage16_bytes + (size_t)(k % kNodesPerStage) * row_bytes;
+        char* row = stage16 + ((size_t)(k / kNodesPerStage) * nch16 + chunk) * stage16_bytes +
+                    (size_t)(k % kNodesPerStage) * row_bytes;
         __bf16* cell = reinterpret_cast<__bf16*>(row + kb * 64 + g * 32) + t;
         cell[0] = hi;
         cell[8] = lo;
-        wwin[e] = v;                 // the same slots in float32, [node][kb][g][8]: the winner's row for the distances
+        if (wwin) wwin[e] = v;       // the same slots in float32, [node][kb][g][8]: the winner's row for the distances
     }
     if (e < kpad) {
         const int st = e / kNodesPerStage, r = e % kNodesPerStage;
-        float nh = stage[(size_t)st * stage_floats + (size_t)kNodesPerStage * stride + r];
+        float nh = stage[(size_t)st * nch32 * stage_floats + (size_t)kNodesPerStage * stride + r];
         if (!(nh > kSplitPadNorm)) nh = kSplitPadNorm;
-        reinterpret_cast<float*>(stage16 + (size_t)st * stage16_bytes + (size_t)kNodesPerStage * row_bytes)[r] = nh;
+        for (int chunk = 0; chunk < nch16; ++chunk)
+            reinterpret_cast<float*>(stage16 + ((size_t)st * nch16 + chunk) * stage16_bytes +
+                                     (size_t)kNodesPerStage * row_bytes)[r] = nh;
     }
 }
 
@@ -1288,6 +1295,255 @@ __global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2
 }
 
 // ---------------------------------------------------------------------------------------------------------
+// The split search for D > 64: chunks of 64 features (four 16-feature blocks) through the same stage rows, one block
+// of 32 samples per wavefront, the four node blocks' accumulators of a stage live across the chunks (as
+// bmu_wide_tile).  A wavefront meets every chunk of its samples once per stage, so the samples' bf16 parts are not
+// made in this kernel (tried: the conversion, 250 vector instructions per chunk and stage beside 48 MFMAs, made it
+// slower than the float32 kernel) but once per pass by bmu_split_convert_kernel, into a[parts]: per presented
+// sample and slot group of eight features 32 bytes, [hi x 8 | lo x 8], which a lane reads as they are.
+// Every chunk's partial product is summed on its own from zero and then added, so that the roundings inside a chunk
+// are relative to |x_chunk| |w_chunk| and add up to at most |x| |w| over the chunks (Cauchy-Schwarz).
+// Slot group q of chunk ch is the row's window [min(64 ch + 4 q, D - 4), + 4); the weights (bmu_prep_split_kernel)
+// and the samples (the conversion) are zero in front of a shifted window's own features.
+// ---------------------------------------------------------------------------------------------------------
+// one thread per (presented sample, group of eight slots): centred, cut into bf16 parts
+__global__ void __launch_bounds__(256) bmu_split_convert_kernel(const BmuArgs a, int nch16)
+{
+    const int groups = nch16 * 8;
+    const int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (e >= a.m * groups) return;
+    const int64_t i = e / groups;
+    const int grp = (int)(e - i * groups);
+    const int chunk = grp >> 3, kb = (grp >> 1) & 3, g = grp & 1;
+    const int64_t row = a.idx ? (int64_t)a.idx[i] : i;
+    const float* xr = a.X + row * a.ldx;
+    float v[8];
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        const int f0 = 64 * chunk + 4 * (4 * kb + 2 * g + h);
+        const int start = f0 < a.D - 4 ? f0 : a.D - 4;
+        const int shift = f0 - start;                                     // own slots: index >= shift
+        const float4 x4 = load4(xr + start), c4 = load4(a.centre + start);
+        v[4 * h + 0] = shift <= 0 ? x4.x - c4.x : 0.0f;
+        v[4 * h + 1] = shift <= 1 ? x4.y - c4.y : 0.0f;
+        v[4 * h + 2] = shift <= 2 ? x4.z - c4.z : 0.0f;
+        v[4 * h + 3] = shift <= 3 ? x4.w - c4.w : 0.0f;
+    }
+    bf16x8 hi, lo;
+    split8(v, hi, lo);
+    bf16x8* out = reinterpret_cast<bf16x8*>(a.parts) + e * 2;
+    out[0] = hi;
+    out[1] = lo;
+}
+
+template <bool CAND>
+__device__ __forceinline__ void bmu_split_wide_tile(const BmuArgs& a, int64_t tile_index, unsigned int count, float4* lds4)
+{
+    constexpr int KB = 4, NBS = kNodesPerStage / 32;
+    constexpr int RS = split_row_bytes(KB);
+    constexpr int STAGE_F4 = split_stage_f4(KB);
+    constexpr int PRE = STAGE_F4 / kThreads;
+    static_assert(PRE <= 9, "stage copy holds at most nine float4 per thread");
+    const char* ldsb = reinterpret_cast<const char*>(lds4);
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int j = lane & 31, g = lane >> 5;
+    const int64_t i = (tile_index * kWavesPerGroup + wave) * 32 + j;      // sample position, or list entry (CAND)
+    const int64_t total = CAND ? (int64_t)count : a.m;
+    const bool valid = i < total;
+    int64_t ii = valid ? i : total - 1;
+    float cut = NAN;                                                        // CAND; no score compares >= NaN
+    CandSet noted;
+    if constexpr (CAND) {
+        if (valid) cut = a.cutv[ii];
+        ii = (int64_t)a.recheck[ii];
+    }
+    const int64_t row = a.idx ? (int64_t)a.idx[ii] : ii;
+    const float* xr = a.X + row * a.ldx;
+
+    float best = -INFINITY, second = -INFINITY;
+    int rsel = 0, tsel = 0;
+    const int nstages = a.kpad / kNodesPerStage;
+    const int nch = (a.D + 63) / 64;
+    const int nq = nstages * nch;
+    const float4* src4 = reinterpret_cast<const float4*>(a.stage16);
+#pragma unroll
+    for (int p = 0; p < PRE; ++p) lds4[tid + p * kThreads] = src4[tid + p * kThreads];
+    __syncthreads();
+
+    // this lane's parts of a chunk: four groups of eight slots, 32 bytes each
+    const bf16x8* prow = reinterpret_cast<const bf16x8*>(a.parts) + (size_t)ii * (nch * 8) * 2;
+    auto read_chunk = [&](int chunk, bf16x8 (&h8)[KB], bf16x8 (&l8)[KB]) {
+#pragma unroll
+        for (int kb = 0; kb < KB; ++kb) {
+            const bf16x8* p = prow + (size_t)((chunk * 4 + kb) * 2 + g) * 2;
+            h8[kb] = p[0];
+            l8[kb] = p[1];
+        }
+    };
+    bf16x8 xh[KB], xl[KB];
+    read_chunk(0, xh, xl);
+
+    floatx16 acc[NBS];
+    int st = 0, ch = 0;
+    for (int q = 0; q < nq; ++q) {
+        const int buf = q & 1;
+        float4 pre0, pre1, pre2, pre3, pre4, pre5, pre6, pre7, pre8;
+        {
+            const int nxt = (q + 1 < nq) ? q + 1 : q;
+            const float4* s4 = src4 + (size_t)nxt * STAGE_F4 + tid;
+#define SOM_PRE_LOAD(i) if constexpr (PRE > i) pre##i = s4[i * kThreads];
+            SOM_PRE_LOAD(0) SOM_PRE_LOAD(1) SOM_PRE_LOAD(2) SOM_PRE_LOAD(3) SOM_PRE_LOAD(4)
+            SOM_PRE_LOAD(5) SOM_PRE_LOAD(6) SOM_PRE_LOAD(7) SOM_PRE_LOAD(8)
+#undef SOM_PRE_LOAD
+        }
+        // the samples' next chunk travels to registers during this chunk's arithmetic
+        const int chn = (ch + 1 == nch) ? 0 : ch + 1;
+        bf16x8 xhn[KB], xln[KB];
+        read_chunk(chn, xhn, xln);
+        __builtin_amdgcn_sched_barrier(0);
+        const char* wbuf = ldsb + (size_t)buf * STAGE_F4 * 16;
+        const float* nbuf = reinterpret_cast<const float*>(wbuf + kNodesPerStage * RS);
+        bf16x8 wh[KB], wl[KB];
+        {
+            const char* wrow = wbuf + j * RS + g * 32;
+#pragma unroll
+            for (int kb = 0; kb < KB; ++kb) {
+                wh[kb] = *reinterpret_cast<const bf16x8*>(wrow + kb * 64);
+                wl[kb] = *reinterpret_cast<const bf16x8*>(wrow + kb * 64 + 16);
+            }
+        }
+#pragma unroll
+        for (int nb = 0; nb < NBS; ++nb) {
+            if (ch == 0) {
+                const float4* nh = reinterpret_cast<const float4*>(nbuf + nb * 32 + 4 * g);
+#pragma unroll
+                for (int t = 0; t < 4; ++t) {
+                    const float4 v = nh[2 * t];
+                    acc[nb][4 * t + 0] = v.x;
+                    acc[nb][4 * t + 1] = v.y;
+                    acc[nb][4 * t + 2] = v.z;
+                    acc[nb][4 * t + 3] = v.w;
+                }
+            }
+            const char* wnext = wbuf + ((nb + 1) * 32 + j) * RS + g * 32;
+            floatx16 part;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) part[r] = 0.0f;
+#pragma unroll
+            for (int kb = 0; kb < KB; ++kb) {
+                part = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wh[kb], xh[kb], part, 0, 0, 0);
+                part = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wh[kb], xl[kb], part, 0, 0, 0);
+                part = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wl[kb], xh[kb], part, 0, 0, 0);
+                // the next block's rows, into the registers this block has finished with
+                if (nb + 1 < NBS) {
+                    wh[kb] = *reinterpret_cast<const bf16x8*>(wnext + kb * 64);
+                    wl[kb] = *reinterpret_cast<const bf16x8*>(wnext + kb * 64 + 16);
+                    __builtin_amdgcn_sched_group_barrier(0x008, 3, 0);     // three MFMAs
+                    __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);     // two LDS reads
+                }
+            }
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[nb][r] += part[r];
+            if (CAND && ch == nch - 1) {
+                const int tile = st * NBS + nb;
+#pragma unroll
+                for (int r = 0; r < 16; ++r)
+                    if (acc[nb][r] >= cut) noted.note(tile * 32 + 4 * g, 8 * (r >> 2) + (r & 3));
+            }
+            if (!CAND && ch == nch - 1) {
+                const int tile = st * NBS + nb;
+                const float before = best;
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const float v = acc[nb][r];
+                    rsel = (v > best) ? r : rsel;
+                    second = __builtin_amdgcn_fmed3f(best, second, v);
+                    best = vmax(best, v);
+                }
+                tsel = (best > before) ? tile : tsel;
+            }
+        }
+        {
+            float4* d4 = lds4 + (buf ^ 1) * STAGE_F4 + tid;
+#define SOM_PRE_STORE(i) if constexpr (PRE > i) d4[i * kThreads] = pre##i;
+            SOM_PRE_STORE(0) SOM_PRE_STORE(1) SOM_PRE_STORE(2) SOM_PRE_STORE(3) SOM_PRE_STORE(4)
+            SOM_PRE_STORE(5) SOM_PRE_STORE(6) SOM_PRE_STORE(7) SOM_PRE_STORE(8)
+#undef SOM_PRE_STORE
+        }
+        __syncthreads();
+        if (++ch == nch) {
+            ch = 0;
+            ++st;
+        }
+#pragma unroll
+        for (int kb = 0; kb < KB; ++kb) {
+            xh[kb] = xhn[kb];
+            xl[kb] = xln[kb];
+        }
+    }
+
+    if constexpr (CAND) {
+        if (valid) a.cand[(size_t)i * 2 + g] = noted.packed();
+        return;
+    }
+    // ---- join the two half-wavefronts; squared norm and exact winner distance from memory, half the features each
+    int node = tsel * 32 + 8 * (rsel >> 2) + 4 * g + (rsel & 3);
+    const float ob = __shfl_xor(best, 32), os = __shfl_xor(second, 32);
+    const int on = __shfl_xor(node, 32);
+    const float sec = fmaxf(fmaxf(second, os), fminf(best, ob));
+    const bool other = (ob > best) || (ob == best && on < node);
+    const float bst = other ? ob : best;
+    node = other ? on : node;
+    node = node < a.K ? node : a.K - 1;
+    float xn = 0.f, part = 0.f;
+    const float* wr = a.W + (size_t)node * a.D;
+    for (int f = g; f < a.D; f += 2) {
+        const float xv = xr[f];
+        const float xc = xv - a.centre[f];
+        const float df = xv - wr[f];
+        xn = fmaf(xc, xc, xn);
+        part = fmaf(df, df, part);
+    }
+    xn += __shfl_xor(xn, 32);
+    part += __shfl_xor(part, 32);
+    double qs = 0.0, qs2 = 0.0;
+    const float wmax2 = __uint_as_float(a.scal[0]);
+    const float wmax = sqrtf(wmax2) * 1.000001f;
+    // per score: the split leaves 3 * 2^-18 (1 + 2^-7); inside a chunk 12 MFMAs of at most 8 units of 2^-24 each
+    // (relative to the chunk's magnitude, see above), one addition per chunk, one rounding for -|w|^2/2; two scores,
+    // plus the centring roundings and slack as in bmu_kernel
+    const float rel = 2.0f * (3.0f * 3.8146973e-06f * 1.0078125f + (float)(96 + nch + 1) * 5.9604645e-08f) + 12.0f * 5.9604645e-08f;
+    const float bound = (sqrtf(xn) * wmax + 0.5f * wmax2) * rel;
+    const bool mine = valid && g == 0;
+    const bool close = mine && a.K > 1 && !((bst - sec) > bound);
+    if (mine) {
+        a.bmu[i] = node;
+        if (a.d2) a.d2[i] = part;
+        if (!close) {
+            qs = sqrt((double)part);
+            qs2 = (double)part;
+        }
+    }
+    list_push(&a.scal[a.slot], a.recheck, a.cutv, close, i, bst - bound);
+    if (a.qe) group_qe_add(a.qe_part, qs, qs2);
+}
+
+__global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 2))) bmu_split_wide_kernel(const BmuArgs a)
+{
+    extern __shared__ float4 lds4[];
+    bmu_split_wide_tile<false>(a, blockIdx.x, 0u, lds4);
+}
+
+__global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 2))) bmu_split_wide_cand_kernel(const BmuArgs a)
+{
+    extern __shared__ float4 lds4[];
+    const unsigned int count = a.scal[a.slot];
+    if (!cand_pass_serves(a, count)) return;
+    constexpr int64_t per_tile = (int64_t)kWavesPerGroup * 32;
+    for (int64_t t = blockIdx.x; t * per_tile < (int64_t)count; t += gridDim.x) bmu_split_wide_tile<true>(a, t, count, lds4);
+}
+
+// ---------------------------------------------------------------------------------------------------------
 // exact re-decision of the listed samples by direct differences, sum_d (x_d - w_kd)^2 for every node.
 // A workgroup takes kExactGroup samples at a time; thread t owns nodes t, t + 256, ... so one coalesced read of
 // the transposed weights serves all samples of the group, and the samples' features are broadcast from LDS.
@@ -1599,10 +1855,12 @@ int bmu_prepare(som_ctx* ctx, const float* W, int32_t K, int32_t D, BmuPrep* out
     // rows for the bf16 matrix pipe where the split search applies
     // (small maps stay with the float32 search: a tile is mostly prologue and epilogue there, and the split search's
     // are the longer ones; measured at 10^7 x 50: 256 nodes 3.5 ms against 4.5, 576 nodes 5.7 against 5.1)
-    const int kb = (nch == 1 && D >= 4 && K > kSplitMinNodes && ctx->search != SOM_SEARCH_FLOAT32) ? (D + 15) / 16 : 0;
+    const bool split = D >= 4 && K > kSplitMinNodes && ctx->search != SOM_SEARCH_FLOAT32;
+    const int kb = !split ? 0 : (nch == 1 ? (D + 15) / 16 : 4);
+    const int nch16 = !split ? 0 : (nch == 1 ? 1 : (D + 63) / 64);
     const size_t stage16_one = kb ? (size_t)(kb == 1 ? split_stage_f4(1) : kb == 2 ? split_stage_f4(2) : kb == 3 ? split_stage_f4(3) : split_stage_f4(4)) * 16 : 0;
-    const size_t stage16_bytes = (size_t)(kpad / kNodesPerStage) * stage16_one;
-    const size_t wwin_bytes = (size_t)kpad * kb * 16 * sizeof(float);
+    const size_t stage16_bytes = (size_t)(kpad / kNodesPerStage) * nch16 * stage16_one;
+    const size_t wwin_bytes = nch == 1 ? (size_t)kpad * kb * 16 * sizeof(float) : 0;
     const size_t need = stage_bytes + wt_bytes + centre_bytes + stage16_bytes + wwin_bytes + 256;
     if (need > ctx->prep_bytes) {
         if (ctx->prep_blob) {
@@ -1623,7 +1881,8 @@ int bmu_prepare(som_ctx* ctx, const float* W, int32_t K, int32_t D, BmuPrep* out
     out->wt = (float*)(base + 256 + stage_bytes);
     out->centre = (float*)(base + 256 + stage_bytes + wt_bytes);
     out->stage16 = kb ? (void*)(base + 256 + stage_bytes + wt_bytes + centre_bytes) : nullptr;
-    out->wwin = kb ? (float*)(base + 256 + stage_bytes + wt_bytes + centre_bytes + stage16_bytes) : nullptr;
+    out->wwin = wwin_bytes ? (float*)(base + 256 + stage_bytes + wt_bytes + centre_bytes + stage16_bytes) : nullptr;
+    out->nch16 = nch16;
     out->kb = kb;
     out->kpad = kpad;
     out->steps = steps;
@@ -1640,9 +1899,10 @@ int bmu_prepare(som_ctx* ctx, const float* W, int32_t K, int32_t D, BmuPrep* out
                        stride, nch, stage_floats_for(stride), out->centre, out->stage, out->wt, out->scal, qe, small);
     if (int rc = check_hip(ctx, hipGetLastError(), "bmu_prep launch")) return rc;
     if (kb) {
-        hipLaunchKernelGGL(bmu_prep_split_kernel, dim3((unsigned)(((long long)kpad * kb * 16 + 255) / 256)), dim3(256), 0,
-                           ctx->stream, W, K, D, kpad, kb, out->centre, out->stage, stride, stage_floats_for(stride),
-                           (char*)out->stage16, split_row_bytes(kb), (int)stage16_one, out->wwin);
+        hipLaunchKernelGGL(bmu_prep_split_kernel, dim3((unsigned)(((long long)kpad * nch16 * kb * 16 + 255) / 256)),
+                           dim3(256), 0, ctx->stream, W, K, D, kpad, kb, nch16, out->centre, out->stage, stride,
+                           stage_floats_for(stride), nch, (char*)out->stage16, split_row_bytes(kb), (int)stage16_one,
+                           out->wwin);
         return check_hip(ctx, hipGetLastError(), "bmu_prep_split launch");
     }
     return SOM_OK;
@@ -1666,6 +1926,28 @@ static int launch_bmu_wide(som_ctx* ctx, const BmuArgs& a)
     const int64_t groups = (a.m + per_group - 1) / per_group;
     hipLaunchKernelGGL(kern, dim3((unsigned)groups), dim3(kThreads), lds_bytes, ctx->stream, a);
     return check_hip(ctx, hipGetLastError(), "bmu (wide) kernel launch");
+}
+
+static int launch_bmu_split_wide(som_ctx* ctx, const BmuArgs& a, int nch16)
+{
+    constexpr size_t lds_bytes = 2 * (size_t)split_stage_f4(4) * 16;
+    static bool attr_set = false;
+    if (!attr_set) {
+        if (int rc = check_hip(ctx,
+                               hipFuncSetAttribute(reinterpret_cast<const void*>(bmu_split_wide_kernel),
+                                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes),
+                               "raising the dynamic LDS limit"))
+            return rc;
+        attr_set = true;
+    }
+    // the pass's samples as bf16 parts first
+    const int64_t groups8 = a.m * nch16 * 8;
+    hipLaunchKernelGGL(bmu_split_convert_kernel, dim3((unsigned)((groups8 + 255) / 256)), dim3(256), 0, ctx->stream, a, nch16);
+    if (int rc = check_hip(ctx, hipGetLastError(), "bmu (split, wide) conversion launch")) return rc;
+    const int64_t per_group = (int64_t)kWavesPerGroup * 32;
+    const int64_t groups = (a.m + per_group - 1) / per_group;
+    hipLaunchKernelGGL(bmu_split_wide_kernel, dim3((unsigned)groups), dim3(kThreads), lds_bytes, ctx->stream, a);
+    return check_hip(ctx, hipGetLastError(), "bmu (split, wide) kernel launch");
 }
 
 // grid of the candidate kernels: the tiles of the longest list they may serve, at most kCandGrid workgroups
@@ -1692,6 +1974,23 @@ static int launch_bmu_wide_cand(som_ctx* ctx, const BmuArgs& a)
     }
     hipLaunchKernelGGL(kern, dim3(cand_grid(a, (int64_t)kWavesPerGroup * 32)), dim3(kThreads), lds_bytes, ctx->stream, a);
     return check_hip(ctx, hipGetLastError(), "bmu (wide) candidate kernel launch");
+}
+
+static int launch_bmu_split_wide_cand(som_ctx* ctx, const BmuArgs& a)
+{
+    constexpr size_t lds_bytes = 2 * (size_t)split_stage_f4(4) * 16;
+    static bool attr_set = false;
+    if (!attr_set) {
+        if (int rc = check_hip(ctx,
+                               hipFuncSetAttribute(reinterpret_cast<const void*>(bmu_split_wide_cand_kernel),
+                                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes),
+                               "raising the dynamic LDS limit"))
+            return rc;
+        attr_set = true;
+    }
+    hipLaunchKernelGGL(bmu_split_wide_cand_kernel, dim3(cand_grid(a, (int64_t)kWavesPerGroup * 32)), dim3(kThreads),
+                       lds_bytes, ctx->stream, a);
+    return check_hip(ctx, hipGetLastError(), "bmu (split, wide) candidate kernel launch");
 }
 
 template <int STEPS, int MS>
@@ -1869,8 +2168,31 @@ static int bmu_run_pass(som_ctx* ctx, BmuPrep& prep, BmuArgs a);
 // 10^9 rows listed more than that and fell back to direct differences over all nodes for every listed sample.
 int bmu_run(som_ctx* ctx, BmuPrep& prep, BmuArgs a)
 {
-    constexpr int64_t kRowsPerPass = (int64_t)1 << 27;
+    int64_t kRowsPerPass = (int64_t)1 << 27;
     const int64_t m = a.m;
+    // the split search for D > 64 reads the pass's samples as bf16 parts from a workspace of its own: 256 bytes per
+    // sample and chunk of 64 features, at most kPartsBytes in all (shorter passes for wide rows)
+    if (prep.stage16 && prep.nch > 1) {
+        const size_t row_bytes = (size_t)prep.nch16 * 256;
+        int64_t rows = (int64_t)(kPartsBytes / row_bytes) / 128 * 128;
+        if (rows < 128) rows = 128;
+        if (rows < kRowsPerPass) kRowsPerPass = rows;
+        const size_t need = (size_t)(m < kRowsPerPass ? m : kRowsPerPass) * row_bytes;
+        if (need > ctx->parts_bytes) {
+            if (ctx->parts_blob) {
+                if (int rc = check_hip(ctx, hipStreamSynchronize(ctx->stream), "sync before workspace growth")) return rc;
+                (void)hipFree(ctx->parts_blob);
+                ctx->parts_blob = nullptr;
+                ctx->parts_bytes = 0;
+            }
+            if (hipMalloc(&ctx->parts_blob, need) != hipSuccess) {
+                (void)hipGetLastError();
+                return fail(ctx, SOM_ENOMEM, "cannot allocate %zu bytes for the samples' bf16 parts", need);
+            }
+            ctx->parts_bytes = need;
+        }
+        a.parts = ctx->parts_blob;
+    }
     for (int64_t off = 0; off < m; off += kRowsPerPass) {
         BmuArgs b = a;
         b.m = m - off < kRowsPerPass ? m - off : kRowsPerPass;
@@ -1942,14 +2264,16 @@ static int bmu_run_pass(som_ctx* ctx, BmuPrep& prep, BmuArgs a)
         stop = ctx->prof_events[ctx->prof_used].second;
         ++ctx->prof_used;
     }
-    int rc = prep.nch > 1 ? (prep.steps == 25   ? launch_bmu_wide<25>(ctx, a)
+    int rc = prep.nch > 1 ? (prep.stage16        ? launch_bmu_split_wide(ctx, a, prep.nch16)
+                             : prep.steps == 25 ? launch_bmu_wide<25>(ctx, a)
                              : prep.steps == 28 ? launch_bmu_wide<28>(ctx, a)
                                                 : launch_bmu_wide<32>(ctx, a))
                           : (prep.stage16 ? dispatch_bmu_split(ctx, prep.kb, a) : dispatch_bmu(ctx, prep.steps, a));
     if (stop) (void)hipEventRecord(stop, ctx->stream);
     if (rc) return rc;
     if (cand_possible) {
-        rc = prep.nch > 1 ? (prep.steps == 25   ? launch_bmu_wide_cand<25>(ctx, a)
+        rc = prep.nch > 1 ? (prep.stage16        ? launch_bmu_split_wide_cand(ctx, a)
+                             : prep.steps == 25 ? launch_bmu_wide_cand<25>(ctx, a)
                              : prep.steps == 28 ? launch_bmu_wide_cand<28>(ctx, a)
                                                 : launch_bmu_wide_cand<32>(ctx, a))
                           : (prep.stage16 ? dispatch_bmu_split_cand(ctx, prep.kb, a) : dispatch_bmu_cand(ctx, prep.steps, a));

@@ -19,6 +19,7 @@ struct BmuPrep {
     void* stage16 = nullptr;       // bf16 hi/lo stage rows of the split search (4 <= D <= 64), else null
     float* wwin = nullptr;         // [Kpad][kb][2][8] the same slots as stage16 in float32 (centred, zeros off-window)
     int kb = 0;                    // 16-feature blocks of a stage16 row
+    int nch16 = 0;                 // chunks of a stage in stage16 (1 for D <= 64, 64-feature chunks above)
     float* wt = nullptr;           // [D][Kpad] transposed weights (as given, not centred)
     float* centre = nullptr;       // [D] column means of W; stage rows and sample registers hold values minus this
     // [0] = bits of max_k |w_k - centre|^2, [1], [2] = recheck-list length (alternating calls), [3] = total,
@@ -40,6 +41,7 @@ struct BmuArgs {
     int32_t stride;          // BmuPrep::stride (floats per row of the float32 stage)
     const void* stage16;     // BmuPrep::stage16 (null: float32 search)
     const float* wwin;       // BmuPrep::wwin
+    void* parts;             // split search, D > 64: the pass's samples as bf16 parts, [m][chunks * 8][hi x 8 | lo x 8]
     const float* wt;         // BmuPrep::wt
     const float* centre;     // BmuPrep::centre
     unsigned int* scal;      // BmuPrep::scal
@@ -82,6 +84,8 @@ struct som_ctx {
     int32_t* bmu_ws = nullptr;     // BMU indices of the epoch drivers (one chunk's worth)
     size_t bmu_elems = 0;
     void* acc_blob = nullptr;      // per-workgroup float64 slices + counts of the accumulation pass
+    void* parts_blob = nullptr;    // the presented samples of a pass as bf16 parts (split search, D > 64)
+    size_t parts_bytes = 0;
     size_t acc_bytes = 0;
     void* upd_blob = nullptr;      // influence matrix + split-k partials of the update
     size_t upd_bytes = 0;
