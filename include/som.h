@@ -170,7 +170,7 @@ int som_set_reproducible(som_ctx* ctx, int on);
  *   SOM_SEARCH_AUTO (default)  for D >= 4 and K > 384 the samples and weights are cut into two bf16 parts each
  *                              and a score is the sum of three bf16 MFMA products (error below 2^-15 of
  *                              |x||w| + |w|^2/2 for a difference of two scores); for D > 64 the samples' parts
- *                              are written once per call into a library-owned workspace of up to 16 GB (rows go
+ *                              are written once per call into a library-owned workspace of up to 8 GB (rows go
  *                              through in passes that fit it); other shapes use the float32 MFMA search;
  *   SOM_SEARCH_FLOAT32         float32 MFMA for every shape.
  * Applies to every later som_bmu / som_epoch / som_epoch_host on this context.

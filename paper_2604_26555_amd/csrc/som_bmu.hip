@@ -625,7 +625,7 @@ constexpr int split_stage_f4(int kb)
 }
 constexpr float kSplitPadNorm = -3.0e38f;
 constexpr int kSplitMinNodes = 384;            // SOM_SEARCH_AUTO: smaller maps use the float32 search
-constexpr size_t kPartsBytes = (size_t)16 << 30;   // workspace of the samples' bf16 parts (D > 64), per pass
+constexpr size_t kPartsBytes = (size_t)8 << 30;    // workspace of the samples' bf16 parts (D > 64), per pass
 constexpr int kSplitMS = 2;
 
 __device__ __forceinline__ void split8(const float (&v)[8], bf16x8& hi, bf16x8& lo)

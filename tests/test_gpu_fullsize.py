@@ -137,3 +137,33 @@ def test_bmu_over_more_rows_than_one_pass(som):
     q = qe.cpu().numpy()
     assert abs(q[1] - float(d2.double().sum())) <= 1e-6 * q[1]
     assert abs(q[0] - float(d2.double().sqrt().sum())) <= 1e-6 * q[0]
+
+
+def test_bmu_wide_rows_in_several_passes(som):
+    """D = 8192: the default search writes the samples' bf16 parts into a bounded workspace and takes the rows in
+    passes that fit it (262144 rows here); sampled rows around the pass boundary against the brute-force oracle."""
+    from concurrent.futures import ThreadPoolExecutor
+    from synth import Uniform01
+    m, D, K = 300_001, 8192, 400
+    gen = Uniform01(815, D)
+    Xd = torch.empty((m, D), dtype=torch.float32, device="cuda")
+    piece = 1 << 14
+    with ThreadPoolExecutor(8) as pool:
+        for lo, rows in zip(range(0, m, piece), pool.map(lambda lo: gen.rows(lo, min(m, lo + piece)), range(0, m, piece))):
+            Xd[lo:lo + len(rows)].copy_(torch.from_numpy(rows))
+    W = gen.rows(m, m + K).copy()
+    Wd = torch.from_numpy(W).cuda()
+    d2 = torch.empty(m, dtype=torch.float32, device="cuda")
+    b_gpu, _, _ = som.som_bmu(Xd, Wd, d2=d2)
+    som.som_sync()
+    edge = 262_144
+    rows = np.unique(np.concatenate([np.random.default_rng(4).choice(m, 300, replace=False),
+                                     [0, edge - 129, edge - 1, edge, edge + 1, edge + 127, edge + 128, m - 1]]))
+    rows_d = torch.from_numpy(rows).cuda()
+    b, best, second = oracle.bmu(Xd[rows_d].cpu().numpy(), W)
+    mask = oracle.near_tie_mask(best, second)
+    got = b_gpu[rows_d].cpu().numpy()
+    assert ((got == b) | mask).all()
+    same = got == b
+    np.testing.assert_allclose(d2[rows_d].cpu().numpy()[same], best[same], rtol=1e-4, atol=1e-12)
+    assert int(b_gpu.min()) >= 0 and int(b_gpu.max()) < K
