@@ -71,7 +71,10 @@ int som_sync(som_ctx* ctx);
  * Measurement support (not an operation of the paper).  While profiling is enabled the library brackets every
  * launch of its main BMU kernel with a pair of HIP events on the context's stream; som_profile_read waits for the
  * stream, writes up to `capacity` kernel durations in milliseconds (launch order) to ms [host], stores the number
- * of launches recorded since the last read in *count [host], and starts a new record.
+ * of launches recorded since the last read in *count [host], and starts a new record.  A call over more rows than one
+ * pass holds (2^27; fewer for D > 64 in the default search, whose pass must fit the samples' bf16 parts into 8 GB)
+ * launches the kernel once per pass; for D > 64 in the default search a launch's bracket includes the conversion of
+ * the pass's samples.
  */
 int som_profile(som_ctx* ctx, int enable);
 int som_profile_read(som_ctx* ctx, float* ms, int32_t capacity, int32_t* count);
