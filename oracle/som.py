@@ -97,7 +97,7 @@ def near_tie_mask(d2_best: np.ndarray, d2_second: np.ndarray, rel: float = 1e-5)
 
 
 def quantization_error(d2_best: np.ndarray) -> float:
-    """Mean Euclidean distance from each sample to its BMU (Section 4.2's QE)."""
+    """Mean Euclidean distance from each sample to its BMU (the quantisation error of Section 4.1.2)."""
     return float(np.mean(np.sqrt(d2_best))) if len(d2_best) else 0.0
 
 
@@ -248,11 +248,15 @@ def neighborhood_update_shifted(S, n, G, sigma, W):
     return Wn, unchanged
 
 
-def bmu_gram(X, W, block: int = 65536):
+def bmu_gram(X, W, block: int = 65536, rel_tol: float = 1e-9):
     """BMU through |x|^2 - 2 x.w + |w|^2 with a float64 BLAS product; checked against ``bmu`` in the tests.
 
-    The winner and runner-up are then re-evaluated by direct differences so the returned distances carry no
-    cancellation error.
+    The Gram form only shortlists: the two nodes with the smallest Gram values are re-evaluated by direct
+    differences and ordered by (distance, node index), so the returned distances carry no cancellation error and
+    an exact tie between them goes to the lower index whatever order the rounded Gram values put them in.  A
+    row in which a third node's Gram value lies within ``rel_tol`` (|x|^2 + max |w|^2) of the smallest one - a
+    margin some 10^5 times the rounding error of the float64 Gram form - could have its lowest-index minimum
+    outside that pair; such rows are decided by ``bmu``, i.e. by the definition over all nodes.
     """
     X = np.asarray(X)
     W = np.asarray(W, dtype=np.float64)
@@ -264,22 +268,30 @@ def bmu_gram(X, W, block: int = 65536):
     for lo in range(0, m, block):
         hi = min(m, lo + block)
         Xb = np.asarray(X[lo:hi], dtype=np.float64)
-        g = wn[None, :] - 2.0 * (Xb @ W.T)
-        rows = np.arange(hi - lo)
-        if K > 1:
-            c0 = np.argmin(g, axis=1)
-            g[rows, c0] = np.inf
-            c1 = np.argmin(g, axis=1)
-            d0 = np.einsum("id,id->i", Xb - W[c0], Xb - W[c0])
-            d1 = np.einsum("id,id->i", Xb - W[c1], Xb - W[c1])
-            swap = (d1 < d0) | ((d1 == d0) & (c1 < c0))
-            bb = np.where(swap, c1, c0)
-            b[lo:hi] = bb
-            best[lo:hi] = np.where(swap, d1, d0)
-            second[lo:hi] = np.where(swap, d0, d1)
-        else:
+        if K == 1:
             b[lo:hi] = 0
             best[lo:hi] = np.einsum("id,id->i", Xb - W[0], Xb - W[0])
+            continue
+        g = wn[None, :] - 2.0 * (Xb @ W.T)
+        rows = np.arange(hi - lo)
+        c0 = np.argmin(g, axis=1)
+        g0 = g[rows, c0]
+        g[rows, c0] = np.inf
+        c1 = np.argmin(g, axis=1)
+        g[rows, c1] = np.inf
+        tol = rel_tol * (np.einsum("id,id->i", Xb, Xb) + wn.max())
+        crowded = np.nonzero(g.min(axis=1) <= g0 + tol)[0] if K > 2 else np.empty(0, dtype=np.int64)
+        d0 = np.einsum("id,id->i", Xb - W[c0], Xb - W[c0])
+        d1 = np.einsum("id,id->i", Xb - W[c1], Xb - W[c1])
+        swap = (d1 < d0) | ((d1 == d0) & (c1 < c0))
+        b[lo:hi] = np.where(swap, c1, c0)
+        best[lo:hi] = np.where(swap, d1, d0)
+        second[lo:hi] = np.where(swap, d0, d1)
+        if crowded.size:
+            bb, db, ds = bmu(Xb[crowded], W)
+            b[lo + crowded] = bb
+            best[lo + crowded] = db
+            second[lo + crowded] = ds
         del g, rows
     return b, best, second
 

@@ -513,6 +513,30 @@ def test_topology_on_a_square_grid(som):
     assert np.array_equal(T, oracle.graph_distances("mst", W).astype(np.float32))
 
 
+def test_topology_exact_ties_do_not_block(som):
+    """The blocker test of Algorithm 2 is strict.  Squared distances below are small integers (exact in float64 on
+    both sides), and a third node exactly as far from one end as the ends are apart must not remove the edge."""
+    cases = [
+        ([[1, 0, 0], [0, 1, 0], [0, 0, 1]], {(0, 1), (0, 2), (1, 2)}),            # equilateral: all lengths^2 = 2
+        ([[0, 0], [5, 0], [3, 4]], {(0, 1), (0, 2), (1, 2)}),                      # isosceles 25, 25, 20
+        ([[0, 0], [5, 0], [3, 3]], {(0, 2), (1, 2)}),                              # apex strictly inside the lune
+        ([[0], [1], [2], [3]], {(0, 1), (1, 2), (2, 3)}),                          # equally spaced on a line
+        ([[0, 0], [1, 0], [1, 1], [0, 1], [0.5, 0.5]], {(0, 4), (1, 4), (2, 4), (3, 4)}),
+        ([[0, 0], [2, 0], [1, 1], [1, -1]], {(0, 2), (0, 3), (1, 2), (1, 3)}),
+    ]
+    for nodes, edges in cases:
+        W = np.array(nodes, dtype=np.float32)
+        R = som.som_topology(dev(W), "rng").cpu().numpy()
+        p, q = np.nonzero(np.triu(R == 1))
+        assert set(zip(p.tolist(), q.tolist())) == edges, nodes
+        assert np.array_equal(R, oracle.graph_distances("rng", W).astype(np.float32))
+    # a larger tie-rich case: the vertices of a 4 x 4 x 4 integer cube plus body centres (distances 3/4 tie 24-fold)
+    g = np.stack(np.meshgrid(*[np.arange(4)] * 3, indexing="ij"), -1).reshape(-1, 3)
+    W = np.concatenate([g, g[(g < 3).all(1)] + 0.5]).astype(np.float32)
+    R = som.som_topology(dev(W), "rng").cpu().numpy()
+    assert np.array_equal(R, oracle.graph_distances("rng", W).astype(np.float32))
+
+
 def test_topology_spanning_tree_above_the_boruvka_limit(som):
     """More than 4096 nodes take the single-workgroup Prim kernel."""
     K = 4100

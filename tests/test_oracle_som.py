@@ -96,6 +96,54 @@ def test_bmu_exact_tie_takes_lowest_index():
     assert oracle.bmu_gram(np.array([[0.9]], dtype=np.float32), Wd)[0].tolist() == [1]
 
 
+def _offset_tie_case(seed):
+    """A sample x and the eight nodes x + (+-a, +-b, +-c) in shuffled order, plus one far node.  x and the offsets
+    sit on one binary grid per coordinate, so every x_d +- offset_d is again a float32 value and every direct
+    difference is exactly +-offset_d: the eight squared distances are the same sum of the same three squares, equal
+    bit for bit in any precision.  The three coordinates live at different scales (about 1000, 0.5 and 5), so
+    |w|^2 and x.w need more than 53 bits and the order of the eight float64 Gram values |w|^2 - 2 x.w is decided
+    by rounding."""
+    r = _rng(seed)
+    x = np.array([[1024 + r.integers(1, 2 ** 22) / 2.0 ** 13, r.integers(1, 2 ** 22) / 2.0 ** 22,
+                   4 + r.integers(1, 2 ** 21) / 2.0 ** 20]])
+    off = np.array([r.integers(1, 2 ** 20) / 2.0 ** 13, r.integers(1, 2 ** 21) / 2.0 ** 22, r.integers(1, 2 ** 20) / 2.0 ** 20])
+    signs = np.array([[sa, sb, sc] for sa in (1, -1) for sb in (1, -1) for sc in (1, -1)], dtype=np.float64)
+    W = np.concatenate([x + signs[r.permutation(8)] * off, x + [[400.0, 3.0, 0.0]]])
+    assert (W.astype(np.float32) == W).all() and (x.astype(np.float32) == x).all()
+    return x.astype(np.float32), W.astype(np.float32), float((off * off).sum())
+
+
+def test_bmu_gram_exact_ties_follow_the_definition_not_the_gram_order():
+    # known result: eight nodes at exactly the same distance, one far node; index 0 wins, the runner-up ties with it
+    low_index_outside_gram_pair = pair_in_descending_order = 0
+    for seed in range(40):
+        x, W, d2 = _offset_tie_case(seed)
+        Wd = W.astype(np.float64)
+        g = (Wd * Wd).sum(1) - 2.0 * (x.astype(np.float64) @ Wd.T)[0]
+        pair = np.argsort(g, kind="stable")[:2]
+        low_index_outside_gram_pair += 0 not in pair
+        pair_in_descending_order += pair[0] > pair[1]
+        for fn in (oracle.bmu, oracle.bmu_gram):
+            b, best, second = fn(x, W)
+            assert b.tolist() == [0] and best[0] == second[0] and abs(best[0] - d2) <= 1e-15 * d2, (fn.__name__, seed)
+    # the cases really are adverse for a shortlist of two: both situations occurred
+    assert low_index_outside_gram_pair > 0 and pair_in_descending_order > 0
+
+
+def test_bmu_gram_two_way_tie_in_descending_gram_order():
+    # two nodes at exactly equal distance whose Gram values put the higher index first: the lower index wins
+    hits = 0
+    for seed in range(40):
+        x, W, d2 = _offset_tie_case(seed)
+        W = W[[0, 1, 8]]
+        Wd = W.astype(np.float64)
+        g = (Wd * Wd).sum(1) - 2.0 * (x.astype(np.float64) @ Wd.T)[0]
+        hits += g[1] < g[0]
+        b, best, second = oracle.bmu_gram(x, W)
+        assert b.tolist() == [0] and best[0] == second[0] and abs(best[0] - d2) <= 1e-15 * d2
+    assert hits > 0
+
+
 def test_bmu_single_node():
     X, _, _ = _random_problem(3)
     b, best, second = oracle.bmu(X, X[:1])

@@ -99,6 +99,37 @@ def test_rng_on_a_square_and_a_line():
     assert {tuple(e) for e in oracle.mst_edges(W).tolist()} == {(0, 1), (1, 2), (2, 3)}
 
 
+def test_rng_exact_ties_do_not_block():
+    """Algorithm 2's blocker test is strict: a third node exactly as far from one end as the ends are from each
+    other blocks nothing.  All squared distances below are small integers, exact in any precision."""
+    # three mutually equidistant nodes (every squared distance is 2): all three edges
+    W = np.array([[1, 0, 0], [0, 1, 0], [0, 0, 1]], dtype=np.float32)
+    assert oracle.node_sq_distances(W)[np.triu_indices(3, 1)].tolist() == [2.0, 2.0, 2.0]
+    assert {tuple(e) for e in oracle.rng_edges(W).tolist()} == {(0, 1), (0, 2), (1, 2)}
+    # isosceles: |pq|^2 = |pr|^2 = 25, |qr|^2 = 20.  r ties with q seen from p, so (p,q) and (p,r) both stay;
+    # (q,r) is the shortest side and stays as well
+    W = np.array([[0, 0], [5, 0], [3, 4]], dtype=np.float32)
+    assert oracle.node_sq_distances(W)[np.triu_indices(3, 1)].tolist() == [25.0, 25.0, 20.0]
+    assert {tuple(e) for e in oracle.rng_edges(W).tolist()} == {(0, 1), (0, 2), (1, 2)}
+    # the same triangle with its apex pulled one unit closer to p: now r is strictly inside the lune of (p,q)
+    W = np.array([[0, 0], [5, 0], [3, 3]], dtype=np.float32)       # |pr|^2 = 18, |qr|^2 = 13 < 25
+    assert {tuple(e) for e in oracle.rng_edges(W).tolist()} == {(0, 2), (1, 2)}
+    # equally spaced collinear nodes 0, 1, 2, 3: consecutive pairs only (the middle nodes block strictly), and a
+    # unit square with its centre: centre-corner edges (1/2) are shorter than the sides (1), the centre is strictly
+    # inside every side's lune (max = 1/2 < 1), so only the four spokes stay
+    W = np.array([[0.0], [1.0], [2.0], [3.0]], dtype=np.float32)
+    assert {tuple(e) for e in oracle.rng_edges(W).tolist()} == {(0, 1), (1, 2), (2, 3)}
+    W = np.array([[0, 0], [1, 0], [1, 1], [0, 1], [0.5, 0.5]], dtype=np.float32)
+    assert {tuple(e) for e in oracle.rng_edges(W).tolist()} == {(0, 4), (1, 4), (2, 4), (3, 4)}
+    # regular unit square alone: the diagonal's ends see the other corners at exactly the side length (1 < 2:
+    # blocked), and each side sees the far corners at distances (1, 2): max 2 > 1, not blocked
+    W = np.array([[0, 0], [2, 0], [1, 1], [1, -1]], dtype=np.float32)   # a square standing on a corner, side^2 = 2
+    assert {tuple(e) for e in oracle.rng_edges(W).tolist()} == {(0, 2), (0, 3), (1, 2), (1, 3)}
+    # hop counts of the tie triangle: everything one hop apart
+    G = oracle.graph_distances("rng", W=np.array([[1, 0, 0], [0, 1, 0], [0, 0, 1]], dtype=np.float32))
+    assert G.tolist() == [[0, 1, 1], [1, 0, 1], [1, 1, 0]]
+
+
 def test_graph_distances_dispatch():
     W = _nodes(20, K=16)
     assert (oracle.graph_distances("rect", lattice=(4, 4)) == oracle.rect_lattice_distances(4, 4)).all()
