@@ -80,12 +80,23 @@ int som_profile(som_ctx* ctx, int enable);
 int som_profile_read(som_ctx* ctx, float* ms, int32_t capacity, int32_t* count);
 
 /*
+ * Measurement support (not an operation of the paper): the accumulation behaviour of the bf16 matrix pipe, on which
+ * the rounding bound of the default search rests.  For each of n problems one v_mfma_f32_32x32x16_bf16 is executed:
+ *     Dout[t][i][j] = C[t][i][j] + sum_{k < 16} A[t][i][k] * Bt[t][j][k]
+ *   A, Bt [device] uint16[n][32][16]: bf16 bit patterns (Bt holds B transposed), 16-byte aligned
+ *   C, Dout [device] float[n][32][32]
+ * The products are exact in float32; how the pipe adds the seventeen terms is what a caller measures by comparing
+ * Dout with the exact sum.  Asynchronous on the context's stream; n <= 2^24.
+ */
+int som_matrix_pipe_probe(som_ctx* ctx, const uint16_t* A, const uint16_t* Bt, const float* C, float* Dout, int64_t n);
+
+/*
  * Best-matching-unit search (Section 3.3.1, definition of b(x)).
  *   X [device] N x D, ldx;  idx [device] m row numbers or NULL;  W [device] K x D
  *   bmu [device] int32[m], required: bmu[i] = b(x_{idx[i]})
  *   d2  [device] float[m] or NULL: squared distance to the BMU, recomputed by direct differences
  *   qe  [device] double[2] or NULL, OVERWRITTEN with { sum_i sqrt(d2_i), sum_i d2_i }  (the quantisation
- *       error of Section 4.2 is qe[0] / m)
+ *       error of Section 4.1.2 is qe[0] / m)
  * The N x K distance matrix is never formed in memory.  m == 0 is allowed (qe becomes {0, 0}).
  */
 int som_bmu(som_ctx* ctx, const float* X, int64_t N, int32_t D, int64_t ldx,

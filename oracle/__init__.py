@@ -9,5 +9,5 @@ from .som import (  # noqa: F401
 )
 from .topology import (  # noqa: F401
     rect_lattice_distances, hex_lattice_positions, hex_lattice_distances, node_sq_distances,
-    mst_edges, rng_edges, hop_distances, graph_distances,
+    mst_edges, rng_edges, rng_blocked, hop_distances, graph_distances,
 )

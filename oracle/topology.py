@@ -37,11 +37,17 @@ def hex_lattice_distances(n_rows: int, n_cols: int) -> np.ndarray:
     return np.sqrt((diff * diff).sum(axis=2))
 
 
-def node_sq_distances(W: np.ndarray) -> np.ndarray:
-    """Pairwise squared distances between node weight vectors, by direct differences."""
+def node_sq_distances(W: np.ndarray, block: int = 256) -> np.ndarray:
+    """Pairwise squared distances between node weight vectors, by direct differences.
+
+    Rows are taken in blocks only to bound the size of the temporary; every entry is the same sum either way."""
     W = np.asarray(W, dtype=np.float64)
-    diff = W[:, None, :] - W[None, :, :]
-    return np.einsum("pqd,pqd->pq", diff, diff)
+    K = W.shape[0]
+    d2 = np.empty((K, K), dtype=np.float64)
+    for lo in range(0, K, block):
+        diff = W[lo:lo + block, None, :] - W[None, :, :]
+        d2[lo:lo + block] = np.einsum("pqd,pqd->pq", diff, diff)
+    return d2
 
 
 def mst_edges(W: np.ndarray) -> np.ndarray:
@@ -73,6 +79,19 @@ def mst_edges(W: np.ndarray) -> np.ndarray:
     return np.asarray(edges, dtype=np.int64).reshape(-1, 2)
 
 
+def rng_blocked(d2: np.ndarray, p: int) -> np.ndarray:
+    """Blocker test of Algorithm 2 (steps 7-9) for node p against every q at once, on squared distances d2.
+
+    blocked[q] is True when some third node r (r != p, r != q) is strictly closer to both ends than they are to each
+    other:  max(d(p, r), d(q, r)) < d(p, q).
+    """
+    K = d2.shape[0]
+    m = np.maximum(d2[p][None, :], d2)          # m[q, r] = max(d2[p, r], d2[q, r])
+    m[:, p] = np.inf
+    m[np.arange(K), np.arange(K)] = np.inf      # r must differ from q (and from p)
+    return m.min(axis=1) < d2[p]
+
+
 def rng_edges(W: np.ndarray) -> np.ndarray:
     """Relative neighbourhood graph over the node weights (Algorithm 2, steps 7-9).
 
@@ -83,11 +102,7 @@ def rng_edges(W: np.ndarray) -> np.ndarray:
     K = d2.shape[0]
     edges = []
     for p in range(K):
-        # lune test for all q > p at once: blocked[q] = any_r max(d2[p, r], d2[q, r]) < d2[p, q]
-        m = np.maximum(d2[p][None, :], d2)          # m[q, r] = max(d2[p, r], d2[q, r])
-        m[:, p] = np.inf
-        m[np.arange(K), np.arange(K)] = np.inf      # r must differ from q (and from p)
-        blocked = m.min(axis=1) < d2[p]
+        blocked = rng_blocked(d2, p)
         for q in range(p + 1, K):
             if not blocked[q]:
                 edges.append((p, q))

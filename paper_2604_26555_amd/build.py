@@ -10,8 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libsom.so")
-PROBE = os.path.join(HERE, "probe_matrix_pipe")      # stand-alone measurement program, not loaded by anything
-SOURCES = ["som_api.hip", "som_bmu.hip", "som_accumulate.hip", "som_accumulate_mfma.hip", "som_accumulate_f64.hip", "som_update.hip", "som_topology.hip"]
+SOURCES = ["som_api.hip", "som_bmu.hip", "som_accumulate.hip", "som_accumulate_mfma.hip", "som_accumulate_f64.hip", "som_update.hip", "som_topology.hip", "som_probe.hip"]
 
 FLAGS = [
     "-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950",
@@ -49,12 +48,6 @@ def build(verbose: bool = True, extra_flags=()) -> str:
     with ThreadPoolExecutor(max_workers=4) as pool:
         objs = list(pool.map(compile_one, SOURCES))
     cmd = [cc, "-shared", "-fPIC", "--offload-arch=gfx950", *objs, "-o", LIB]
-    if verbose:
-        print(" ".join(cmd), flush=True)
-    subprocess.run(cmd, check=True)
-    # the probe of the matrix pipe's accumulation error and co-issue (see its header); an executable of its own
-    cmd = [cc, "-O2", "-std=c++17", "--offload-arch=gfx950", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-           "-Wno-unused-result", os.path.join(CSRC, "probe_matrix_pipe.hip"), "-o", PROBE]
     if verbose:
         print(" ".join(cmd), flush=True)
     subprocess.run(cmd, check=True)

@@ -30,6 +30,7 @@ EXPORTS = [
     "som_create", "som_destroy", "som_strerror", "som_last_error", "som_sync", "som_bmu", "som_accumulate",
     "som_neighborhood_update", "som_epoch", "som_epoch_host", "som_profile", "som_profile_read",
     "som_set_update_rule", "som_topology", "som_set_safeguard", "som_set_reproducible", "som_set_search",
+    "som_matrix_pipe_probe",
 ]
 
 
@@ -89,6 +90,8 @@ def load_library(path: str = LIB_PATH) -> C.CDLL:
     lib.som_set_safeguard.restype = C.c_int
     lib.som_topology.argtypes = [vp, vp, i32, i32, C.c_int, vp]
     lib.som_topology.restype = C.c_int
+    lib.som_matrix_pipe_probe.argtypes = [vp, vp, vp, vp, vp, i64]
+    lib.som_matrix_pipe_probe.restype = C.c_int
     lib.som_epoch.argtypes = [vp, vp, i64, i32, i64, vp, i64, vp, i32, vp, f64, C.c_int, f64, C.POINTER(SomStats)]
     lib.som_epoch.restype = C.c_int
     lib.som_epoch_host.argtypes = [vp, vp, i64, i32, i64, C.c_int, vp, i32, vp, f64, C.c_int, f64,
@@ -207,6 +210,21 @@ class Som:
         count = C.c_int32(0)
         self._check(self.lib.som_profile_read(self._h, buf, capacity, C.byref(count)), "som_profile_read")
         return [buf[i] for i in range(min(capacity, count.value))]
+
+    def som_matrix_pipe_probe(self, A, Bt, Cm, Dout=None):
+        """One bf16 MFMA per problem: Dout = Cm + A @ Bt^T.  A, Bt: (n, 32, 16) bf16; Cm: (n, 32, 32) float32."""
+        n = A.shape[0]
+        if A.shape != (n, 32, 16) or Bt.shape != (n, 32, 16) or Cm.shape != (n, 32, 32) or not (
+                A.is_contiguous() and Bt.is_contiguous() and Cm.is_contiguous()):
+            raise ValueError("shapes: A, Bt (n, 32, 16) bf16, C (n, 32, 32) float32, all contiguous")
+        if Dout is None:
+            Dout = torch.empty_like(Cm)
+        rc = self.lib.som_matrix_pipe_probe(self._h, _ptr(A, torch.bfloat16, "A", self.device),
+                                            _ptr(Bt, torch.bfloat16, "Bt", self.device),
+                                            _ptr(Cm, torch.float32, "C", self.device),
+                                            _ptr(Dout, torch.float32, "Dout", self.device), n)
+        self._check(rc, "som_matrix_pipe_probe")
+        return Dout
 
     # ------------------------------------------------------------------ stage 1
     def som_bmu(self, X, W, idx=None, bmu=None, d2=None, qe=None):

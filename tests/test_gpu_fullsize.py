@@ -95,6 +95,9 @@ def test_full_size_accumulate_properties_and_epoch(som, cfg1):
     mask = oracle.near_tie_mask(best, second)
     assert ((b_np == ref_b) | mask).all(), f"{((b_np != ref_b) & ~mask).sum()} BMU mismatches outside the near-tie mask"
     b_use = np.where(mask, b_np, ref_b)
+    flips = int((b_np != ref_b).sum())
+    print(f"full size: {flips} of {wl.n} samples differ from the oracle's unit inside the mask ({int(mask.sum())} masked)", flush=True)
+    assert flips <= 2e-4 * wl.n            # the oracle follows the GPU inside the mask only; that licence is bounded
     G_or = oracle.graph_distances(wl.topology, lattice=wl.lattice)
     ref = oracle.epoch_grouped(X, None, W, G_or, float(sig[5]), b=b_use)
     st = som.som_epoch(Xd, Wd, G, float(sig[5]))
@@ -167,3 +170,95 @@ def test_bmu_wide_rows_in_several_passes(som):
     same = got == b
     np.testing.assert_allclose(d2[rows_d].cpu().numpy()[same], best[same], rtol=1e-4, atol=1e-12)
     assert int(b_gpu.min()) >= 0 and int(b_gpu.max()) < K
+
+
+# ------------------------------------------------------------------------------------------- top of the grid axis
+# Supplementary Table S3 takes the map up to 64 x 64 = 4096 nodes; the three tests below put every stage at that size
+# against the oracle.
+
+def test_update_at_4096_nodes(som):
+    K, D = 4096, 50
+    rng = np.random.default_rng(4096)
+    W = rng.normal(size=(K, D)).astype(np.float32)
+    n = rng.integers(0, 400, size=K).astype(np.int64)
+    n[rng.random(K) < 0.3] = 0
+    S = rng.normal(size=(K, D)) * n[:, None]
+    G = oracle.hex_lattice_distances(64, 64).astype(np.float32)
+    for sigma in (32.0, 2.0, 0.4):
+        Wd = torch.from_numpy(W).cuda()
+        ng = torch.zeros(1, dtype=torch.int32, device="cuda")
+        som.som_neighborhood_update(torch.from_numpy(S).cuda(), torch.from_numpy(n).cuda(), torch.from_numpy(G).cuda(), sigma, Wd,
+                                    n_guarded=ng)
+        W_or, guarded, den = oracle.neighborhood_update(S, n, G.astype(np.float64), sigma, W)
+        keep = ~((den > oracle.DEFAULT_EPS_H / 4) & (den < oracle.DEFAULT_EPS_H * 4))
+        scale = np.maximum(np.abs(W_or).max(axis=1, keepdims=True), 1e-30)
+        err = np.abs(Wd.cpu().numpy() - W_or) / scale
+        print(f"update K=4096 sigma={sigma}: max relative error {err[keep].max():.2e}, guarded {int(guarded.sum())}", flush=True)
+        assert (err[keep] <= 1e-4).all()
+        assert abs(int(ng.item()) - int(guarded.sum())) <= int((~keep).sum())
+
+
+@pytest.mark.parametrize("search", ["auto", "float32"])
+def test_epoch_at_4096_nodes_teacher_forced(som, search):
+    """64 x 64 hexagonal map, 2 * 10^5 x 50 samples: units, distances, weights and counters of two epochs (large and small
+    radius) against the oracle, each started from the same weights."""
+    wl = make_workload("cfg1", n=200_000, k=4096, lattice=(64, 64))
+    X = wl.data().rows(0, wl.n)
+    W = X[draw_initial_rows(wl.seed, wl.n, wl.k)].copy()
+    G_or = oracle.hex_lattice_distances(64, 64)
+    Xd, Gd = torch.from_numpy(X).cuda(), torch.from_numpy(G_or.astype(np.float32)).cuda()
+    som.som_set_search(search)
+    try:
+        for sigma in (32.0, 1.5):
+            Wd = torch.from_numpy(W).cuda()
+            d2 = torch.empty(wl.n, dtype=torch.float32, device="cuda")
+            b_gpu, _, _ = som.som_bmu(Xd, Wd, d2=d2)
+            b_gpu = b_gpu.cpu().numpy()
+            b, best, second = oracle.bmu_gram(X, W, block=16384)
+            mask = oracle.near_tie_mask(best, second)
+            bad = (b_gpu != b) & ~mask
+            assert not bad.any(), f"{int(bad.sum())} units differ outside the near-tie mask"
+            flips = int((b_gpu != b).sum())
+            print(f"K=4096 {search} sigma={sigma}: {flips} in-mask differences, {int(mask.sum())} masked of {wl.n}", flush=True)
+            assert flips <= 2e-4 * wl.n
+            same = b_gpu == b
+            np.testing.assert_allclose(d2.cpu().numpy()[same], best[same], rtol=1e-4, atol=1e-12)
+            ref = oracle.epoch_grouped(X, None, W, G_or, sigma, b=np.where(mask, b_gpu, b))
+            st = som.som_epoch(Xd, Wd, Gd, sigma)
+            keep = ~((ref["den"] > oracle.DEFAULT_EPS_H / 4) & (ref["den"] < oracle.DEFAULT_EPS_H * 4))
+            scale = np.maximum(np.abs(ref["W"]).max(axis=1, keepdims=True), 1e-30)
+            err = np.abs(Wd.cpu().numpy() - ref["W"]) / scale
+            assert (err[keep] <= 1e-4).all(), f"max relative weight error {err[keep].max():.2e}"
+            qe = oracle.quantization_error(best)
+            assert abs(st.qe - qe) <= 1e-4 * qe and st.m == wl.n
+            assert st.n_empty == int((ref["n"] == 0).sum())
+            W = ref["W"].astype(np.float32)          # the second epoch runs on a spread-out map
+    finally:
+        som.som_set_search("auto")
+
+
+def test_relative_neighbourhood_graph_at_4096_nodes(som):
+    """K = 4096, D = 50.  The oracle's blocker test decides the complete neighbour row of 96 sampled nodes (among them
+    the first and the last); the whole graph must be symmetric, contain the oracle's spanning tree, and its hop counts
+    from sampled sources must be the unweighted shortest paths of its own edges (the routine the oracle's hop counts
+    are pinned to)."""
+    from scipy.sparse import csr_matrix
+    from scipy.sparse.csgraph import shortest_path
+    from synth import GaussianMixture
+    K, D = 4096, 50
+    W = GaussianMixture(4096, D, 12).rows(0, K)
+    R = som.som_topology(torch.from_numpy(W).cuda(), "rng").cpu().numpy()
+    adj = R == 1
+    assert np.array_equal(R, R.T) and (R.diagonal() == 0).all() and np.isfinite(R).all()
+    d2 = oracle.node_sq_distances(W)
+    rows = np.unique(np.concatenate([np.random.default_rng(1).choice(K, 94, replace=False), [0, K - 1]]))
+    for p in rows:
+        expect = ~oracle.rng_blocked(d2, int(p))
+        expect[p] = False
+        assert np.array_equal(adj[p], expect), f"neighbour row of node {p} differs from the blocker test"
+    e = oracle.mst_edges(W)
+    assert adj[e[:, 0], e[:, 1]].all()                       # the graph contains the minimum spanning tree
+    src = [0, 777, 2048, K - 1]
+    hops = shortest_path(csr_matrix(adj.astype(np.int8)), unweighted=True, indices=src)
+    assert np.array_equal(R[src], hops.astype(np.float32))
+    print(f"RNG K=4096: {int(adj.sum()) // 2} edges, largest hop count {int(R.max())}", flush=True)
