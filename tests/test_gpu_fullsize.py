@@ -30,6 +30,21 @@ def cfg1():
     return wl, X, W0
 
 
+def bounded_flips(b_gpu, b, mask, best, second, D, what):
+    """The oracle's update follows the GPU's unit inside the 1e-5 near-tie mask; that licence is bounded.  The library
+    decides near-ties by float32 direct differences ((D + 3) 2^-24 relative error per squared distance), so it may
+    differ from the float64 oracle only where the best two distances are closer than (D + 4) 2^-23 relative, and the
+    share of such samples stays below 5e-3."""
+    flip = b_gpu != b
+    assert not (flip & ~mask).any()
+    flips = int(flip.sum())
+    print(f"{what}: {flips} of {len(b)} samples differ from the oracle's unit inside the mask ({int(mask.sum())} masked), "
+          f"share {flips / len(b):.2e}", flush=True)
+    gap = (second[flip] - best[flip]) / np.maximum(second[flip], np.finfo(np.float64).tiny)
+    assert (gap <= (D + 4) * 2.0 ** -23).all(), f"{what}: a differing unit at relative gap {gap.max():.2e}"
+    assert flips <= 5e-3 * len(b)
+
+
 def trained(som, wl, Xd, W0, epochs):
     """Weights after a few GPU epochs (a spread-out map rather than the initial sample rows)."""
     from paper_2604_26555_amd import topology
@@ -95,9 +110,7 @@ def test_full_size_accumulate_properties_and_epoch(som, cfg1):
     mask = oracle.near_tie_mask(best, second)
     assert ((b_np == ref_b) | mask).all(), f"{((b_np != ref_b) & ~mask).sum()} BMU mismatches outside the near-tie mask"
     b_use = np.where(mask, b_np, ref_b)
-    flips = int((b_np != ref_b).sum())
-    print(f"full size: {flips} of {wl.n} samples differ from the oracle's unit inside the mask ({int(mask.sum())} masked)", flush=True)
-    assert flips <= 2e-4 * wl.n            # the oracle follows the GPU inside the mask only; that licence is bounded
+    bounded_flips(b_np, ref_b, mask, best, second, wl.d, "full size")
     G_or = oracle.graph_distances(wl.topology, lattice=wl.lattice)
     ref = oracle.epoch_grouped(X, None, W, G_or, float(sig[5]), b=b_use)
     st = som.som_epoch(Xd, Wd, G, float(sig[5]))
@@ -218,9 +231,7 @@ def test_epoch_at_4096_nodes_teacher_forced(som, search):
             mask = oracle.near_tie_mask(best, second)
             bad = (b_gpu != b) & ~mask
             assert not bad.any(), f"{int(bad.sum())} units differ outside the near-tie mask"
-            flips = int((b_gpu != b).sum())
-            print(f"K=4096 {search} sigma={sigma}: {flips} in-mask differences, {int(mask.sum())} masked of {wl.n}", flush=True)
-            assert flips <= 2e-4 * wl.n
+            bounded_flips(b_gpu, b, mask, best, second, wl.d, f"K=4096 {search} sigma={sigma}")
             same = b_gpu == b
             np.testing.assert_allclose(d2.cpu().numpy()[same], best[same], rtol=1e-4, atol=1e-12)
             ref = oracle.epoch_grouped(X, None, W, G_or, sigma, b=np.where(mask, b_gpu, b))

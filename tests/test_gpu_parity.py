@@ -222,7 +222,11 @@ def test_bmu_at_the_edge_of_the_recheck_band(som, search, regime):
     xn = np.linalg.norm(X - c, axis=1)
     wmax = np.linalg.norm(W - c, axis=1).max()
     rel = {"auto": 5.1e-5, "float32": 6.7e-6}[search]
-    ratio = 0.5 * (second - best) / (rel * (xn * wmax + 0.5 * wmax * wmax))
+    magnitude = xn * wmax + 0.5 * wmax * wmax
+    if search == "auto":        # half of this search's bound is taken with the winner's own norm instead of the largest
+        wb = np.linalg.norm(W[b] - c, axis=1)
+        magnitude = 0.5 * (magnitude + xn * wb + 0.5 * wb * wb)
+    ratio = 0.5 * (second - best) / (rel * magnitude)
     hist = [int(((ratio >= lo) & (ratio < hi) & ~mask).sum()) for lo, hi in ((0.25, 0.5), (0.5, 1), (1, 2), (2, 4))]
     gaps = ((second - best) / second)[(ratio >= 0.25) & (ratio < 4)]
     print(f"{regime}/{search}: samples at 0.25-0.5-1-2-4 x bound: {hist}; their best-two gaps {gaps.min():.1e} ... {gaps.max():.1e} "
@@ -662,19 +666,23 @@ def test_topology_feeds_an_epoch(som):
 
 
 # ------------------------------------------------------------------------------------------- whole epochs
-FLIP_CEILING = 2e-4      # share of the presented samples that may differ from the oracle's unit inside the near-tie mask
+FLIP_CEILING = 5e-3      # share of the presented samples that may differ from the oracle's unit inside the near-tie mask
 
 
-def assert_few_flips(b_gpu, b, mask, what):
+def assert_few_flips(b_gpu, b, mask, best, second, D, what):
     """Inside the 1e-5 mask either unit is acceptable, and the oracle's update then follows the GPU's choice.  That
-    licence is bounded: float32 direct differences can reorder two float64 distances only when they are closer than
-    about D * 2^-23 relative, a small part of the mask, so the share of samples that differ stays far below the
-    ceiling; a search that flipped its way through the mask would not."""
-    flips = int((b_gpu != b).sum())
-    assert not ((b_gpu != b) & ~mask).any()
-    m = len(b)
-    print(f"{what}: {flips} of {m} samples differ from the oracle's unit inside the mask ({int(mask.sum())} masked)", flush=True)
-    assert flips <= max(3, FLIP_CEILING * m), f"{what}: {flips} in-mask flips of {m} samples"
+    licence is bounded twice.  Per sample: the library decides every near-tie by float32 direct differences, whose
+    squared distances carry at most (D + 3) 2^-24 relative error each, so it may differ from the float64 oracle only
+    where the oracle's best two distances are closer than (D + 4) 2^-23 relative - a search that flipped its way
+    through the rest of the mask fails here.  Overall: the share of such samples stays below FLIP_CEILING."""
+    flip = b_gpu != b
+    assert not (flip & ~mask).any()
+    m, flips = len(b), int(flip.sum())
+    print(f"{what}: {flips} of {m} samples differ from the oracle's unit inside the mask ({int(mask.sum())} masked), "
+          f"share {flips / max(m, 1):.2e}", flush=True)
+    gap = (second[flip] - best[flip]) / np.maximum(second[flip], np.finfo(np.float64).tiny)
+    assert (gap <= (D + 4) * 2.0 ** -23).all(), f"{what}: a differing unit at relative gap {gap.max():.2e}"
+    assert flips <= max(3, FLIP_CEILING * m), f"{what}: {flips} in-mask differences of {m} samples"
 
 
 def run_teacher_forced(som, wl, n_rows, epochs, idx_fn=None):
@@ -691,9 +699,10 @@ def run_teacher_forced(som, wl, n_rows, epochs, idx_fn=None):
         b_gpu, _, _ = som.som_bmu(Xd, dev(W32), idx=idx_d)
         b_gpu = b_gpu.cpu().numpy()
         b, best, mask = check_bmu(b_gpu, None, X, W32, idx)
+        second = oracle.bmu(X if idx is None else X[idx.astype(np.int64)], W32)[2]
         # inside the near-tie mask either index is a valid BMU: the oracle's update follows the GPU's choice there
         b_use = np.where(mask, b_gpu, b)
-        assert_few_flips(b_gpu, b, mask, f"{wl.name} epoch {e}")
+        assert_few_flips(b_gpu, b, mask, best, second, X.shape[1], f"{wl.name} epoch {e}")
         ref = oracle.epoch_grouped(X, idx, W32, G.astype(np.float64), sig[e], b=b_use)
         Wd = dev(W32)
         st = som.som_epoch(Xd, Wd, dev(G), sig[e], idx=idx_d)
