@@ -127,6 +127,21 @@ int som_neighborhood_update(som_ctx* ctx, const double* S, const uint64_t* n, co
                             float* W, int32_t* n_guarded);
 
 /*
+ * som_neighborhood_update for callers that cannot allocate device memory: code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc.  Same arguments, same kernels and same results as som_neighborhood_update,
+ * but the split-k partial sums (and the exponent shifts of SOM_SAFEGUARD_SHIFT) go to a fixed device array of 8.25 MiB
+ * that the library holds on each GPU it runs on until the process ends, instead of a workspace grown on demand; the
+ * call makes no hipMalloc / hipFree and enqueues no memset (counters are cleared by a small kernel).
+ * Limits: D <= 63, K <= 32768 and K * (D + 1) <= 65536 (for instance 1024 nodes x 63 features, 4096 x 15); larger
+ * shapes return SOM_EINVAL with the limits in som_last_error and touch nothing.
+ * Every call on a GPU, from whatever context or stream, shares that GPU's array: calls that overlap in time on one
+ * GPU race and give wrong results; calls ordered on one stream (or otherwise serialised) are safe.
+ */
+int som_neighborhood_update_static(som_ctx* ctx, const double* S, const uint64_t* n, const float* G,
+                                   int32_t K, int32_t D, double sigma, int kernel, double eps_h,
+                                   float* W, int32_t* n_guarded);
+
+/*
  * General update rule of the paragraph after Eq. 4: learning rate eta (the eta_t inside U_j of Eq. 3) and
  * optional momentum.  With   u_j = eta (Num_j / Den_j - w_j)   (= U_j / H_j; 0 where Den_j < eps_h)   every
  * later update on this context (som_neighborhood_update, som_epoch, som_epoch_host) applies

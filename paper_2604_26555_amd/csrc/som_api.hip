@@ -123,6 +123,7 @@ int som_create(som_ctx** out, int device, void* hip_stream)
         ok = ok && hipEventCreateWithFlags(&c->ev_consumed[i], hipEventDisableTiming) == hipSuccess;
     }
     for (int i = 0; i < 4 && ok; ++i) ok = ok && hipEventCreate(&c->ev_t[i]) == hipSuccess;
+    ok = ok && update_static_init(c) == SOM_OK;
     if (!ok) {
         (void)hipGetLastError();
         som_destroy(c);
@@ -288,6 +289,24 @@ int som_neighborhood_update(som_ctx* ctx, const double* S, const uint64_t* n, co
     if (eps_h <= 0.0) eps_h = 1e-30;
     if (int rc = launch_fill_zero(ctx, ctx->small, 64)) return rc;
     if (int rc = update_run(ctx, S, (const unsigned long long*)n, G, K, D, sigma, eps_h, W, ctx->small)) return rc;
+    if (n_guarded)
+        return check_hip(ctx, hipMemcpyAsync(n_guarded, ctx->small, sizeof(int32_t), hipMemcpyDeviceToDevice, ctx->stream),
+                         "copying the guarded-node count");
+    return SOM_OK;
+}
+
+int som_neighborhood_update_static(som_ctx* ctx, const double* S, const uint64_t* n, const float* G, int32_t K, int32_t D,
+                                   double sigma, int kernel, double eps_h, float* W, int32_t* n_guarded)
+{
+    if (!ctx) return SOM_EINVAL;
+    if (!S || !n || !W) return fail(ctx, SOM_EINVAL, "null S, n or W");
+    if (int rc = update_checks(ctx, G, K, D, sigma, kernel)) return rc;
+    if (!device_readable(S) || !device_readable(n) || !device_readable(G) || !device_readable(W))
+        return fail(ctx, SOM_EINVAL, "S, n, G and W must be device-accessible memory");
+    if (int rc = check_hip(ctx, hipSetDevice(ctx->device), "hipSetDevice")) return rc;
+    if (eps_h <= 0.0) eps_h = 1e-30;
+    if (int rc = launch_fill_zero(ctx, ctx->small, 64)) return rc;
+    if (int rc = update_static_run(ctx, S, (const unsigned long long*)n, G, K, D, sigma, eps_h, W, ctx->small)) return rc;
     if (n_guarded)
         return check_hip(ctx, hipMemcpyAsync(n_guarded, ctx->small, sizeof(int32_t), hipMemcpyDeviceToDevice, ctx->stream),
                          "copying the guarded-node count");

@@ -63,6 +63,9 @@ struct BmuArgs {
 };
 
 constexpr int kQeSlots = 256;
+constexpr int kMaxDevices = 64;                 // devices the per-device tables hold
+constexpr int kUpdateStaticCells = 65536;       // som_neighborhood_update_static: K * (D + 1) at most
+constexpr int kUpdateStaticNodes = 32768;       // and K at most
 constexpr int kCandSlots = 8;         // 16-bit places per (list entry, half-wavefront): up to seven node ids and a count
 
 } // namespace som
@@ -89,6 +92,7 @@ struct som_ctx {
     size_t acc_bytes = 0;
     void* upd_blob = nullptr;      // influence matrix + split-k partials of the update
     size_t upd_bytes = 0;
+    double* upd_static = nullptr;  // this device's fixed update workspace (som_neighborhood_update_static)
     int safeguard = 0;             // SOM_SAFEGUARD_*
     int reproducible = 0;          // prefer the fixed-order accumulation kernel
     int search = 0;                // SOM_SEARCH_*
@@ -135,5 +139,8 @@ int accumulate_f64_run(som_ctx* ctx, const float* X, int32_t D, int64_t ldx, con
                         const int32_t* bmu, int32_t K, double* S, unsigned long long* n, bool zero_first);
 int update_run(som_ctx* ctx, const double* S, const unsigned long long* n, const float* G, int32_t K,
                int32_t D, double sigma, double eps_h, float* W, int32_t* small);
+int update_static_init(som_ctx* ctx);
+int update_static_run(som_ctx* ctx, const double* S, const unsigned long long* n, const float* G, int32_t K,
+                      int32_t D, double sigma, double eps_h, float* W, int32_t* small);
 
 } // namespace som

@@ -13,6 +13,8 @@
 
 #include <math.h>
 
+#include <mutex>
+
 namespace som {
 
 typedef double doublex4 __attribute__((ext_vector_type(4)));
@@ -154,6 +156,38 @@ __global__ void __launch_bounds__(256) finish_kernel(const double* __restrict__ 
     }
 }
 
+// the three launches of one update on the given workspaces: H [K*K] (only when D + 1 > 64), part [kSplitK*K*(D+1)],
+// shift [K] (only with the shifted-exponent safeguard)
+static int update_launch(som_ctx* ctx, double* H, double* part, double* shift_ws, const double* S,
+                         const unsigned long long* n, const float* G, int32_t K, int32_t D, double sigma, double eps_h,
+                         float* W, int32_t* small)
+{
+    const size_t h_elems = (size_t)K * K;
+    const double inv2s2 = 1.0 / (2.0 * sigma * sigma);
+    const dim3 grid((K + 15) / 16, (D + 1 + 63) / 64, kSplitK / 4);
+    double* shift = nullptr;
+    if (ctx->safeguard == SOM_SAFEGUARD_SHIFT) {
+        shift = shift_ws;
+        hipLaunchKernelGGL(shift_kernel, dim3((K + 255) / 256), dim3(256), 0, ctx->stream, G, n, K, shift);
+        if (int rc = check_hip(ctx, hipGetLastError(), "exponent shift launch")) return rc;
+    }
+    if (grid.y == 1) {
+        hipLaunchKernelGGL(contract_kernel<true>, grid, dim3(256), 0, ctx->stream, G, (const double*)nullptr, inv2s2,
+                           (const double*)shift, S, n, K, D, part);
+    } else {
+        hipLaunchKernelGGL(influence_kernel, dim3((unsigned)((h_elems + 255) / 256)), dim3(256), 0, ctx->stream, G, K, inv2s2,
+                           (const double*)shift, n, H);
+        if (int rc = check_hip(ctx, hipGetLastError(), "influence kernel launch")) return rc;
+        hipLaunchKernelGGL(contract_kernel<false>, grid, dim3(256), 0, ctx->stream, G, (const double*)H, inv2s2,
+                           (const double*)nullptr, S, n, K, D, part);
+    }
+    if (int rc = check_hip(ctx, hipGetLastError(), "contraction kernel launch")) return rc;
+    const bool plain = ctx->eta == 1.0 && ctx->mu == 0.0;
+    hipLaunchKernelGGL(finish_kernel, dim3((K * D + 255) / 256), dim3(256), 0, ctx->stream, part, n, K, D, eps_h, plain,
+                       ctx->eta, ctx->mu, ctx->velocity, W, small);
+    return check_hip(ctx, hipGetLastError(), "update finish launch");
+}
+
 int update_run(som_ctx* ctx, const double* S, const unsigned long long* n, const float* G, int32_t K, int32_t D,
                double sigma, double eps_h, float* W, int32_t* small)
 {
@@ -174,29 +208,45 @@ int update_run(som_ctx* ctx, const double* S, const unsigned long long* n, const
     }
     double* H = (double*)ctx->upd_blob;
     double* part = H + h_elems;
-    const double inv2s2 = 1.0 / (2.0 * sigma * sigma);
-    const dim3 grid((K + 15) / 16, (D + 1 + 63) / 64, kSplitK / 4);
-    double* shift = nullptr;
-    if (ctx->safeguard == SOM_SAFEGUARD_SHIFT) {
-        shift = part + (size_t)kSplitK * K * (D + 1);
-        hipLaunchKernelGGL(shift_kernel, dim3((K + 255) / 256), dim3(256), 0, ctx->stream, G, n, K, shift);
-        if (int rc = check_hip(ctx, hipGetLastError(), "exponent shift launch")) return rc;
+    return update_launch(ctx, H, part, part + (size_t)kSplitK * K * (D + 1), S, n, G, K, D, sigma, eps_h, W, small);
+}
+
+// ---------------------------------------------------------------------------------------------------------
+// The same update for callers that cannot allocate (som_neighborhood_update_static): the split-k partials and the
+// exponent shifts live in a fixed device array instead of a grown workspace.  One array per GPU, shared by every
+// call on that GPU and holding the last call's contents; every cell a call reads it has written first (the
+// contraction writes all kSplitK partials of every node and column, the shift kernel every node), so nothing needs
+// clearing.  Host code never uses the array's name as an address: the device address is looked up once per device.
+// ---------------------------------------------------------------------------------------------------------
+static __device__ __align__(256) double scratch[(size_t)kSplitK * kUpdateStaticCells + kUpdateStaticNodes];
+
+static std::mutex g_scratch_mutex;
+static double* g_scratch_ptr[kMaxDevices] = {};     // per device: its own copy of the array, at its own address
+
+// called by som_create with the context's device current
+int update_static_init(som_ctx* ctx)
+{
+    if (ctx->device < 0 || ctx->device >= kMaxDevices) return SOM_OK;   // the static entry point reports it when used
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[ctx->device]) {
+        void* p = nullptr;
+        if (int rc = check_hip(ctx, hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)), "looking up the static update workspace")) return rc;
+        g_scratch_ptr[ctx->device] = (double*)p;
     }
-    if (grid.y == 1) {
-        hipLaunchKernelGGL(contract_kernel<true>, grid, dim3(256), 0, ctx->stream, G, (const double*)nullptr, inv2s2,
-                           (const double*)shift, S, n, K, D, part);
-    } else {
-        hipLaunchKernelGGL(influence_kernel, dim3((unsigned)((h_elems + 255) / 256)), dim3(256), 0, ctx->stream, G, K, inv2s2,
-                           (const double*)shift, n, H);
-        if (int rc = check_hip(ctx, hipGetLastError(), "influence kernel launch")) return rc;
-        hipLaunchKernelGGL(contract_kernel<false>, grid, dim3(256), 0, ctx->stream, G, (const double*)H, inv2s2,
-                           (const double*)nullptr, S, n, K, D, part);
-    }
-    if (int rc = check_hip(ctx, hipGetLastError(), "contraction kernel launch")) return rc;
-    const bool plain = ctx->eta == 1.0 && ctx->mu == 0.0;
-    hipLaunchKernelGGL(finish_kernel, dim3((K * D + 255) / 256), dim3(256), 0, ctx->stream, part, n, K, D, eps_h, plain,
-                       ctx->eta, ctx->mu, ctx->velocity, W, small);
-    return check_hip(ctx, hipGetLastError(), "update finish launch");
+    ctx->upd_static = g_scratch_ptr[ctx->device];
+    return SOM_OK;
+}
+
+int update_static_run(som_ctx* ctx, const double* S, const unsigned long long* n, const float* G, int32_t K, int32_t D,
+                      double sigma, double eps_h, float* W, int32_t* small)
+{
+    if (D + 1 > 64 || K > kUpdateStaticNodes || (int64_t)K * (D + 1) > kUpdateStaticCells)
+        return fail(ctx, SOM_EINVAL,
+                    "som_neighborhood_update_static serves D <= 63, K <= %d and K * (D + 1) <= %d (got K = %d, D = %d)",
+                    kUpdateStaticNodes, kUpdateStaticCells, K, D);
+    if (!ctx->upd_static) return fail(ctx, SOM_ESTATE, "the static update workspace was not set up on this device");
+    double* part = ctx->upd_static;
+    return update_launch(ctx, nullptr, part, part + (size_t)kSplitK * kUpdateStaticCells, S, n, G, K, D, sigma, eps_h, W, small);
 }
 
 } // namespace som

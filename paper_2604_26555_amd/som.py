@@ -30,7 +30,7 @@ EXPORTS = [
     "som_create", "som_destroy", "som_strerror", "som_last_error", "som_sync", "som_bmu", "som_accumulate",
     "som_neighborhood_update", "som_epoch", "som_epoch_host", "som_profile", "som_profile_read",
     "som_set_update_rule", "som_topology", "som_set_safeguard", "som_set_reproducible", "som_set_search",
-    "som_matrix_pipe_probe",
+    "som_matrix_pipe_probe", "som_neighborhood_update_static",
 ]
 
 
@@ -82,6 +82,8 @@ def load_library(path: str = LIB_PATH) -> C.CDLL:
     lib.som_accumulate.restype = C.c_int
     lib.som_neighborhood_update.argtypes = [vp, vp, vp, vp, i32, i32, f64, C.c_int, f64, vp, vp]
     lib.som_neighborhood_update.restype = C.c_int
+    lib.som_neighborhood_update_static.argtypes = [vp, vp, vp, vp, i32, i32, f64, C.c_int, f64, vp, vp]
+    lib.som_neighborhood_update_static.restype = C.c_int
     lib.som_set_reproducible.argtypes = [vp, C.c_int]
     lib.som_set_reproducible.restype = C.c_int
     lib.som_set_search.argtypes = [vp, C.c_int]
@@ -272,6 +274,20 @@ class Som:
                                               float(eps_h), _ptr(W, torch.float32, "W", self.device),
                                               _ptr(n_guarded, torch.int32, "n_guarded", self.device))
         self._check(rc, "som_neighborhood_update")
+        return W
+
+    def som_neighborhood_update_static(self, S, n, G, sigma, W, eps_h=0.0, n_guarded=None, kernel=SOM_KERNEL_GAUSSIAN):
+        """som_neighborhood_update without any device allocation (fixed per-GPU workspace; K * (D + 1) <= 65536)."""
+        K, D, _ = _matrix(W, "W")
+        if not W.is_contiguous() or S.shape != (K, D) or not S.is_contiguous() or G.shape != (K, K) \
+                or not G.is_contiguous() or n.numel() != K:
+            raise ValueError("shapes: W K x D, S K x D, G K x K, n K (all contiguous)")
+        rc = self.lib.som_neighborhood_update_static(self._h, _ptr(S, torch.float64, "S", self.device),
+                                                     _ptr(n, torch.uint64, "n", self.device),
+                                                     _ptr(G, torch.float32, "G", self.device), K, D, float(sigma), kernel,
+                                                     float(eps_h), _ptr(W, torch.float32, "W", self.device),
+                                                     _ptr(n_guarded, torch.int32, "n_guarded", self.device))
+        self._check(rc, "som_neighborhood_update_static")
         return W
 
     def som_set_reproducible(self, on=True):
