@@ -23,10 +23,21 @@ METRIC = "samples/sec per batch-SOM epoch (BMU+update), 1024 nodes x 50 features
 
 def stream_bench(args, wl, X, W0, sig, som, pkg, torch) -> int:
     """Host-resident X through som_epoch_host; reports whole-epoch samples/s and the copy stream's GB/s."""
-    Xh = X if args.stream == "mmap" else torch.from_numpy(X)
+    Xh = X if args.stream in ("mmap", "file") else torch.from_numpy(X)
     if args.stream == "pinned":
         Xh = Xh.pin_memory()
     Wd = torch.from_numpy(W0).cuda()
+    # what the host link itself sustains on this box: plain copies of 1 GiB from pinned memory, best of three
+    probe_h = torch.empty(1 << 28, dtype=torch.float32).pin_memory()
+    probe_d = torch.empty(1 << 28, dtype=torch.float32, device="cuda")
+    link_peak = 0.0
+    for _ in range(3):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        probe_d.copy_(probe_h, non_blocking=True)
+        torch.cuda.synchronize()
+        link_peak = max(link_peak, probe_h.numel() * 4 / (time.perf_counter() - t0) / 1e9)
+    del probe_h, probe_d
     lattice = wl.topology in ("rect", "hex")
     if lattice:
         G = torch.from_numpy(pkg.topology.graph_distances(wl.topology, lattice=wl.lattice)).cuda()
@@ -36,6 +47,8 @@ def stream_bench(args, wl, X, W0, sig, som, pkg, torch) -> int:
     def epoch(e):
         if not lattice:                      # data-driven graph, rebuilt on the device from the current weights
             som.som_topology(Wd, wl.topology, G)
+        if args.stream == "file":
+            return som.som_epoch_file(Xh, 0, wl.n, wl.d, Wd, G, float(sig[min(e, len(sig) - 1)]), chunk_rows=args.chunk_rows)
         return som.som_epoch_host(Xh, Wd, G, float(sig[min(e, len(sig) - 1)]), chunk_rows=args.chunk_rows)
 
     for e in range(args.warmup):
@@ -58,7 +71,9 @@ def stream_bench(args, wl, X, W0, sig, som, pkg, torch) -> int:
         "config": {"workload": f"{wl.name}: {wl.k}-node {wl.topology} map, {wl.n} x {wl.d} float32 samples in {args.stream} "
                                f"host memory, chunks of {args.chunk_rows} rows", "samples": wl.n, "chunk_rows": args.chunk_rows},
         "host_link": {"bytes_per_epoch": nbytes, "copy_stream_GBps": nbytes * args.steps / (h2d_ms * 1e-3) / 1e9 if h2d_ms else None,
-                      "end_to_end_GBps": nbytes * args.steps / dt / 1e9},
+                      "end_to_end_GBps": nbytes * args.steps / dt / 1e9, "pinned_copy_peak_GBps": link_peak,
+                      "end_to_end_frac_of_pinned_copy_peak": nbytes * args.steps / dt / 1e9 / link_peak,
+                      "chunks_per_epoch": -(-wl.n // args.chunk_rows)},
     }
     som.close()
     print(json.dumps(out))
@@ -82,11 +97,12 @@ def main() -> int:
                          "otherwise; float32 = float32 MFMA for every shape (same results either way)")
     ap.add_argument("--topology", default=None, choices=["rect", "hex", "mst", "rng"],
                     help="override the workload's map topology (mst and rng are rebuilt on the device every epoch)")
-    ap.add_argument("--stream", default=None, choices=["pinned", "pageable", "mmap"],
-                    help="keep X in host memory (or, mmap, in a memory-mapped file written to --mmap-dir first) and run "
-                         "som_epoch_host (the chunked loading path) instead")
+    ap.add_argument("--stream", default=None, choices=["pinned", "pageable", "mmap", "file"],
+                    help="keep X in host memory (or, mmap / file, in a file written to --mmap-dir first and then mapped, "
+                         "or read with pread by som_epoch_file) and run the chunked loading path instead")
     ap.add_argument("--mmap-dir", default="/tmp", help="where --stream mmap writes its sample file (deleted afterwards)")
-    ap.add_argument("--chunk-rows", type=int, default=4_000_000)
+    ap.add_argument("--chunk-rows", type=int, default=4_000_000,
+                    help="chunk length of the loading path in rows (cfg4 as configured: 64000000)")
     ap.add_argument("--rows", type=int, default=None, help="override the workload's sample count")
     ap.add_argument("--cpu-rows", type=int, default=1_000_000, help="rows of the workload the CPU oracle is timed on")
     ap.add_argument("--no-float32-reference", action="store_true",
@@ -123,6 +139,33 @@ def main() -> int:
         Xw.flush()
         del Xw
         X = np.load(mmap_path, mmap_mode="r")
+    elif args.stream == "file":
+        # the same file, handed to the library as a descriptor: chunks are read with pread into the staging buffers
+        mmap_path = os.path.join(args.mmap_dir, f"som_bench_{os.getpid()}.f32")
+        Xw = np.memmap(mmap_path, mode="w+", dtype=np.float32, shape=(wl.n, wl.d))
+        wl.data().fill(Xw)
+        Xw.flush()
+        init_rows = draw_initial_rows(wl.seed, wl.n, wl.k)
+        W0_file = np.ascontiguousarray(Xw[np.sort(init_rows)])
+        del Xw
+        X = os.open(mmap_path, os.O_RDONLY)
+    elif args.stream and wl.n * wl.d * 4 > (8 << 30):
+        # a large host-resident matrix: one anonymous allocation, filled in place by the host's cores (the generators
+        # are seeded per block of rows, so the data do not depend on how the work is cut)
+        from concurrent.futures import ThreadPoolExecutor
+        X = np.empty((wl.n, wl.d), dtype=np.float32)
+        gen = wl.data()
+        piece = 1 << 22
+        done = [0]
+
+        def fill_piece(lo):
+            gen.fill(X[lo:lo + piece], lo)
+            done[0] += 1
+            if done[0] % 32 == 0:
+                print(f"[bench] {done[0] * piece} rows generated after {time.time() - t0:.0f}s", file=sys.stderr, flush=True)
+
+        with ThreadPoolExecutor(max_workers=min(16, os.cpu_count() or 8)) as pool:
+            list(pool.map(fill_piece, range(0, wl.n, piece)))
     elif not args.stream and wl.n * wl.d * 4 > (48 << 30):
         # Too large to hold twice on the host: the matrix is generated in pieces (the generators are seeded per
         # block of rows, so the data do not depend on how they are cut) and goes to the device piece by piece; a
@@ -146,7 +189,9 @@ def main() -> int:
     else:
         X = wl.data().rows(0, wl.n)
     init_rows = draw_initial_rows(wl.seed, wl.n, wl.k)
-    if X is not None:
+    if args.stream == "file":
+        W0 = W0_file[np.argsort(np.argsort(init_rows))]
+    elif X is not None:
         W0 = np.ascontiguousarray(X[init_rows])
     else:
         W0 = Xd[torch.from_numpy(init_rows).cuda()].cpu().numpy()
@@ -160,6 +205,8 @@ def main() -> int:
             return stream_bench(args, wl, X, W0, sig, som, pkg, torch)
         finally:
             if mmap_path:
+                if args.stream == "file":
+                    os.close(X)
                 del X
                 os.remove(mmap_path)
     if X is not None:

@@ -24,7 +24,7 @@
  *
  * Calls return SOM_OK or a negative code; they never abort and never throw.  Arguments are checked first and
  * a rejected call has no side effects.  Work is enqueued on the context's stream and the call returns without
- * waiting, unless a [host] output is requested (som_epoch's stats, som_epoch_host).  The caller owns every
+ * waiting, unless a [host] output is requested (som_epoch's stats, som_epoch_host, som_epoch_file).  The caller owns every
  * buffer it passes and keeps it alive until som_sync (or a synchronising call) returns; the library owns only
  * its internal workspaces.  A context is bound to one device and is not thread-safe.
  */
@@ -44,7 +44,7 @@ enum {
     SOM_EINVAL = -1, /* bad argument (null pointer, non-positive size, ldx < D, m != N without idx, ...) */
     SOM_ENOMEM = -2, /* a workspace allocation failed */
     SOM_EHIP = -3,   /* a HIP runtime call or kernel launch failed; see som_last_error */
-    SOM_EIO = -4,    /* reserved for file-backed streaming */
+    SOM_EIO = -4,    /* som_epoch_file: the sample file is too short or a read failed; see som_last_error */
     SOM_ESTATE = -5  /* context unusable (no gfx950 device, destroyed) */
 };
 
@@ -221,9 +221,10 @@ typedef struct {
 } som_stats;
 
 /*
- * One whole epoch on device-resident samples: BMU search fused with the per-BMU accumulation (the BMU indices
- * never travel through memory), then the neighbourhood update of W in place.  Arguments as above.  stats is
- * [host] or NULL; a non-NULL stats makes the call wait for the epoch to finish.  m == 0 leaves W unchanged.
+ * One whole epoch on device-resident samples: best-matching-unit search over the presented rows (the BMU indices go
+ * to a library-owned buffer), per-BMU accumulation in a second pass over the same rows, then the neighbourhood update
+ * of W in place.  Arguments as above.  stats is [host] or NULL; a non-NULL stats makes the call wait for the epoch
+ * to finish.  m == 0 leaves W unchanged.
  */
 int som_epoch(som_ctx* ctx, const float* X, int64_t N, int32_t D, int64_t ldx,
               const uint32_t* idx, int64_t m, float* W, int32_t K,
@@ -233,12 +234,27 @@ int som_epoch(som_ctx* ctx, const float* X, int64_t N, int32_t D, int64_t ldx,
  * One whole epoch on samples in HOST memory (Section 3.3.2's chunked loading path: pinned host chunk, copy
  * to the GPU on a side stream overlapped with compute on the previous chunk, accumulators carried across the
  * chunks, one update at the end).  Xhost [host] is any readable N x D float32 array, dense (ldx = D), for
- * instance a memory-mapped file.  chunk_rows > 0 is the chunk length in rows; the library owns two pinned
- * staging buffers and two device buffers of chunk_rows x D floats, allocated on first use and kept until
- * som_destroy.  pinned != 0 promises that Xhost itself is pinned (hipHostMalloc) memory, in which case it is
- * copied from directly.  Always waits for the epoch to finish.
+ * instance a memory-mapped file; the library reads all N * D floats of it with memcpy, so a mapping shorter than that
+ * faults as any read beyond it would (use som_epoch_file to have a short file reported instead).  chunk_rows > 0 is
+ * the chunk length in rows; the library owns two pinned staging buffers and two device buffers of chunk_rows x D
+ * floats, allocated on first use and kept until som_destroy.  pinned != 0 promises that Xhost itself is pinned
+ * (hipHostMalloc) memory, in which case it is copied from directly.  Always waits for the epoch to finish; after a
+ * failure both of the library's streams have been drained and the context stays usable (W is unchanged unless the
+ * failure came from the update itself).
  */
 int som_epoch_host(som_ctx* ctx, const float* Xhost, int64_t N, int32_t D, int64_t chunk_rows, int pinned,
+                   float* W, int32_t K, const float* G, double sigma, int kernel, double eps_h,
+                   som_stats* stats);
+
+/*
+ * The same epoch on samples in a FILE (the disk-backed regime of Section 3.3.2): rows 0..N-1 are the N * D float32
+ * values that start at byte `offset` of the open file descriptor fd (dense, row-major).  Each chunk is read with
+ * pread by several host threads straight into a pinned staging buffer (no mapping, no intermediate copy) while the
+ * previous chunk is on the GPU.  A regular file shorter than offset + N * D * 4 bytes is rejected up front with
+ * SOM_EIO and no side effects; a read error or an early end of file during the epoch returns SOM_EIO after both
+ * streams have been drained, W unchanged.  The descriptor stays the caller's; its file position is not used.
+ */
+int som_epoch_file(som_ctx* ctx, int fd, int64_t offset, int64_t N, int32_t D, int64_t chunk_rows,
                    float* W, int32_t K, const float* G, double sigma, int kernel, double eps_h,
                    som_stats* stats);
 

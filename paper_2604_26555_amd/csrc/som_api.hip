@@ -6,7 +6,13 @@
 #include <stdio.h>
 #include <string.h>
 
+#include <errno.h>
+#include <sys/stat.h>
+#include <sys/types.h>
+#include <unistd.h>
+
 #include <algorithm>
+#include <atomic>
 #include <thread>
 #include <vector>
 
@@ -163,6 +169,7 @@ void som_destroy(som_ctx* c)
     if (c->small) (void)hipFree(c->small);
     if (c->qe_part) (void)hipFree(c->qe_part);
     if (c->host_small) (void)hipHostFree(c->host_small);
+    for (hipEvent_t e : c->h2d_events) (void)hipEventDestroy(e);
     for (auto& pr : c->prof_events) {
         (void)hipEventDestroy(pr.first);
         (void)hipEventDestroy(pr.second);
@@ -417,38 +424,73 @@ static void parallel_copy(void* dst, const void* src, size_t bytes)
     for (auto& t : th) t.join();
 }
 
-int som_epoch_host(som_ctx* ctx, const float* Xhost, int64_t N, int32_t D, int64_t chunk_rows, int pinned, float* W,
-                   int32_t K, const float* G, double sigma, int kernel, double eps_h, som_stats* stats)
+// reads [offset, offset + bytes) of a file into dst with several host threads; 0, or an errno value (EIO for a file
+// that ends early)
+static int parallel_pread(int fd, void* dst, int64_t offset, size_t bytes)
 {
-    if (int rc = common_checks(ctx, Xhost, N, D, D, nullptr, N, W, K)) return rc;
-    if (int rc = update_checks(ctx, G, K, D, sigma, kernel)) return rc;
-    if (chunk_rows < 1) return fail(ctx, SOM_EINVAL, "chunk_rows must be positive");
-    if (chunk_rows > 0x7fffffffLL) return fail(ctx, SOM_EINVAL, "chunk_rows above 2^31-1");
-    if (!device_readable(W) || !device_readable(G)) return fail(ctx, SOM_EINVAL, "W and G must be device-accessible memory");
-    if (int rc = check_hip(ctx, hipSetDevice(ctx->device), "hipSetDevice")) return rc;
-    if (eps_h <= 0.0) eps_h = 1e-30;
-    if (N == 0) {
-        if (stats) {
-            memset(stats, 0, sizeof(*stats));
-            stats->n_empty = K;
-            stats->n_guarded = K;
+    unsigned hw = std::thread::hardware_concurrency();
+    unsigned nt = std::min<unsigned>(hw ? hw : 4, 16);
+    if (bytes < ((size_t)8 << 20)) nt = 1;
+    const size_t per = ((bytes / nt) + 4095) & ~(size_t)4095;
+    std::atomic<int> err{0};
+    auto work = [&](size_t lo, size_t len) {
+        size_t done = 0;
+        while (done < len && err.load(std::memory_order_relaxed) == 0) {
+            const ssize_t r = pread(fd, (char*)dst + lo + done, std::min(len - done, (size_t)1 << 30), (off_t)(offset + lo + done));
+            if (r < 0) {
+                if (errno == EINTR) continue;
+                err.store(errno ? errno : EIO);
+                return;
+            }
+            if (r == 0) {           // end of file inside the range the caller promised
+                err.store(EIO);
+                return;
+            }
+            done += (size_t)r;
         }
-        return SOM_OK;
+    };
+    if (nt <= 1) {
+        work(0, bytes);
+        return err.load();
     }
+    std::vector<std::thread> th;
+    for (unsigned t = 0; t < nt; ++t) {
+        const size_t lo = (size_t)t * per;
+        if (lo >= bytes) break;
+        th.emplace_back(work, lo, std::min(per, bytes - lo));
+    }
+    for (auto& t : th) t.join();
+    return err.load();
+}
+
+// where the chunks of a streamed epoch come from
+struct ChunkSource {
+    const float* host = nullptr; // host memory (pageable, mapped or pinned), or
+    int pinned = 0;              // ... caller-pinned memory, copied from directly
+    int fd = -1;                 // a file descriptor read with pread
+    int64_t offset = 0;          // byte offset of row 0 in the file
+};
+
+// the chunk loop shared by som_epoch_host and som_epoch_file (Section 3.3.2): stage chunk c + 1 into a pinned buffer and
+// copy it to the device on the copy stream while chunk c is searched and accumulated on the compute stream
+static int stream_epoch(som_ctx* ctx, const ChunkSource& src, int64_t N, int32_t D, int64_t chunk_rows, float* W, int32_t K,
+                        const float* G, double sigma, double eps_h, som_stats* stats)
+{
     if (chunk_rows > N) chunk_rows = N;
+    const bool staged = !(src.host && src.pinned);
     const size_t chunk_elems = (size_t)chunk_rows * D;
-    if (chunk_elems > ctx->chunk_elems || (!pinned && !ctx->pinned[0])) {
+    if (chunk_elems > ctx->chunk_elems || (staged && !ctx->pinned[0])) {
         if (int rc = check_hip(ctx, hipDeviceSynchronize(), "sync before buffer growth")) return rc;
         for (int i = 0; i < 2; ++i) {
             if (ctx->dchunk[i]) (void)hipFree(ctx->dchunk[i]);
             if (ctx->pinned[i]) (void)hipHostFree(ctx->pinned[i]);
             ctx->dchunk[i] = ctx->pinned[i] = nullptr;
         }
-        ctx->chunk_elems = 0;
         const size_t want = std::max(chunk_elems, ctx->chunk_elems);
+        ctx->chunk_elems = 0;
         for (int i = 0; i < 2; ++i) {
             if (hipMalloc((void**)&ctx->dchunk[i], want * sizeof(float)) != hipSuccess ||
-                (!pinned && hipHostMalloc((void**)&ctx->pinned[i], want * sizeof(float), hipHostMallocDefault) != hipSuccess)) {
+                (staged && hipHostMalloc((void**)&ctx->pinned[i], want * sizeof(float), hipHostMallocDefault) != hipSuccess)) {
                 (void)hipGetLastError();
                 return fail(ctx, SOM_ENOMEM, "cannot allocate the chunk buffers (%zu bytes each)", want * sizeof(float));
             }
@@ -456,39 +498,54 @@ int som_epoch_host(som_ctx* ctx, const float* Xhost, int64_t N, int32_t D, int64
         ctx->chunk_elems = want;
     }
     if (int rc = begin_epoch(ctx, K, D, chunk_rows)) return rc;
+    const int64_t nchunks = (N + chunk_rows - 1) / chunk_rows;
+    // timing events of the copies: a pool owned by the context, grown on demand and reused by every epoch
+    const bool timed = stats != nullptr;
+    while (timed && ctx->h2d_events.size() < (size_t)(2 * nchunks)) {
+        hipEvent_t e;
+        if (int rc = check_hip(ctx, hipEventCreate(&e), "event creation")) return rc;
+        ctx->h2d_events.push_back(e);
+    }
     BmuPrep prep;
     (void)hipEventRecord(ctx->ev_t[0], ctx->stream);
     if (int rc = bmu_prepare(ctx, W, K, D, &prep, ctx->qe, ctx->small)) return rc;
 
-    const int64_t nchunks = (N + chunk_rows - 1) / chunk_rows;
+    // After a failure inside the loop both streams are drained before the call returns: nothing of this epoch is
+    // still in flight into the chunk buffers when the caller uses the context again.
+    auto bail = [&](int rc) {
+        (void)hipStreamSynchronize(ctx->copy_stream);
+        (void)hipStreamSynchronize(ctx->stream);
+        (void)hipGetLastError();
+        return rc;
+    };
     HostSmall* h = (HostSmall*)ctx->host_small;
-    float ms_h2d = 0.f;
-    std::vector<hipEvent_t> h2d_marks; // pairs (start, stop) per chunk, created lazily for timing
     for (int64_t c = 0; c < nchunks; ++c) {
         const int b = (int)(c & 1);
         const int64_t lo = c * chunk_rows;
         const int64_t rows = std::min(chunk_rows, N - lo);
         const size_t bytes = (size_t)rows * D * sizeof(float);
-        const float* src = Xhost + (size_t)lo * D;
-        if (!pinned) {
+        const float* from = src.host ? src.host + (size_t)lo * D : nullptr;
+        if (staged) {
             // the staging buffer is free once its previous copy to the device has finished
             if (c >= 2)
-                if (int rc = check_hip(ctx, hipEventSynchronize(ctx->ev_copied[b]), "waiting for a staging buffer")) return rc;
-            parallel_copy(ctx->pinned[b], src, bytes);
-            src = ctx->pinned[b];
+                if (int rc = check_hip(ctx, hipEventSynchronize(ctx->ev_copied[b]), "waiting for a staging buffer")) return bail(rc);
+            if (src.host) {
+                parallel_copy(ctx->pinned[b], from, bytes);
+            } else if (int e = parallel_pread(src.fd, ctx->pinned[b], src.offset + (int64_t)((size_t)lo * D * sizeof(float)), bytes)) {
+                return bail(fail(ctx, SOM_EIO, "reading rows %lld..%lld of the sample file: %s", (long long)lo,
+                                 (long long)(lo + rows - 1), strerror(e)));
+            }
+            from = ctx->pinned[b];
         }
         // the device buffer is free once the compute of two chunks ago has consumed it
         if (c >= 2)
-            if (int rc = check_hip(ctx, hipStreamWaitEvent(ctx->copy_stream, ctx->ev_consumed[b], 0), "stream wait")) return rc;
-        hipEvent_t e0, e1;
-        if (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess) return fail(ctx, SOM_EHIP, "event creation failed");
-        h2d_marks.push_back(e0);
-        h2d_marks.push_back(e1);
-        (void)hipEventRecord(e0, ctx->copy_stream);
-        if (int rc = check_hip(ctx, hipMemcpyAsync(ctx->dchunk[b], src, bytes, hipMemcpyHostToDevice, ctx->copy_stream), "host-to-device copy")) return rc;
-        (void)hipEventRecord(e1, ctx->copy_stream);
+            if (int rc = check_hip(ctx, hipStreamWaitEvent(ctx->copy_stream, ctx->ev_consumed[b], 0), "stream wait")) return bail(rc);
+        if (timed) (void)hipEventRecord(ctx->h2d_events[2 * c], ctx->copy_stream);
+        if (int rc = check_hip(ctx, hipMemcpyAsync(ctx->dchunk[b], from, bytes, hipMemcpyHostToDevice, ctx->copy_stream), "host-to-device copy"))
+            return bail(rc);
+        if (timed) (void)hipEventRecord(ctx->h2d_events[2 * c + 1], ctx->copy_stream);
         (void)hipEventRecord(ctx->ev_copied[b], ctx->copy_stream);
-        if (int rc = check_hip(ctx, hipStreamWaitEvent(ctx->stream, ctx->ev_copied[b], 0), "stream wait")) return rc;
+        if (int rc = check_hip(ctx, hipStreamWaitEvent(ctx->stream, ctx->ev_copied[b], 0), "stream wait")) return bail(rc);
         BmuArgs a{};
         a.X = ctx->dchunk[b];
         a.ldx = D;
@@ -499,24 +556,76 @@ int som_epoch_host(som_ctx* ctx, const float* Xhost, int64_t N, int32_t D, int64
         a.W = W;
         a.qe = ctx->qe;
         a.bmu = ctx->bmu_ws;
-        if (int rc = bmu_run(ctx, prep, a)) return rc;
-        if (int rc = accumulate_run(ctx, ctx->dchunk[b], D, D, nullptr, rows, ctx->bmu_ws, K, ctx->S, ctx->n, c == 0)) return rc;
+        if (int rc = bmu_run(ctx, prep, a)) return bail(rc);
+        if (int rc = accumulate_run(ctx, ctx->dchunk[b], D, D, nullptr, rows, ctx->bmu_ws, K, ctx->S, ctx->n, c == 0)) return bail(rc);
         (void)hipEventRecord(ctx->ev_consumed[b], ctx->stream);
     }
     (void)hipEventRecord(ctx->ev_t[1], ctx->stream);
-    if (int rc = check_hip(ctx, hipMemcpyAsync(h->scal, prep.scal, sizeof(h->scal), hipMemcpyDeviceToHost, ctx->stream), "reading statistics")) return rc;
-    if (int rc = update_run(ctx, ctx->S, ctx->n, G, K, D, sigma, eps_h, W, ctx->small)) return rc;
+    if (int rc = check_hip(ctx, hipMemcpyAsync(h->scal, prep.scal, sizeof(h->scal), hipMemcpyDeviceToHost, ctx->stream), "reading statistics"))
+        return bail(rc);
+    if (int rc = update_run(ctx, ctx->S, ctx->n, G, K, D, sigma, eps_h, W, ctx->small)) return bail(rc);
     (void)hipEventRecord(ctx->ev_t[2], ctx->stream);
     int rc = check_hip(ctx, hipStreamSynchronize(ctx->stream), "waiting for the epoch");
     if (!rc) rc = check_hip(ctx, hipStreamSynchronize(ctx->copy_stream), "waiting for the copy stream");
-    for (size_t i = 0; i + 1 < h2d_marks.size(); i += 2) {
+    if (rc) return bail(rc);
+    float ms_h2d = 0.f;
+    for (int64_t c = 0; timed && c < nchunks; ++c) {
         float ms = 0.f;
-        if (!rc && hipEventElapsedTime(&ms, h2d_marks[i], h2d_marks[i + 1]) == hipSuccess) ms_h2d += ms;
+        if (hipEventElapsedTime(&ms, ctx->h2d_events[2 * c], ctx->h2d_events[2 * c + 1]) == hipSuccess) ms_h2d += ms;
     }
-    for (hipEvent_t e : h2d_marks) (void)hipEventDestroy(e);
-    if (rc) return rc;
     if (stats) return finish_stats(ctx, N, (int64_t)h->scal[3], stats, true, ms_h2d);
     return SOM_OK;
+}
+
+static int stream_checks(som_ctx* ctx, const void* X, int64_t N, int32_t D, int64_t chunk_rows, const float* W, int32_t K,
+                         const float* G, double sigma, int kernel)
+{
+    if (int rc = common_checks(ctx, X, N, D, D, nullptr, N, W, K)) return rc;
+    if (int rc = update_checks(ctx, G, K, D, sigma, kernel)) return rc;
+    if (chunk_rows < 1) return fail(ctx, SOM_EINVAL, "chunk_rows must be positive");
+    if (chunk_rows > 0x7fffffffLL) return fail(ctx, SOM_EINVAL, "chunk_rows above 2^31-1");
+    if (!device_readable(W) || !device_readable(G)) return fail(ctx, SOM_EINVAL, "W and G must be device-accessible memory");
+    return check_hip(ctx, hipSetDevice(ctx->device), "hipSetDevice");
+}
+
+static int empty_epoch(int32_t K, som_stats* stats)
+{
+    if (stats) {
+        memset(stats, 0, sizeof(*stats));
+        stats->n_empty = K;
+        stats->n_guarded = K;
+    }
+    return SOM_OK;
+}
+
+int som_epoch_host(som_ctx* ctx, const float* Xhost, int64_t N, int32_t D, int64_t chunk_rows, int pinned, float* W,
+                   int32_t K, const float* G, double sigma, int kernel, double eps_h, som_stats* stats)
+{
+    if (int rc = stream_checks(ctx, Xhost, N, D, chunk_rows, W, K, G, sigma, kernel)) return rc;
+    if (N == 0) return empty_epoch(K, stats);
+    ChunkSource src;
+    src.host = Xhost;
+    src.pinned = pinned;
+    return stream_epoch(ctx, src, N, D, chunk_rows, W, K, G, sigma, eps_h <= 0.0 ? 1e-30 : eps_h, stats);
+}
+
+int som_epoch_file(som_ctx* ctx, int fd, int64_t offset, int64_t N, int32_t D, int64_t chunk_rows, float* W, int32_t K,
+                   const float* G, double sigma, int kernel, double eps_h, som_stats* stats)
+{
+    // (the shared checks want a non-null sample pointer for N > 0: the file stands in for it)
+    if (int rc = stream_checks(ctx, N > 0 ? (const void*)W : nullptr, N, D, chunk_rows, W, K, G, sigma, kernel)) return rc;
+    if (fd < 0 || offset < 0) return fail(ctx, SOM_EINVAL, "bad file descriptor or negative offset");
+    struct stat st;
+    if (fstat(fd, &st) != 0) return fail(ctx, SOM_EIO, "fstat on the sample file: %s", strerror(errno));
+    const int64_t need = offset + (int64_t)((size_t)N * D * sizeof(float));
+    if (S_ISREG(st.st_mode) && (int64_t)st.st_size < need)
+        return fail(ctx, SOM_EIO, "the sample file holds %lld bytes, %lld rows of %d floats from offset %lld need %lld",
+                    (long long)st.st_size, (long long)N, D, (long long)offset, (long long)need);
+    if (N == 0) return empty_epoch(K, stats);
+    ChunkSource src;
+    src.fd = fd;
+    src.offset = offset;
+    return stream_epoch(ctx, src, N, D, chunk_rows, W, K, G, sigma, eps_h <= 0.0 ? 1e-30 : eps_h, stats);
 }
 
 } // extern "C"

@@ -114,6 +114,7 @@ struct som_ctx {
     hipEvent_t ev_copied[2] = {nullptr, nullptr};
     hipEvent_t ev_consumed[2] = {nullptr, nullptr};
     hipEvent_t ev_t[4] = {nullptr, nullptr, nullptr, nullptr};
+    std::vector<hipEvent_t> h2d_events;   // (start, stop) per chunk of a streamed epoch; grown on demand, reused
     // measurement support: event pairs around every launch of the main BMU kernel while profiling is on
     bool profiling = false;
     std::vector<std::pair<hipEvent_t, hipEvent_t>> prof_events;

@@ -30,7 +30,7 @@ EXPORTS = [
     "som_create", "som_destroy", "som_strerror", "som_last_error", "som_sync", "som_bmu", "som_accumulate",
     "som_neighborhood_update", "som_epoch", "som_epoch_host", "som_profile", "som_profile_read",
     "som_set_update_rule", "som_topology", "som_set_safeguard", "som_set_reproducible", "som_set_search",
-    "som_matrix_pipe_probe", "som_neighborhood_update_static",
+    "som_matrix_pipe_probe", "som_neighborhood_update_static", "som_epoch_file",
 ]
 
 
@@ -99,6 +99,8 @@ def load_library(path: str = LIB_PATH) -> C.CDLL:
     lib.som_epoch_host.argtypes = [vp, vp, i64, i32, i64, C.c_int, vp, i32, vp, f64, C.c_int, f64,
                                    C.POINTER(SomStats)]
     lib.som_epoch_host.restype = C.c_int
+    lib.som_epoch_file.argtypes = [vp, C.c_int, i64, i64, i32, i64, vp, i32, vp, f64, C.c_int, f64, C.POINTER(SomStats)]
+    lib.som_epoch_file.restype = C.c_int
     _lib = lib
     return lib
 
@@ -360,4 +362,17 @@ class Som:
                                      _ptr(G, torch.float32, "G", self.device), float(sigma), kernel, float(eps_h),
                                      C.byref(st))
         self._check(rc, "som_epoch_host")
+        return _stats(st)
+
+    def som_epoch_file(self, fd, offset, N, D, W, G, sigma, chunk_rows, eps_h=0.0, kernel=SOM_KERNEL_GAUSSIAN):
+        """One epoch on the N x D float32 rows stored from byte ``offset`` of the open file descriptor ``fd``."""
+        K, Dw, _ = _matrix(W, "W")
+        if Dw != D or not W.is_contiguous() or G.shape != (K, K) or not G.is_contiguous():
+            raise ValueError("shapes: W K x D contiguous with the file's D, G K x K contiguous")
+        st = SomStats()
+        rc = self.lib.som_epoch_file(self._h, int(fd), int(offset), int(N), int(D), int(chunk_rows),
+                                     _ptr(W, torch.float32, "W", self.device), K,
+                                     _ptr(G, torch.float32, "G", self.device), float(sigma), kernel, float(eps_h),
+                                     C.byref(st))
+        self._check(rc, "som_epoch_file")
         return _stats(st)

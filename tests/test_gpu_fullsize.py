@@ -273,3 +273,36 @@ def test_relative_neighbourhood_graph_at_4096_nodes(som):
     hops = shortest_path(csr_matrix(adj.astype(np.int8)), unweighted=True, indices=src)
     assert np.array_equal(R[src], hops.astype(np.float32))
     print(f"RNG K=4096: {int(adj.sum()) // 2} edges, largest hop count {int(R.max())}", flush=True)
+
+
+def test_streamed_epoch_with_a_chunk_above_4_gib(som):
+    """2.5 * 10^7 x 50 rows (5 GB) in host memory, streamed in chunks of 2.2 * 10^7 rows (4.4 GB: byte counts beyond
+    32 bits in the staging copies, the transfers and the kernels' row offsets), against the same epoch on resident
+    samples; best-matching units of sampled rows on both sides of the chunk boundary against the brute-force oracle."""
+    from concurrent.futures import ThreadPoolExecutor
+    wl = make_workload("cfg4", n=25_000_000)
+    gen = wl.data()
+    X = np.empty((wl.n, wl.d), dtype=np.float32)
+    piece = 1 << 20
+    with ThreadPoolExecutor(8) as pool:
+        list(pool.map(lambda lo: gen.fill(X[lo:lo + piece], lo), range(0, wl.n, piece)))
+    W0 = X[draw_initial_rows(wl.seed, wl.n, wl.k)].copy()
+    G = torch.from_numpy(oracle.rect_lattice_distances(32, 32).astype(np.float32)).cuda()
+    chunk = 22_000_000
+    assert chunk * wl.d * 4 > 1 << 32
+    Wa, Wb = torch.from_numpy(W0).cuda(), torch.from_numpy(W0).cuda()
+    print("streaming 2.5e7 rows in chunks of 2.2e7", flush=True)
+    sb = som.som_epoch_host(X, Wb, G, 4.0, chunk_rows=chunk)
+    Xd = torch.from_numpy(X).cuda()
+    sa = som.som_epoch(Xd, Wa, G, 4.0)
+    print(f"streamed {sb.ms_bmu_acc:.1f} ms of compute, {sb.ms_h2d:.1f} ms of copies; resident {sa.ms_bmu_acc:.1f} ms", flush=True)
+    np.testing.assert_allclose(Wb.cpu().numpy(), Wa.cpu().numpy(), rtol=1e-6, atol=1e-7)
+    assert sa.m == sb.m == wl.n and abs(sa.sum_dist - sb.sum_dist) <= 1e-9 * sa.sum_dist and sa.n_empty == sb.n_empty
+    b_gpu, _, _ = som.som_bmu(Xd, torch.from_numpy(W0).cuda())
+    rows = np.unique(np.concatenate([np.random.default_rng(9).choice(wl.n, 3000, replace=False),
+                                     [0, chunk - 1, chunk, chunk + 1, wl.n - 1]]))
+    b, best, second = oracle.bmu(X[rows], W0)
+    mask = oracle.near_tie_mask(best, second)
+    assert ((b_gpu.cpu().numpy()[rows] == b) | mask).all()
+    # the streamed statistics are those of the oracle on the sampled rows' scale: mean distance within sampling error
+    assert abs(sb.qe - float(np.sqrt(best).mean())) <= 0.05 * sb.qe

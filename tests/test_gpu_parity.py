@@ -851,6 +851,56 @@ def test_streamed_epoch_equals_resident_epoch(som, chunk):
     np.testing.assert_allclose(Wc.cpu().numpy(), Wa.cpu().numpy(), rtol=1e-6, atol=1e-7)
 
 
+def test_streamed_epoch_from_a_file(som, tmp_path):
+    """som_epoch_file reads the chunks with pread: same epoch as the resident one, from offset 0 and from an offset;
+    a file that is too short is refused up front, a descriptor that cannot be read fails inside the chunk loop, and
+    the context works afterwards in both cases."""
+    import os
+    from paper_2604_26555_amd import SomError, SOM_EIO
+    wl = make_workload("cfg4", n=30_000, k=100, lattice=(10, 10))
+    X = wl.data().rows(0, wl.n)
+    W0 = X[draw_initial_rows(wl.seed, wl.n, wl.k)]
+    G = dev(oracle.graph_distances("rect", lattice=(10, 10)).astype(np.float32))
+    path = str(tmp_path / "samples.f32")
+    with open(path, "wb") as f:
+        f.write(b"\0" * 4096)                       # a header the offset skips
+        f.write(X.tobytes())
+    Wa = dev(W0)
+    sa = som.som_epoch(dev(X), Wa, G, 2.0)
+    fd = os.open(path, os.O_RDONLY)
+    try:
+        for chunk in (7001, 30_000, 100_000):
+            Wb = dev(W0)
+            sb = som.som_epoch_file(fd, 4096, wl.n, wl.d, Wb, G, 2.0, chunk_rows=chunk)
+            np.testing.assert_allclose(Wb.cpu().numpy(), Wa.cpu().numpy(), rtol=1e-6, atol=1e-7)
+            assert sb.m == wl.n and abs(sa.sum_dist - sb.sum_dist) <= 1e-9 * sa.sum_dist and sa.n_empty == sb.n_empty
+        ref = oracle.epoch_grouped(X, None, W0, oracle.rect_lattice_distances(10, 10), 2.0)
+        weights_close(Wb.cpu().numpy(), ref["W"], ref["den"])
+        # one row more than the file holds: refused before anything runs
+        Wc = dev(W0)
+        with pytest.raises(SomError) as e:
+            som.som_epoch_file(fd, 4096, wl.n + 1, wl.d, Wc, G, 2.0, chunk_rows=7001)
+        assert e.value.code == SOM_EIO and "holds" in str(e.value)
+        assert (Wc.cpu().numpy() == W0).all()
+    finally:
+        os.close(fd)
+    # a pipe cannot be read at an offset: the first chunk's read fails inside the loop
+    r, w = os.pipe()
+    try:
+        Wc = dev(W0)
+        with pytest.raises(SomError) as e:
+            som.som_epoch_file(r, 0, wl.n, wl.d, Wc, G, 2.0, chunk_rows=7001)
+        assert e.value.code == SOM_EIO and "reading rows" in str(e.value)
+        assert (Wc.cpu().numpy() == W0).all()
+    finally:
+        os.close(r)
+        os.close(w)
+    Wd = dev(W0)
+    sd = som.som_epoch_host(X, Wd, G, 2.0, chunk_rows=7001)          # the context still works
+    np.testing.assert_allclose(Wd.cpu().numpy(), Wa.cpu().numpy(), rtol=1e-6, atol=1e-7)
+    assert sd.m == wl.n
+
+
 # ------------------------------------------------------------------------------------------- error paths
 def test_argument_errors_are_reported_not_fatal(som):
     from paper_2604_26555_amd import SomError, SOM_EINVAL
