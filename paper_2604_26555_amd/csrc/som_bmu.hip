@@ -222,6 +222,75 @@ __device__ __forceinline__ void list_push(unsigned int* __restrict__ counter, ui
     }
 }
 
+// The re-decision list of a pass.  The search kernels do not append to it themselves: one atomic per wavefront on the
+// list's single length word serialises in the memory system (about 10 ns each; with a few per cent of the samples
+// listed nearly every wavefront has one, and the 15,625 wavefronts of 10^6 samples then spent up to 0.1 ms of a
+// 0.4 ms kernel queueing for it).  Each sample instead gets one word, its cut (best score minus the rounding bound)
+// or kNotListed, and this kernel compacts the listed ones: a workgroup takes 4096 samples at a time, counts with a
+// scan, and reserves its entries with one atomic.  The order of the list is immaterial (every entry is decided on its
+// own).
+constexpr float kNotListed = __builtin_nanf("");
+constexpr int kListThreads = 1024, kListPerThread = 4;
+
+__global__ void __launch_bounds__(kListThreads) bmu_list_kernel(const BmuArgs a)
+{
+    __shared__ unsigned int wave_base[kListThreads / 64];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    constexpr int64_t per_block = (int64_t)kListThreads * kListPerThread;
+    for (int64_t chunk = blockIdx.x; chunk * per_block < a.m; chunk += gridDim.x) {
+        const int64_t i0 = chunk * per_block + (int64_t)tid * kListPerThread;
+        float c[kListPerThread];
+        if (i0 + kListPerThread <= a.m) {
+            const float4 t = *reinterpret_cast<const float4*>(a.cut_all + i0);      // i0 is a multiple of four
+            c[0] = t.x;
+            c[1] = t.y;
+            c[2] = t.z;
+            c[3] = t.w;
+        } else {
+#pragma unroll
+            for (int q = 0; q < kListPerThread; ++q) c[q] = (i0 + q < a.m) ? a.cut_all[i0 + q] : kNotListed;
+        }
+        static_assert(kListPerThread == 4, "a thread's cuts travel as one float4");
+        unsigned int mine = 0u;
+#pragma unroll
+        for (int q = 0; q < kListPerThread; ++q) mine += (c[q] == c[q]) ? 1u : 0u;
+        unsigned int incl = mine;                         // inclusive scan over the wavefront
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+            const unsigned int t = __shfl_up(incl, o);
+            if (lane >= o) incl += t;
+        }
+        if (lane == 63) wave_base[wave] = incl;
+        __syncthreads();
+        if (wave == 0) {
+            // exclusive scan of the wavefronts' totals; the last lane reserves the workgroup's entries
+            const unsigned int w = lane < kListThreads / 64 ? wave_base[lane] : 0u;
+            unsigned int wi = w;
+#pragma unroll
+            for (int o = 1; o < kListThreads / 64; o <<= 1) {
+                const unsigned int t = __shfl_up(wi, o);
+                if (lane >= o) wi += t;
+            }
+            const unsigned int total = __shfl(wi, kListThreads / 64 - 1);
+            unsigned int base = 0u;
+            if (lane == 0 && total) base = atomicAdd(&a.scal[a.slot], total);
+            base = __shfl(base, 0);
+            if (lane < kListThreads / 64) wave_base[lane] = base + wi - w;
+        }
+        __syncthreads();
+        unsigned int pos = wave_base[wave] + incl - mine;
+#pragma unroll
+        for (int q = 0; q < kListPerThread; ++q) {
+            if (c[q] == c[q]) {
+                a.recheck[pos] = (uint32_t)(i0 + q);
+                a.cutv[pos] = c[q];
+                ++pos;
+            }
+        }
+        __syncthreads();                                 // wave_base is rewritten by the next chunk
+    }
+}
+
 // sixteen bytes from a 4-byte aligned address in one load (global memory needs no more than dword alignment)
 __device__ __forceinline__ float4 load4(const float* p)
 {
@@ -545,7 +614,7 @@ __device__ __forceinline__ void bmu_tile(const BmuArgs& a, int64_t first, int64_
                 qs2 += (double)r_part;
             }
         }
-        list_push(&a.scal[a.slot], a.recheck, a.cutv, close, i, r_best - bound);
+        if (r_valid) a.cut_all[i] = close ? r_best - bound : kNotListed;
     }
     if (a.qe) group_qe_add(a.qe_part, qs, qs2);
 }
@@ -618,10 +687,11 @@ __global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2
 // ---------------------------------------------------------------------------------------------------------
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 
-constexpr int split_row_bytes(int kb) { return kb * 64 + 16; }
-constexpr int split_stage_f4(int kb)
+// bytes of a stage row: kb whole 16-feature blocks of 64 bytes, 32 bytes for a packed tail block, 16 bytes of padding
+constexpr int split_row_bytes(int kb, bool tail = false) { return kb * 64 + (tail ? 32 : 0) + 16; }
+constexpr int split_stage_f4(int kb, bool tail = false)
 {
-    return ((kNodesPerStage * split_row_bytes(kb) + kNodesPerStage * 4) / 16 + kThreads - 1) / kThreads * kThreads;
+    return ((kNodesPerStage * split_row_bytes(kb, tail) + kNodesPerStage * 4) / 16 + kThreads - 1) / kThreads * kThreads;
 }
 constexpr float kSplitPadNorm = -3.0e38f;
 constexpr int kSplitMinNodes = 384;            // SOM_SEARCH_AUTO: smaller maps use the float32 search
@@ -642,31 +712,45 @@ __device__ __forceinline__ int split_window(int q, int D) { return 4 * q < D - 4
 
 // stage16 from W: one thread per (node, slot), chunks of kb_count 16-feature blocks (one chunk for D <= 64, chunks of
 // 64 features above); the first kpad threads also copy the half squared norms from the float32 stage (written by
-// bmu_prep_kernel, which runs before this one on the same stream; nch32 = its chunks per stage)
+// bmu_prep_kernel, which runs before this one on the same stream; nch32 = its chunks per stage).
+// tail_r > 0 (D <= 64 only): the last tail_r <= 4 features do not get a 16-feature block of their own (three MFMAs
+// for a block that is mostly padding) but one packed block whose sixteen slots hold the three products side by side,
+//     weights  [ hi(r) | hi(r) | lo(r) | 0 ... ]   against samples  [ hi(r) | lo(r) | hi(r) | 0 ... ],
+// one MFMA.  The float32 copy of the packed block (wwin) carries the r centred weights in its first slots.
 __global__ void __launch_bounds__(256) bmu_prep_split_kernel(const float* __restrict__ W, int K, int D, int kpad, int kb_count,
-                                                             int nch16, const float* __restrict__ centre,
+                                                             int tail_r, int nch16, const float* __restrict__ centre,
                                                              const float* __restrict__ stage, int stride, int stage_floats,
                                                              int nch32, char* __restrict__ stage16, int row_bytes,
                                                              int stage16_bytes, float* __restrict__ wwin)
 {
     const int e = blockIdx.x * 256 + threadIdx.x;
-    const int per_chunk = kb_count * 16, slots = nch16 * per_chunk;
+    const int per_chunk = kb_count * 16 + (tail_r ? 16 : 0), slots = nch16 * per_chunk;
     if (e < kpad * slots) {
         const int k = e / slots, sl = e - k * slots;
         const int chunk = sl / per_chunk, within = sl - chunk * per_chunk;
         const int kb = within >> 4, g = (within >> 3) & 1, t = within & 7;
-        const int f0 = 64 * chunk + 4 * (4 * kb + 2 * g + (t >> 2));      // the slot group's own first feature
-        const int f = (f0 < D - 4 ? f0 : D - 4) + (t & 3);               // its window, always inside the row
-        const bool real = k < K && f >= f0;
-        const float v = real ? W[(size_t)k * D + f] - centre[f] : 0.0f;
-        const __bf16 hi = (__bf16)v;
-        const __bf16 lo = (__bf16)(v - (float)hi);
         char* row = stage16 + ((size_t)(k / kNodesPerStage) * nch16 + chunk) * stage16_bytes +
                     (size_t)(k % kNodesPerStage) * row_bytes;
-        __bf16* cell = reinterpret_cast<__bf16*>(row + kb * 64 + g * 32) + t;
-        cell[0] = hi;
-        cell[8] = lo;
-        if (wwin) wwin[e] = v;       // the same slots in float32, [node][kb][g][8]: the winner's row for the distances
+        if (kb < kb_count) {
+            const int f0 = 64 * chunk + 4 * (4 * kb + 2 * g + (t >> 2));      // the slot group's own first feature
+            const int f = (f0 < D - 4 ? f0 : D - 4) + (t & 3);               // its window, always inside the row
+            const bool real = k < K && f >= f0;
+            const float v = real ? W[(size_t)k * D + f] - centre[f] : 0.0f;
+            const __bf16 hi = (__bf16)v;
+            const __bf16 lo = (__bf16)(v - (float)hi);
+            __bf16* cell = reinterpret_cast<__bf16*>(row + kb * 64 + g * 32) + t;
+            cell[0] = hi;
+            cell[8] = lo;
+            if (wwin) wwin[e] = v;   // the same slots in float32, [node][kb][g][8]: the winner's row for the distances
+        } else {
+            // packed tail: slot s = 8 g + t holds copy s / r of feature D - r + s % r (copies 0, 1: hi, copy 2: lo)
+            const int sidx = 8 * g + t, copy = sidx / tail_r, f = D - tail_r + sidx % tail_r;
+            const float v = (k < K && copy < 3) ? W[(size_t)k * D + f] - centre[f] : 0.0f;
+            const __bf16 hi = (__bf16)v;
+            const __bf16 lo = (__bf16)(v - (float)hi);
+            reinterpret_cast<__bf16*>(row + kb_count * 64 + g * 16)[t] = (copy == 2) ? lo : hi;
+            if (wwin) wwin[e] = (copy == 0) ? v : 0.0f;
+        }
     }
     if (e < kpad) {
         const int st = e / kNodesPerStage, r = e % kNodesPerStage;
@@ -680,12 +764,16 @@ __global__ void __launch_bounds__(256) bmu_prep_split_kernel(const float* __rest
 
 // CAND = true: the candidate pass over the first `count` entries of the re-decision list (as in bmu_tile): the same
 // scores are formed again, bit for bit, and every node whose score reaches the entry's cut is noted.
-template <int KB, int MS, bool CAND>
+// KB whole 16-feature blocks (three MFMAs each) and, with TAIL, one packed block for the last a.tail_r <= 4 features
+// (one MFMA; layout in bmu_prep_split_kernel).
+template <int KB, bool TAIL, int MS, bool CAND>
 __device__ __forceinline__ void bmu_split_tile(const BmuArgs& a, int64_t first, int64_t tile_index, unsigned int count,
                                                float4* lds4)
 {
-    constexpr int RS = split_row_bytes(KB);
-    constexpr int STAGE_F4 = split_stage_f4(KB);
+    constexpr int RS = split_row_bytes(KB, TAIL);
+    constexpr int STAGE_F4 = split_stage_f4(KB, TAIL);
+    constexpr int KBA = KB > 0 ? KB : 1;               // array lengths (no zero-length arrays when D <= 4)
+    constexpr int WROW = KB * 16 + (TAIL ? 16 : 0);    // floats of a node's row in wwin
     constexpr int PRE = STAGE_F4 / kThreads;
     const char* ldsb = reinterpret_cast<const char*>(lds4);
 
@@ -698,8 +786,8 @@ __device__ __forceinline__ void bmu_split_tile(const BmuArgs& a, int64_t first, 
 
     // This lane's 8 KB slots of a sample row, centred; slots in front of a shifted window's own features read zero
     // (they meet zero weights in the stage rows, and stay out of the norms and distances).
-    auto centred_slots = [&](const float* xr, int D, float (&v)[KB][8]) {
-        float4 raw[KB][2], cen[KB][2];
+    auto centred_slots = [&](const float* xr, int D, float (&v)[KBA][8]) {
+        float4 raw[KBA][2], cen[KBA][2];
 #pragma unroll
         for (int kb = 0; kb < KB; ++kb)
 #pragma unroll
@@ -721,8 +809,52 @@ __device__ __forceinline__ void bmu_split_tile(const BmuArgs& a, int64_t first, 
             }
     };
 
+    // the last tail_r features of a row, centred: vt[t] = feature D - tail_r + t (zero for t >= tail_r); one 16-byte
+    // load of the window [D - 4, D), which lies inside the row because D >= 4
+    const int tail_r = TAIL ? a.tail_r : 0;
+    auto tail_values = [&](const float* xr, int D, float (&vt)[4]) {
+        const float4 raw = load4(xr + D - 4), cen = load4(a.centre + D - 4);
+        const float c4[4] = {raw.x - cen.x, raw.y - cen.y, raw.z - cen.z, raw.w - cen.w};
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            const int src = 4 - tail_r + t;              // 0 .. 3 for t < tail_r
+            float v = c4[3];
+            v = src == 2 ? c4[2] : v;
+            v = src == 1 ? c4[1] : v;
+            v = src == 0 ? c4[0] : v;
+            vt[t] = t < tail_r ? v : 0.0f;
+        }
+    };
+    // this lane's eight slots of the packed block: slot s = 8 g + i holds copy s / tail_r of tail feature s % tail_r,
+    // the samples' copies being hi, lo, hi (against the weights' hi, hi, lo)
+    auto tail_pack = [&](const float (&vt)[4]) {
+        bf16x8 out;
+        __bf16 hi[4], lo[4];
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            hi[t] = (__bf16)vt[t];
+            lo[t] = (__bf16)(vt[t] - (float)hi[t]);
+        }
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const int sidx = 8 * g + i;
+            const int copy = (sidx >= tail_r) + (sidx >= 2 * tail_r) + (sidx >= 3 * tail_r);
+            const int t = sidx - copy * tail_r;
+            __bf16 h = hi[3], l = lo[3];
+            h = t == 2 ? hi[2] : h;
+            l = t == 2 ? lo[2] : l;
+            h = t == 1 ? hi[1] : h;
+            l = t == 1 ? lo[1] : l;
+            h = t == 0 ? hi[0] : h;
+            l = t == 0 ? lo[0] : l;
+            const __bf16 zero = (__bf16)0.0f;
+            out[i] = copy > 2 ? zero : (copy == 1 ? l : h);
+        }
+        return out;
+    };
+
     // ---- this wavefront's samples: centred, cut into bf16 parts, kept in registers
-    bf16x8 xh[MS][KB], xl[MS][KB];
+    bf16x8 xh[MS][KBA], xl[MS][KBA], xt[MS];
     bool valid[MS];
     const float* xrow[MS];
     float cut[MS];          // CAND
@@ -739,10 +871,17 @@ __device__ __forceinline__ void bmu_split_tile(const BmuArgs& a, int64_t first, 
         }
         const int64_t row = a.idx ? (int64_t)a.idx[ii] : ii;
         xrow[mb] = a.X + row * a.ldx;
-        float v[KB][8];
-        centred_slots(xrow[mb], a.D, v);
+        if constexpr (KB > 0) {
+            float v[KBA][8];
+            centred_slots(xrow[mb], a.D, v);
 #pragma unroll
-        for (int kb = 0; kb < KB; ++kb) split8(v[kb], xh[mb][kb], xl[mb][kb]);
+            for (int kb = 0; kb < KB; ++kb) split8(v[kb], xh[mb][kb], xl[mb][kb]);
+        }
+        if constexpr (TAIL) {
+            float vt[4];
+            tail_values(xrow[mb], a.D, vt);
+            xt[mb] = tail_pack(vt);
+        }
     }
 
     // running best / runner-up scores of this lane's half of the rows (position in the block in the low four bits
@@ -791,10 +930,21 @@ __device__ __forceinline__ void bmu_split_tile(const BmuArgs& a, int64_t first, 
 #pragma unroll
         for (int r = 0; r < 16; ++r) accB[mb][r] = kSplitPadNorm;
 
-    constexpr int GROUPS = 3 * KB;             // groups of MS MFMAs per node block
+    constexpr int GROUPS = 3 * KB + (TAIL ? 1 : 0);   // groups of MS MFMAs per node block
     constexpr int STEPS_ALL = 16 * MS;         // fold steps per node block
-    auto block = [&](floatx16 (&cur)[MS], const floatx16 (&prev)[MS], bf16x8 (&wh)[KB], bf16x8 (&wl)[KB], floatx16& c,
-                     const char* wnext, const float4* nhnext, bool more, int tile) {
+    auto block = [&](floatx16 (&cur)[MS], const floatx16 (&prev)[MS], bf16x8 (&wh)[KBA], bf16x8 (&wl)[KBA], bf16x8& wtl,
+                     floatx16& c, const char* wnext, const float4* nhnext, bool more, int tile) {
+        // the norms of the next block replace c once the block's first group has read it
+        auto next_norms = [&]() {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const float4 t = nhnext[2 * q];
+                c[4 * q + 0] = t.x;
+                c[4 * q + 1] = t.y;
+                c[4 * q + 2] = t.z;
+                c[4 * q + 3] = t.w;
+            }
+        };
 #pragma unroll
         for (int kb = 0; kb < KB; ++kb) {
 #pragma unroll
@@ -814,16 +964,7 @@ __device__ __forceinline__ void bmu_split_tile(const BmuArgs& a, int64_t first, 
                 }
                 // LDS reads of the next block, into the registers this group has just finished with
                 if (more) {
-                    if (grp == 0) {
-#pragma unroll
-                        for (int q = 0; q < 4; ++q) {
-                            const float4 t = nhnext[2 * q];
-                            c[4 * q + 0] = t.x;
-                            c[4 * q + 1] = t.y;
-                            c[4 * q + 2] = t.z;
-                            c[4 * q + 3] = t.w;
-                        }
-                    }
+                    if (grp == 0) next_norms();
                     if (term == 2) {
                         wh[kb] = *reinterpret_cast<const bf16x8*>(wnext + kb * 64);
                         wl[kb] = *reinterpret_cast<const bf16x8*>(wnext + kb * 64 + 16);
@@ -832,10 +973,27 @@ __device__ __forceinline__ void bmu_split_tile(const BmuArgs& a, int64_t first, 
                 __builtin_amdgcn_sched_barrier(0);
             }
         }
+        if constexpr (TAIL) {
+            constexpr int grp = 3 * KB;
+#pragma unroll
+            for (int mb = 0; mb < MS; ++mb) {
+                cur[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wtl, xt[mb], grp == 0 ? c : cur[mb], 0, 0, 0);
+                const int m = grp * MS + mb;
+                const int s0 = m * STEPS_ALL / (GROUPS * MS), s1 = (m + 1) * STEPS_ALL / (GROUPS * MS);
+#pragma unroll
+                for (int sidx = s0; sidx < s1; ++sidx) fold_step(prev, sidx, tile - 1);
+                if (mb + 1 < MS) __builtin_amdgcn_sched_barrier(0);
+            }
+            if (more) {
+                if (grp == 0) next_norms();
+                wtl = *reinterpret_cast<const bf16x8*>(wnext + KB * 64 - g * 16);    // (wnext carries g * 32)
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
     };
 
     // The first node block's operands; every later block's are read while the block before it is on the matrix pipe.
-    bf16x8 wh[KB], wl[KB];
+    bf16x8 wh[KBA], wl[KBA], wtl;
     floatx16 c;
     {
         const char* wrow = ldsb + j * RS + g * 32;
@@ -844,6 +1002,7 @@ __device__ __forceinline__ void bmu_split_tile(const BmuArgs& a, int64_t first, 
             wh[kb] = *reinterpret_cast<const bf16x8*>(wrow + kb * 64);
             wl[kb] = *reinterpret_cast<const bf16x8*>(wrow + kb * 64 + 16);
         }
+        if constexpr (TAIL) wtl = *reinterpret_cast<const bf16x8*>(wrow + KB * 64 - g * 16);
         const float4* nh = reinterpret_cast<const float4*>(ldsb + kNodesPerStage * RS) + g;
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
@@ -886,8 +1045,8 @@ __device__ __forceinline__ void bmu_split_tile(const BmuArgs& a, int64_t first, 
             return reinterpret_cast<const float4*>(base + kNodesPerStage * RS + nb * 32 * 4) + g;
         };
         const int tile = st * NB;
-        block(accA, accB, wh, wl, c, rows_of(wbuf, 1), norms_of(wbuf, 1), true, tile);
-        block(accB, accA, wh, wl, c, rows_of(wbuf, 2), norms_of(wbuf, 2), true, tile + 1);
+        block(accA, accB, wh, wl, wtl, c, rows_of(wbuf, 1), norms_of(wbuf, 1), true, tile);
+        block(accB, accA, wh, wl, wtl, c, rows_of(wbuf, 2), norms_of(wbuf, 2), true, tile + 1);
         {
             float4* d4 = lds4 + (buf ^ 1) * STAGE_F4 + tid;
 #define SOM_PRE_STORE(i) if constexpr (PRE > i) d4[i * kThreads] = pre##i;
@@ -896,9 +1055,9 @@ __device__ __forceinline__ void bmu_split_tile(const BmuArgs& a, int64_t first, 
 #undef SOM_PRE_STORE
         }
         __builtin_amdgcn_sched_barrier(0);
-        block(accA, accB, wh, wl, c, rows_of(wbuf, 3), norms_of(wbuf, 3), true, tile + 2);
+        block(accA, accB, wh, wl, wtl, c, rows_of(wbuf, 3), norms_of(wbuf, 3), true, tile + 2);
         __syncthreads();
-        block(accB, accA, wh, wl, c, rows_of(obuf, 0), norms_of(obuf, 0), true, tile + 3);
+        block(accB, accA, wh, wl, wtl, c, rows_of(obuf, 0), norms_of(obuf, 0), true, tile + 3);
     }
     // the last block's scores
 #pragma unroll
@@ -919,9 +1078,9 @@ __device__ __forceinline__ void bmu_split_tile(const BmuArgs& a, int64_t first, 
     // addition: 16 * 2^-24 (|C| + sum |products|).  |C| + sum |products| never exceeds |w|^2 / 2 + (|xh| + |xl|)
     // (|wh| + |wl|) <= 1.016 times the magnitude bound, hence 49 units for each of the 3 KB MFMAs.  (The largest error
     // seen on operands built against aligning, truncating and sequential adders stays well inside 16 units:
-    // tests/test_gpu_matrix_pipe.py fails on the first result outside them.)  The position bits take 16 units of
-    // the last place; -|w|^2/2 and the two centrings as in the float32 kernel.
-    const float rel = 2.0f * (3.0f * 3.8146973e-06f * 1.0078125f + (float)(49 * KB + 1) * 5.9604645e-08f + 1.9073486e-06f) +
+    // tests/test_gpu_matrix_pipe.py fails on the first result outside them.)  The packed tail block is one MFMA
+    // more.  The position bits take 16 units of the last place; -|w|^2/2 and the two centrings as in the float32 kernel.
+    const float rel = 2.0f * (3.0f * 3.8146973e-06f * 1.0078125f + (float)(49 * KB + (TAIL ? 17 : 0) + 1) * 5.9604645e-08f + 1.9073486e-06f) +
                       12.0f * 5.9604645e-08f;
     // (the window offsets are worked out again rather than carried through the stage loop in registers)
     int d_again = a.D;
@@ -950,10 +1109,25 @@ __device__ __forceinline__ void bmu_split_tile(const BmuArgs& a, int64_t first, 
             // float32 values, this lane's slots (the row is read again: it is still in the cache; the winner's
             // centred weights come from the float32 copy of the stage rows, in the same slot order)
             float xn = 0.f, part = 0.f, wn = 0.f;
-            {
-                float v[KB][8];
+            if constexpr (TAIL) {
+                // the packed block's features once each: lane half 0 takes them (its first slots of wwin hold the weights)
+                float vt[4];
+                tail_values(xrow[mb], d_again, vt);
+                const float4 w0 = *reinterpret_cast<const float4*>(a.wwin + (size_t)node * WROW + KB * 16);
+                const float w[4] = {w0.x, w0.y, w0.z, w0.w};
+#pragma unroll
+                for (int t = 0; t < 4; ++t) {
+                    const float xv = g == 0 ? vt[t] : 0.0f, wv = g == 0 ? w[t] : 0.0f;
+                    const float df = xv - wv;
+                    xn = fmaf(xv, xv, xn);
+                    part = fmaf(df, df, part);
+                    wn = fmaf(wv, wv, wn);
+                }
+            }
+            if constexpr (KB > 0) {
+                float v[KBA][8];
                 centred_slots(xrow[mb], d_again, v);
-                const float* wr = a.wwin + (size_t)node * (KB * 16) + g * 8;
+                const float* wr = a.wwin + (size_t)node * WROW + g * 8;
 #pragma unroll
                 for (int kb = 0; kb < KB; ++kb) {
                     const float4 w0 = *reinterpret_cast<const float4*>(wr + kb * 16);
@@ -997,26 +1171,26 @@ __device__ __forceinline__ void bmu_split_tile(const BmuArgs& a, int64_t first, 
                 qs2 += (double)r_part;
             }
         }
-        list_push(&a.scal[a.slot], a.recheck, a.cutv, close, i, r_best - bound);
+        if (r_valid) a.cut_all[i] = close ? r_best - bound : kNotListed;
     }
     if (a.qe) group_qe_add(a.qe_part, qs, qs2);
 }
 
 // full tiles for the workgroups below a.full_tiles, half tiles for the last partial round (as bmu_kernel)
-template <int KB, int MS>
+template <int KB, bool TAIL, int MS>
 __global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 2))) bmu_split_kernel(const BmuArgs a)
 {
     extern __shared__ float4 lds4[];
     if ((int64_t)blockIdx.x < a.full_tiles) {
-        bmu_split_tile<KB, MS, false>(a, 0, blockIdx.x, 0u, lds4);
+        bmu_split_tile<KB, TAIL, MS, false>(a, 0, blockIdx.x, 0u, lds4);
     } else if constexpr (MS > 1) {
         constexpr int64_t per_full = (int64_t)kWavesPerGroup * MS * 32;
-        bmu_split_tile<KB, MS / 2, false>(a, a.full_tiles * per_full, (int64_t)blockIdx.x - a.full_tiles, 0u, lds4);
+        bmu_split_tile<KB, TAIL, MS / 2, false>(a, a.full_tiles * per_full, (int64_t)blockIdx.x - a.full_tiles, 0u, lds4);
     }
 }
 
 // candidate pass of the split search: a fixed grid walks the tiles of the list (as bmu_cand_kernel)
-template <int KB, int MS>
+template <int KB, bool TAIL, int MS>
 __global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 2))) bmu_split_cand_kernel(const BmuArgs a)
 {
     extern __shared__ float4 lds4[];
@@ -1026,11 +1200,12 @@ __global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2
     if constexpr (MS > 1) {
         if (count <= kCandHalfTiles) {
             for (int64_t t = blockIdx.x; t * (per_tile / 2) < (int64_t)count; t += gridDim.x)
-                bmu_split_tile<KB, MS / 2, true>(a, 0, t, count, lds4);
+                bmu_split_tile<KB, TAIL, MS / 2, true>(a, 0, t, count, lds4);
             return;
         }
     }
-    for (int64_t t = blockIdx.x; t * per_tile < (int64_t)count; t += gridDim.x) bmu_split_tile<KB, MS, true>(a, 0, t, count, lds4);
+    for (int64_t t = blockIdx.x; t * per_tile < (int64_t)count; t += gridDim.x)
+        bmu_split_tile<KB, TAIL, MS, true>(a, 0, t, count, lds4);
 }
 
 // ---------------------------------------------------------------------------------------------------------
@@ -1275,7 +1450,7 @@ __device__ __forceinline__ void bmu_wide_tile(const BmuArgs& a, int64_t tile_ind
             qs2 = (double)part;
         }
     }
-    list_push(&a.scal[a.slot], a.recheck, a.cutv, close, i, bst - bound);
+    if (mine) a.cut_all[i] = close ? bst - bound : kNotListed;
     if (a.qe) group_qe_add(a.qe_part, qs, qs2);
 }
 
@@ -1527,7 +1702,7 @@ __device__ __forceinline__ void bmu_split_wide_tile(const BmuArgs& a, int64_t ti
             qs2 = (double)part;
         }
     }
-    list_push(&a.scal[a.slot], a.recheck, a.cutv, close, i, bst - bound);
+    if (mine) a.cut_all[i] = close ? bst - bound : kNotListed;
     if (a.qe) group_qe_add(a.qe_part, qs, qs2);
 }
 
@@ -1859,11 +2034,14 @@ int bmu_prepare(som_ctx* ctx, const float* W, int32_t K, int32_t D, BmuPrep* out
     // (small maps stay with the float32 search: a tile is mostly prologue and epilogue there, and the split search's
     // are the longer ones; measured at 10^7 x 50: 256 nodes 3.5 ms against 4.5, 576 nodes 5.7 against 5.1)
     const bool split = D >= 4 && K > kSplitMinNodes && ctx->search != SOM_SEARCH_FLOAT32;
-    const int kb = !split ? 0 : (nch == 1 ? (D + 15) / 16 : 4);
+    // D <= 64: whole 16-feature blocks, and a remainder of one to four features goes into one packed block (one MFMA
+    // instead of three for a block that would be mostly padding); larger remainders get a block of their own
+    const int tail_r = (split && nch == 1 && D % 16 >= 1 && D % 16 <= 4) ? D % 16 : 0;
+    const int kb = !split ? 0 : (nch == 1 ? (tail_r ? D / 16 : (D + 15) / 16) : 4);
     const int nch16 = !split ? 0 : (nch == 1 ? 1 : (D + 63) / 64);
-    const size_t stage16_one = kb ? (size_t)(kb == 1 ? split_stage_f4(1) : kb == 2 ? split_stage_f4(2) : kb == 3 ? split_stage_f4(3) : split_stage_f4(4)) * 16 : 0;
+    const size_t stage16_one = split ? (size_t)split_stage_f4(kb, tail_r > 0) * 16 : 0;
     const size_t stage16_bytes = (size_t)(kpad / kNodesPerStage) * nch16 * stage16_one;
-    const size_t wwin_bytes = nch == 1 ? (size_t)kpad * kb * 16 * sizeof(float) : 0;
+    const size_t wwin_bytes = (split && nch == 1) ? (size_t)kpad * (kb * 16 + (tail_r ? 16 : 0)) * sizeof(float) : 0;
     const size_t need = stage_bytes + wt_bytes + centre_bytes + stage16_bytes + wwin_bytes + 256;
     if (need > ctx->prep_bytes) {
         if (ctx->prep_blob) {
@@ -1883,7 +2061,8 @@ int bmu_prepare(som_ctx* ctx, const float* W, int32_t K, int32_t D, BmuPrep* out
     out->stage = (float*)(base + 256);
     out->wt = (float*)(base + 256 + stage_bytes);
     out->centre = (float*)(base + 256 + stage_bytes + wt_bytes);
-    out->stage16 = kb ? (void*)(base + 256 + stage_bytes + wt_bytes + centre_bytes) : nullptr;
+    out->stage16 = split ? (void*)(base + 256 + stage_bytes + wt_bytes + centre_bytes) : nullptr;
+    out->tail_r = tail_r;
     out->wwin = wwin_bytes ? (float*)(base + 256 + stage_bytes + wt_bytes + centre_bytes + stage16_bytes) : nullptr;
     out->nch16 = nch16;
     out->kb = kb;
@@ -1901,11 +2080,12 @@ int bmu_prepare(som_ctx* ctx, const float* W, int32_t K, int32_t D, BmuPrep* out
     hipLaunchKernelGGL(bmu_prep_kernel, dim3((unsigned)((elems + 255) / 256)), dim3(256), 0, ctx->stream, W, K, D, kpad,
                        stride, nch, stage_floats_for(stride), out->centre, out->stage, out->wt, out->scal, qe, small);
     if (int rc = check_hip(ctx, hipGetLastError(), "bmu_prep launch")) return rc;
-    if (kb) {
-        hipLaunchKernelGGL(bmu_prep_split_kernel, dim3((unsigned)(((long long)kpad * nch16 * kb * 16 + 255) / 256)),
-                           dim3(256), 0, ctx->stream, W, K, D, kpad, kb, nch16, out->centre, out->stage, stride,
-                           stage_floats_for(stride), nch, (char*)out->stage16, split_row_bytes(kb), (int)stage16_one,
-                           out->wwin);
+    if (split) {
+        const long long slots = (long long)kpad * nch16 * (kb * 16 + (tail_r ? 16 : 0));
+        hipLaunchKernelGGL(bmu_prep_split_kernel, dim3((unsigned)((slots + 255) / 256)),
+                           dim3(256), 0, ctx->stream, W, K, D, kpad, kb, tail_r, nch16, out->centre, out->stage, stride,
+                           stage_floats_for(stride), nch, (char*)out->stage16, split_row_bytes(kb, tail_r > 0),
+                           (int)stage16_one, out->wwin);
         return check_hip(ctx, hipGetLastError(), "bmu_prep_split launch");
     }
     return SOM_OK;
@@ -2072,12 +2252,12 @@ static int launch_bmu(som_ctx* ctx, const BmuArgs& a)
     return check_hip(ctx, hipGetLastError(), "bmu kernel launch");
 }
 
-template <int KB, int MS>
+template <int KB, bool TAIL, int MS>
 static int launch_bmu_split(som_ctx* ctx, const BmuArgs& a)
 {
-    constexpr size_t lds_bytes = 2 * (size_t)split_stage_f4(KB) * 16;
+    constexpr size_t lds_bytes = 2 * (size_t)split_stage_f4(KB, TAIL) * 16;
     static bool attr_set = false;
-    auto kern = bmu_split_kernel<KB, MS>;
+    auto kern = bmu_split_kernel<KB, TAIL, MS>;
     if (!attr_set) {
         if (int rc = check_hip(ctx,
                                hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -2108,12 +2288,12 @@ static int launch_bmu_split(som_ctx* ctx, const BmuArgs& a)
     return check_hip(ctx, hipGetLastError(), "bmu split kernel launch");
 }
 
-template <int KB, int MS>
+template <int KB, bool TAIL, int MS>
 static int launch_bmu_split_cand(som_ctx* ctx, const BmuArgs& a)
 {
-    constexpr size_t lds_bytes = 2 * (size_t)split_stage_f4(KB) * 16;
+    constexpr size_t lds_bytes = 2 * (size_t)split_stage_f4(KB, TAIL) * 16;
     static bool attr_set = false;
-    auto kern = bmu_split_cand_kernel<KB, MS>;
+    auto kern = bmu_split_cand_kernel<KB, TAIL, MS>;
     if (!attr_set) {
         if (int rc = check_hip(ctx,
                                hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -2127,26 +2307,34 @@ static int launch_bmu_split_cand(som_ctx* ctx, const BmuArgs& a)
     return check_hip(ctx, hipGetLastError(), "bmu split candidate kernel launch");
 }
 
-static int dispatch_bmu_split_cand(som_ctx* ctx, int kb, const BmuArgs& a)
+static int dispatch_bmu_split_cand(som_ctx* ctx, int kb, bool tail, const BmuArgs& a)
 {
-    switch (kb) {
-    case 1: return launch_bmu_split_cand<1, kSplitMS>(ctx, a);
-    case 2: return launch_bmu_split_cand<2, kSplitMS>(ctx, a);
-    case 3: return launch_bmu_split_cand<3, kSplitMS>(ctx, a);
-    case 4: return launch_bmu_split_cand<4, kSplitMS>(ctx, a);
+    switch (kb * 2 + (tail ? 1 : 0)) {
+    case 1: return launch_bmu_split_cand<0, true, kSplitMS>(ctx, a);
+    case 2: return launch_bmu_split_cand<1, false, kSplitMS>(ctx, a);
+    case 3: return launch_bmu_split_cand<1, true, kSplitMS>(ctx, a);
+    case 4: return launch_bmu_split_cand<2, false, kSplitMS>(ctx, a);
+    case 5: return launch_bmu_split_cand<2, true, kSplitMS>(ctx, a);
+    case 6: return launch_bmu_split_cand<3, false, kSplitMS>(ctx, a);
+    case 7: return launch_bmu_split_cand<3, true, kSplitMS>(ctx, a);
+    case 8: return launch_bmu_split_cand<4, false, kSplitMS>(ctx, a);
     }
-    return fail(ctx, SOM_EINVAL, "no split candidate kernel for %d blocks", kb);
+    return fail(ctx, SOM_EINVAL, "no split candidate kernel for %d blocks%s", kb, tail ? " and a tail" : "");
 }
 
-static int dispatch_bmu_split(som_ctx* ctx, int kb, const BmuArgs& a)
+static int dispatch_bmu_split(som_ctx* ctx, int kb, bool tail, const BmuArgs& a)
 {
-    switch (kb) {
-    case 1: return launch_bmu_split<1, kSplitMS>(ctx, a);
-    case 2: return launch_bmu_split<2, kSplitMS>(ctx, a);
-    case 3: return launch_bmu_split<3, kSplitMS>(ctx, a);
-    case 4: return launch_bmu_split<4, kSplitMS>(ctx, a);
+    switch (kb * 2 + (tail ? 1 : 0)) {
+    case 1: return launch_bmu_split<0, true, kSplitMS>(ctx, a);
+    case 2: return launch_bmu_split<1, false, kSplitMS>(ctx, a);
+    case 3: return launch_bmu_split<1, true, kSplitMS>(ctx, a);
+    case 4: return launch_bmu_split<2, false, kSplitMS>(ctx, a);
+    case 5: return launch_bmu_split<2, true, kSplitMS>(ctx, a);
+    case 6: return launch_bmu_split<3, false, kSplitMS>(ctx, a);
+    case 7: return launch_bmu_split<3, true, kSplitMS>(ctx, a);
+    case 8: return launch_bmu_split<4, false, kSplitMS>(ctx, a);
     }
-    return fail(ctx, SOM_EINVAL, "no split BMU kernel for %d blocks", kb);
+    return fail(ctx, SOM_EINVAL, "no split BMU kernel for %d blocks%s", kb, tail ? " and a tail" : "");
 }
 
 static int dispatch_bmu(som_ctx* ctx, int steps, const BmuArgs& a)
@@ -2221,10 +2409,10 @@ static int bmu_run_pass(som_ctx* ctx, BmuPrep& prep, BmuArgs a)
             ctx->recheck = nullptr;
             ctx->recheck_cap = 0;
         }
-        // sample positions [cap], cuts [cap], second list [cand_cap], candidate sets [cand_cap][2]; the capacity is a
+        // sample positions [cap], cuts [cap], per-sample cuts [cap], second list [cand_cap], candidate sets [cand_cap][2]; the capacity is a
         // multiple of four entries so that the 16-byte candidate sets stay aligned
         const size_t cap = ((size_t)a.m + 3) / 4 * 4, ccap = cand_cap_for(cap);
-        const size_t bytes = cap * 8 + ccap * (4 + 2 * sizeof(ulonglong2));
+        const size_t bytes = cap * 12 + ccap * (4 + 2 * sizeof(ulonglong2));
         if (hipMalloc((void**)&ctx->recheck, bytes) != hipSuccess) {
             (void)hipGetLastError();
             return fail(ctx, SOM_ENOMEM, "cannot allocate the %lld-entry recheck list", (long long)a.m);
@@ -2236,12 +2424,14 @@ static int bmu_run_pass(som_ctx* ctx, BmuPrep& prep, BmuArgs a)
     a.stride = prep.stride;
     a.stage16 = prep.stage16;
     a.wwin = prep.wwin;
+    a.tail_r = prep.tail_r;
     a.wt = prep.wt;
     a.centre = prep.centre;
     a.scal = prep.scal;
     a.recheck = ctx->recheck;
     a.cutv = (float*)(ctx->recheck + ctx->recheck_cap);
-    a.recheck2 = ctx->recheck + 2 * ctx->recheck_cap;
+    a.cut_all = (float*)(ctx->recheck + 2 * ctx->recheck_cap);
+    a.recheck2 = ctx->recheck + 3 * ctx->recheck_cap;
     a.cand = (ulonglong2*)(a.recheck2 + cand_cap_for(ctx->recheck_cap));
     a.cand_cap = (uint32_t)cand_cap_for(ctx->recheck_cap);
     // The candidate pass repeats the search for the listed samples at matrix speed (under a nanosecond per sample
@@ -2271,15 +2461,20 @@ static int bmu_run_pass(som_ctx* ctx, BmuPrep& prep, BmuArgs a)
                              : prep.steps == 25 ? launch_bmu_wide<25>(ctx, a)
                              : prep.steps == 28 ? launch_bmu_wide<28>(ctx, a)
                                                 : launch_bmu_wide<32>(ctx, a))
-                          : (prep.stage16 ? dispatch_bmu_split(ctx, prep.kb, a) : dispatch_bmu(ctx, prep.steps, a));
-    if (stop) (void)hipEventRecord(stop, ctx->stream);
+                          : (prep.stage16 ? dispatch_bmu_split(ctx, prep.kb, prep.tail_r > 0, a) : dispatch_bmu(ctx, prep.steps, a));
     if (rc) return rc;
+    if (a.K > 1) {
+        const int64_t chunks = (a.m + kListThreads * kListPerThread - 1) / (kListThreads * kListPerThread);
+        hipLaunchKernelGGL(bmu_list_kernel, dim3((unsigned)(chunks < 1024 ? chunks : 1024)), dim3(kListThreads), 0, ctx->stream, a);
+        if ((rc = check_hip(ctx, hipGetLastError(), "bmu list launch"))) return rc;
+    }
+    if (stop) (void)hipEventRecord(stop, ctx->stream);
     if (cand_possible) {
         rc = prep.nch > 1 ? (prep.stage16        ? launch_bmu_split_wide_cand(ctx, a)
                              : prep.steps == 25 ? launch_bmu_wide_cand<25>(ctx, a)
                              : prep.steps == 28 ? launch_bmu_wide_cand<28>(ctx, a)
                                                 : launch_bmu_wide_cand<32>(ctx, a))
-                          : (prep.stage16 ? dispatch_bmu_split_cand(ctx, prep.kb, a) : dispatch_bmu_cand(ctx, prep.steps, a));
+                          : (prep.stage16 ? dispatch_bmu_split_cand(ctx, prep.kb, prep.tail_r > 0, a) : dispatch_bmu_cand(ctx, prep.steps, a));
         if (rc) return rc;
         hipLaunchKernelGGL(bmu_cand_exact_kernel, dim3(2048), dim3(256), 0, ctx->stream, a);
         if ((rc = check_hip(ctx, hipGetLastError(), "bmu candidate-distance launch"))) return rc;

@@ -18,7 +18,8 @@ struct BmuPrep {
     float* stage = nullptr;        // [Kpad / 128][nch] blobs: 128 padded weight rows of a chunk, then -|w|^2 / 2
     void* stage16 = nullptr;       // bf16 hi/lo stage rows of the split search (4 <= D <= 64), else null
     float* wwin = nullptr;         // [Kpad][kb][2][8] the same slots as stage16 in float32 (centred, zeros off-window)
-    int kb = 0;                    // 16-feature blocks of a stage16 row
+    int kb = 0;                    // whole 16-feature blocks of a stage16 row
+    int tail_r = 0;                // features of the packed tail block behind them (0: none; D <= 64 only)
     int nch16 = 0;                 // chunks of a stage in stage16 (1 for D <= 64, 64-feature chunks above)
     float* wt = nullptr;           // [D][Kpad] transposed weights (as given, not centred)
     float* centre = nullptr;       // [D] column means of W; stage rows and sample registers hold values minus this
@@ -41,13 +42,15 @@ struct BmuArgs {
     int32_t stride;          // BmuPrep::stride (floats per row of the float32 stage)
     const void* stage16;     // BmuPrep::stage16 (null: float32 search)
     const float* wwin;       // BmuPrep::wwin
+    int32_t tail_r;          // BmuPrep::tail_r
     void* parts;             // split search, D > 64: the pass's samples as bf16 parts, [m][chunks * 8][hi x 8 | lo x 8]
     const float* wt;         // BmuPrep::wt
     const float* centre;     // BmuPrep::centre
     unsigned int* scal;      // BmuPrep::scal
     int32_t slot;            // which of scal[1], scal[2] this call counts into
     int64_t full_tiles;      // bmu_kernel: workgroups below this number take full tiles, the others half tiles
-    uint32_t* recheck;       // [m] sample positions to re-decide
+    float* cut_all;          // [m] per presented sample: its cut when it is to be re-decided, a NaN otherwise
+    uint32_t* recheck;       // [m] sample positions to re-decide (compacted from cut_all by bmu_list_kernel)
     // Candidate pass (long lists only): the search is repeated for the listed samples, and every node whose score
     // reaches the sample's cut is noted; direct differences are then taken over those few nodes only.
     float* cutv;             // [m] per list entry: best score minus the rounding bound

@@ -15,7 +15,7 @@ from typing import Optional
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libsom.so")
+LIB_PATH = os.environ.get("SOM_LIB") or os.path.join(_HERE, "libsom.so")   # SOM_LIB: another build of the library
 
 SOM_OK, SOM_EINVAL, SOM_ENOMEM, SOM_EHIP, SOM_EIO, SOM_ESTATE = 0, -1, -2, -3, -4, -5
 SOM_KERNEL_GAUSSIAN = 0
