@@ -339,6 +339,14 @@ __device__ __forceinline__ float vmax(float a, float b)
     return r;
 }
 
+// plain v_max3_f32, for the same reason
+__device__ __forceinline__ float vmax3(float a, float b, float c)
+{
+    float r;
+    asm("v_max3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
+    return r;
+}
+
 // ---------------------------------------------------------------------------------------------------------
 // main kernel
 // ---------------------------------------------------------------------------------------------------------
@@ -743,12 +751,25 @@ __global__ void __launch_bounds__(256) bmu_prep_split_kernel(const float* __rest
             cell[8] = lo;
             if (wwin) wwin[e] = v;   // the same slots in float32, [node][kb][g][8]: the winner's row for the distances
         } else {
-            // packed tail: slot s = 8 g + t holds copy s / r of feature D - r + s % r (copies 0, 1: hi, copy 2: lo)
+            // packed tail: slot s = 8 g + t holds copy s / r of feature D - r + s % r (copies 0, 1: hi, copy 2: lo);
+            // the three slots behind them hold -|w|^2 / 2 cut into three bf16 parts (exactly: 3 x 8 bits), which
+            // meet ones on the samples' side, so the accumulator starts from zero and no norms are read in the loop
             const int sidx = 8 * g + t, copy = sidx / tail_r, f = D - tail_r + sidx % tail_r;
             const float v = (k < K && copy < 3) ? W[(size_t)k * D + f] - centre[f] : 0.0f;
             const __bf16 hi = (__bf16)v;
             const __bf16 lo = (__bf16)(v - (float)hi);
-            reinterpret_cast<__bf16*>(row + kb_count * 64 + g * 16)[t] = (copy == 2) ? lo : hi;
+            __bf16 cellv = (copy == 2) ? lo : hi;
+            const int ns = sidx - 3 * tail_r;                               // 0, 1, 2: the norm's parts
+            if (ns >= 0 && ns < 3) {
+                float nh = stage[(size_t)(k / kNodesPerStage) * nch32 * stage_floats + (size_t)kNodesPerStage * stride +
+                                 k % kNodesPerStage];
+                if (!(nh > kSplitPadNorm)) nh = kSplitPadNorm;
+                const __bf16 p0 = (__bf16)nh;
+                const __bf16 p1 = (__bf16)(nh - (float)p0);
+                const __bf16 p2 = (__bf16)((nh - (float)p0) - (float)p1);
+                cellv = ns == 0 ? p0 : (ns == 1 ? p1 : p2);
+            }
+            reinterpret_cast<__bf16*>(row + kb_count * 64 + g * 16)[t] = cellv;
             if (wwin) wwin[e] = (copy == 0) ? v : 0.0f;
         }
     }
@@ -847,8 +868,9 @@ __device__ __forceinline__ void bmu_split_tile(const BmuArgs& a, int64_t first, 
             l = t == 1 ? lo[1] : l;
             h = t == 0 ? hi[0] : h;
             l = t == 0 ? lo[0] : l;
-            const __bf16 zero = (__bf16)0.0f;
-            out[i] = copy > 2 ? zero : (copy == 1 ? l : h);
+            const __bf16 zero = (__bf16)0.0f, one = (__bf16)1.0f;
+            const int ns = sidx - 3 * tail_r;                 // 0, 1, 2: opposite the three parts of -|w|^2 / 2
+            out[i] = copy > 2 ? ((ns >= 0 && ns < 3) ? one : zero) : (copy == 1 ? l : h);
         }
         return out;
     };
@@ -895,20 +917,25 @@ __device__ __forceinline__ void bmu_split_tile(const BmuArgs& a, int64_t first, 
         before[mb] = -INFINITY;
         tsel[mb] = 0;
     }
-    // one fold step: score r of sample block mb of the node block `tile`; three vector instructions, plus two per
-    // block for the block number
+    // one fold step: scores r0, r0 + 1 of sample block mb of the node block `tile`.  With v1, v2 the two scores (position
+    // in their low bits), the largest of {best, second, v1, v2} is max3(best, v1, v2) and, because second <= best, the
+    // second largest is max(second, med3(best, v1, v2)): five vector instructions per two scores, plus two per block
+    // for the block number
     auto fold_step = [&](const floatx16 (&acc)[MS], int step, int tile) {
-        const int mb = step >> 4, r = step & 15;
+        const int mb = step >> 3, r0 = 2 * (step & 7);
         if constexpr (CAND) {
             // (the set that the very first block "folds" holds the padding value, which reaches no cut)
-            if (acc[mb][r] >= cut[mb]) noted[mb].note(tile * 32 + 4 * g, 8 * (r >> 2) + (r & 3));
+            if (acc[mb][r0] >= cut[mb]) noted[mb].note(tile * 32 + 4 * g, 8 * (r0 >> 2) + (r0 & 3));
+            if (acc[mb][r0 + 1] >= cut[mb]) noted[mb].note(tile * 32 + 4 * g, 8 * ((r0 + 1) >> 2) + ((r0 + 1) & 3));
             return;
         }
-        if (r == 0) before[mb] = best[mb];
-        const float v = __uint_as_float((__float_as_uint(acc[mb][r]) & 0xfffffff0u) | (unsigned)r);
-        second[mb] = __builtin_amdgcn_fmed3f(best[mb], second[mb], v);
-        best[mb] = vmax(best[mb], v);
-        if (r == 15) tsel[mb] = (best[mb] > before[mb]) ? tile : tsel[mb];
+        if (r0 == 0) before[mb] = best[mb];
+        const float v1 = __uint_as_float((__float_as_uint(acc[mb][r0]) & 0xfffffff0u) | (unsigned)r0);
+        const float v2 = __uint_as_float((__float_as_uint(acc[mb][r0 + 1]) & 0xfffffff0u) | (unsigned)(r0 + 1));
+        const float mid = __builtin_amdgcn_fmed3f(best[mb], v1, v2);
+        best[mb] = vmax3(best[mb], v1, v2);
+        second[mb] = vmax(second[mb], mid);
+        if (r0 == 14) tsel[mb] = (best[mb] > before[mb]) ? tile : tsel[mb];
     };
 
     // ---- stream the nodes through LDS
@@ -931,11 +958,13 @@ __device__ __forceinline__ void bmu_split_tile(const BmuArgs& a, int64_t first, 
         for (int r = 0; r < 16; ++r) accB[mb][r] = kSplitPadNorm;
 
     constexpr int GROUPS = 3 * KB + (TAIL ? 1 : 0);   // groups of MS MFMAs per node block
-    constexpr int STEPS_ALL = 16 * MS;         // fold steps per node block
+    const floatx16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    constexpr int STEPS_ALL = 8 * MS;          // fold steps (two scores each) per node block
     auto block = [&](floatx16 (&cur)[MS], const floatx16 (&prev)[MS], bf16x8 (&wh)[KBA], bf16x8 (&wl)[KBA], bf16x8& wtl,
                      floatx16& c, const char* wnext, const float4* nhnext, bool more, int tile) {
         // the norms of the next block replace c once the block's first group has read it
         auto next_norms = [&]() {
+            if constexpr (TAIL) return;      // the norms travel inside the packed block
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
                 const float4 t = nhnext[2 * q];
@@ -954,7 +983,7 @@ __device__ __forceinline__ void bmu_split_tile(const BmuArgs& a, int64_t first, 
 #pragma unroll
                 for (int mb = 0; mb < MS; ++mb) {
                     cur[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wa, (term == 1) ? xl[mb][kb] : xh[mb][kb],
-                                                                      grp == 0 ? c : cur[mb], 0, 0, 0);
+                                                                      grp == 0 ? (TAIL ? zero16 : c) : cur[mb], 0, 0, 0);
                     // this MFMA's share of the previous block's fold, fenced so that it stays behind it
                     const int m = grp * MS + mb;
                     const int s0 = m * STEPS_ALL / (GROUPS * MS), s1 = (m + 1) * STEPS_ALL / (GROUPS * MS);
@@ -977,7 +1006,7 @@ __device__ __forceinline__ void bmu_split_tile(const BmuArgs& a, int64_t first, 
             constexpr int grp = 3 * KB;
 #pragma unroll
             for (int mb = 0; mb < MS; ++mb) {
-                cur[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wtl, xt[mb], grp == 0 ? c : cur[mb], 0, 0, 0);
+                cur[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wtl, xt[mb], grp == 0 ? zero16 : cur[mb], 0, 0, 0);
                 const int m = grp * MS + mb;
                 const int s0 = m * STEPS_ALL / (GROUPS * MS), s1 = (m + 1) * STEPS_ALL / (GROUPS * MS);
 #pragma unroll
@@ -1006,7 +1035,7 @@ __device__ __forceinline__ void bmu_split_tile(const BmuArgs& a, int64_t first, 
         const float4* nh = reinterpret_cast<const float4*>(ldsb + kNodesPerStage * RS) + g;
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
-            const float4 t = nh[2 * q];
+            const float4 t = TAIL ? float4{0.f, 0.f, 0.f, 0.f} : nh[2 * q];
             c[4 * q + 0] = t.x;
             c[4 * q + 1] = t.y;
             c[4 * q + 2] = t.z;
