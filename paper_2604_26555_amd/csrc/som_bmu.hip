@@ -35,7 +35,7 @@ typedef float floatx16 __attribute__((ext_vector_type(16)));
 constexpr int kWavesPerGroup = 4;
 constexpr int kThreads = kWavesPerGroup * 64;
 
-constexpr uint32_t kCandMin = 10240;            // shortest list the candidate pass serves
+constexpr uint32_t kCandMin = 6144;             // shortest list the candidate pass serves (about 25 us; the all-nodes pass takes 4.6 ns a sample)
 constexpr uint32_t kCandHalfTiles = 65536;      // up to this length its tiles are halved (one per compute unit and more)
 constexpr size_t kCandCapMax = (size_t)1 << 24; // longest one (bounds the candidate buffer at 512 MB + 64 MB)
 constexpr int kCandGrid = 2048;
@@ -92,16 +92,68 @@ __global__ void __launch_bounds__(1024) bmu_centre_kernel(const float* __restric
     }
 }
 
+struct SplitPrep {
+    char* stage16;       // null: no split search for this shape
+    float* wwin;         // float32 copy of the slots (D <= 64 only), or null
+    int kb_count, tail_r, nch16, row_bytes, stage16_bytes;
+};
+constexpr float kSplitPadNorm = -3.0e38f;     // padding nodes of the split search: finite, so that position bits cannot make a NaN
+
+// One slot of the rows for the bf16 matrix pipe: thread e takes (node, slot), chunks of kb_count 16-feature blocks (one
+// chunk for D <= 64, chunks of 64 features above).
+// tail_r > 0 (D <= 64 only): the last tail_r <= 4 features do not get a 16-feature block of their own (three MFMAs
+// for a block that is mostly padding) but one packed block whose sixteen slots hold the three products side by side,
+//     weights  [ hi(r) | hi(r) | lo(r) | norm parts (3) | 0 ... ]   against samples  [ hi(r) | lo(r) | hi(r) | 1 1 1 | 0 ... ],
+// one MFMA (the norm parts are written by the wavefront that sums the node's norm).  The float32 copy of the packed
+// block (wwin) carries the r centred weights in its first slots.
+__device__ __forceinline__ void split_prep_slot(const float* __restrict__ W, int K, int D, int kpad,
+                                                const float* __restrict__ centre, const SplitPrep& sp, int e)
+{
+    const int per_chunk = sp.kb_count * 16 + (sp.tail_r ? 16 : 0), slots = sp.nch16 * per_chunk;
+    if (e >= kpad * slots) return;
+    const int k = e / slots, sl = e - k * slots;
+    const int chunk = sl / per_chunk, within = sl - chunk * per_chunk;
+    const int kb = within >> 4, g = (within >> 3) & 1, t = within & 7;
+    char* row = sp.stage16 + ((size_t)(k / kNodesPerStage) * sp.nch16 + chunk) * sp.stage16_bytes +
+                (size_t)(k % kNodesPerStage) * sp.row_bytes;
+    if (kb < sp.kb_count) {
+        const int f0 = 64 * chunk + 4 * (4 * kb + 2 * g + (t >> 2));      // the slot group's own first feature
+        const int f = (f0 < D - 4 ? f0 : D - 4) + (t & 3);               // its window, always inside the row
+        const bool real = k < K && f >= f0;
+        const float v = real ? W[(size_t)k * D + f] - centre[f] : 0.0f;
+        const __bf16 hi = (__bf16)v;
+        const __bf16 lo = (__bf16)(v - (float)hi);
+        __bf16* cell = reinterpret_cast<__bf16*>(row + kb * 64 + g * 32) + t;
+        cell[0] = hi;
+        cell[8] = lo;
+        if (sp.wwin) sp.wwin[e] = v;   // the same slots in float32, [node][kb][g][8]: the winner's row for the distances
+    } else {
+        // packed tail: slot s = 8 g + t holds copy s / r of feature D - r + s % r (copies 0, 1: hi, copy 2: lo); the
+        // three slots behind them belong to the norm
+        const int sidx = 8 * g + t, copy = sidx / sp.tail_r, f = D - sp.tail_r + sidx % sp.tail_r;
+        const float v = (k < K && copy < 3) ? W[(size_t)k * D + f] - centre[f] : 0.0f;
+        const __bf16 hi = (__bf16)v;
+        const __bf16 lo = (__bf16)(v - (float)hi);
+        const int ns = sidx - 3 * sp.tail_r;
+        if (ns < 0 || ns >= 3) reinterpret_cast<__bf16*>(row + sp.kb_count * 64 + g * 16)[t] = (copy == 2) ? lo : hi;
+        if (sp.wwin) sp.wwin[e] = (copy == 0) ? v : 0.0f;
+    }
+}
+
+// The rows for the bf16 matrix pipe (stage16 != null; layout at bmu_split_tile) are written by the same launch: one thread per
+// (node, slot), and the wavefront that sums a node's norm also writes it where the split search reads it.
+
 __global__ void __launch_bounds__(256) bmu_prep_kernel(const float* __restrict__ W, int K, int D, int kpad, int stride,
                                                        int nch, int stage_floats, const float* __restrict__ centre,
                                                        float* __restrict__ stage, float* __restrict__ wt,
                                                        unsigned int* __restrict__ scal, double* __restrict__ qe,
-                                                       int32_t* __restrict__ small)
+                                                       int32_t* __restrict__ small, const SplitPrep sp)
 {
     const int e = blockIdx.x * 256 + threadIdx.x;
     const int cols = nch * stride;
     if (e < 2 && qe) qe[e] = 0.0;
     if (e < 4 && small) small[e] = 0;
+    if (sp.stage16) split_prep_slot(W, K, D, kpad, centre, sp, e);
     if (e < kpad * cols) {
         const int k = e / cols, c = e - k * cols;
         const int ch = c / stride, fl = c - ch * stride;
@@ -148,6 +200,24 @@ __global__ void __launch_bounds__(256) bmu_prep_kernel(const float* __restrict__
                 const float nh = (k < K) ? (float)(-0.5 * nrm) : -INFINITY;
                 for (int ch = 0; ch < nch; ++ch)
                     stage[((size_t)st * nch + ch) * stage_floats + (size_t)kNodesPerStage * stride + r] = nh;
+                if (sp.stage16) {
+                    const float nf = nh > kSplitPadNorm ? nh : kSplitPadNorm;
+                    for (int ch = 0; ch < sp.nch16; ++ch) {
+                        char* blob = sp.stage16 + ((size_t)st * sp.nch16 + ch) * sp.stage16_bytes;
+                        reinterpret_cast<float*>(blob + (size_t)kNodesPerStage * sp.row_bytes)[r] = nf;
+                        if (sp.tail_r) {
+                            // -|w|^2 / 2 cut into three bf16 parts (exactly: 3 x 8 bits) in the three slots behind the
+                            // packed block's features; they meet ones on the samples' side
+                            const __bf16 p0 = (__bf16)nf;
+                            const __bf16 p1 = (__bf16)(nf - (float)p0);
+                            const __bf16 p2 = (__bf16)((nf - (float)p0) - (float)p1);
+                            __bf16* cell = reinterpret_cast<__bf16*>(blob + (size_t)r * sp.row_bytes + sp.kb_count * 64);
+                            cell[3 * sp.tail_r] = p0;          // slots 8 g + t are contiguous: [g = 0: 8][g = 1: 8]
+                            cell[3 * sp.tail_r + 1] = p1;
+                            cell[3 * sp.tail_r + 2] = p2;
+                        }
+                    }
+                }
                 if (k < K) {
                     float up = (float)nrm;
                     if ((double)up < nrm) up = nextafterf(up, INFINITY);
@@ -701,7 +771,6 @@ constexpr int split_stage_f4(int kb, bool tail = false)
 {
     return ((kNodesPerStage * split_row_bytes(kb, tail) + kNodesPerStage * 4) / 16 + kThreads - 1) / kThreads * kThreads;
 }
-constexpr float kSplitPadNorm = -3.0e38f;
 constexpr int kSplitMinNodes = 384;            // SOM_SEARCH_AUTO: smaller maps use the float32 search
 constexpr size_t kPartsBytes = (size_t)8 << 30;    // workspace of the samples' bf16 parts (D > 64), per pass
 constexpr int kSplitMS = 2;
@@ -717,71 +786,6 @@ __device__ __forceinline__ void split8(const float (&v)[8], bf16x8& hi, bf16x8& 
 
 // first feature of slot group q (four consecutive features)
 __device__ __forceinline__ int split_window(int q, int D) { return 4 * q < D - 4 ? 4 * q : D - 4; }
-
-// stage16 from W: one thread per (node, slot), chunks of kb_count 16-feature blocks (one chunk for D <= 64, chunks of
-// 64 features above); the first kpad threads also copy the half squared norms from the float32 stage (written by
-// bmu_prep_kernel, which runs before this one on the same stream; nch32 = its chunks per stage).
-// tail_r > 0 (D <= 64 only): the last tail_r <= 4 features do not get a 16-feature block of their own (three MFMAs
-// for a block that is mostly padding) but one packed block whose sixteen slots hold the three products side by side,
-//     weights  [ hi(r) | hi(r) | lo(r) | 0 ... ]   against samples  [ hi(r) | lo(r) | hi(r) | 0 ... ],
-// one MFMA.  The float32 copy of the packed block (wwin) carries the r centred weights in its first slots.
-__global__ void __launch_bounds__(256) bmu_prep_split_kernel(const float* __restrict__ W, int K, int D, int kpad, int kb_count,
-                                                             int tail_r, int nch16, const float* __restrict__ centre,
-                                                             const float* __restrict__ stage, int stride, int stage_floats,
-                                                             int nch32, char* __restrict__ stage16, int row_bytes,
-                                                             int stage16_bytes, float* __restrict__ wwin)
-{
-    const int e = blockIdx.x * 256 + threadIdx.x;
-    const int per_chunk = kb_count * 16 + (tail_r ? 16 : 0), slots = nch16 * per_chunk;
-    if (e < kpad * slots) {
-        const int k = e / slots, sl = e - k * slots;
-        const int chunk = sl / per_chunk, within = sl - chunk * per_chunk;
-        const int kb = within >> 4, g = (within >> 3) & 1, t = within & 7;
-        char* row = stage16 + ((size_t)(k / kNodesPerStage) * nch16 + chunk) * stage16_bytes +
-                    (size_t)(k % kNodesPerStage) * row_bytes;
-        if (kb < kb_count) {
-            const int f0 = 64 * chunk + 4 * (4 * kb + 2 * g + (t >> 2));      // the slot group's own first feature
-            const int f = (f0 < D - 4 ? f0 : D - 4) + (t & 3);               // its window, always inside the row
-            const bool real = k < K && f >= f0;
-            const float v = real ? W[(size_t)k * D + f] - centre[f] : 0.0f;
-            const __bf16 hi = (__bf16)v;
-            const __bf16 lo = (__bf16)(v - (float)hi);
-            __bf16* cell = reinterpret_cast<__bf16*>(row + kb * 64 + g * 32) + t;
-            cell[0] = hi;
-            cell[8] = lo;
-            if (wwin) wwin[e] = v;   // the same slots in float32, [node][kb][g][8]: the winner's row for the distances
-        } else {
-            // packed tail: slot s = 8 g + t holds copy s / r of feature D - r + s % r (copies 0, 1: hi, copy 2: lo);
-            // the three slots behind them hold -|w|^2 / 2 cut into three bf16 parts (exactly: 3 x 8 bits), which
-            // meet ones on the samples' side, so the accumulator starts from zero and no norms are read in the loop
-            const int sidx = 8 * g + t, copy = sidx / tail_r, f = D - tail_r + sidx % tail_r;
-            const float v = (k < K && copy < 3) ? W[(size_t)k * D + f] - centre[f] : 0.0f;
-            const __bf16 hi = (__bf16)v;
-            const __bf16 lo = (__bf16)(v - (float)hi);
-            __bf16 cellv = (copy == 2) ? lo : hi;
-            const int ns = sidx - 3 * tail_r;                               // 0, 1, 2: the norm's parts
-            if (ns >= 0 && ns < 3) {
-                float nh = stage[(size_t)(k / kNodesPerStage) * nch32 * stage_floats + (size_t)kNodesPerStage * stride +
-                                 k % kNodesPerStage];
-                if (!(nh > kSplitPadNorm)) nh = kSplitPadNorm;
-                const __bf16 p0 = (__bf16)nh;
-                const __bf16 p1 = (__bf16)(nh - (float)p0);
-                const __bf16 p2 = (__bf16)((nh - (float)p0) - (float)p1);
-                cellv = ns == 0 ? p0 : (ns == 1 ? p1 : p2);
-            }
-            reinterpret_cast<__bf16*>(row + kb_count * 64 + g * 16)[t] = cellv;
-            if (wwin) wwin[e] = (copy == 0) ? v : 0.0f;
-        }
-    }
-    if (e < kpad) {
-        const int st = e / kNodesPerStage, r = e % kNodesPerStage;
-        float nh = stage[(size_t)st * nch32 * stage_floats + (size_t)kNodesPerStage * stride + r];
-        if (!(nh > kSplitPadNorm)) nh = kSplitPadNorm;
-        for (int chunk = 0; chunk < nch16; ++chunk)
-            reinterpret_cast<float*>(stage16 + ((size_t)st * nch16 + chunk) * stage16_bytes +
-                                     (size_t)kNodesPerStage * row_bytes)[r] = nh;
-    }
-}
 
 // CAND = true: the candidate pass over the first `count` entries of the re-decision list (as in bmu_tile): the same
 // scores are formed again, bit for bit, and every node whose score reaches the entry's cut is noted.
@@ -2106,18 +2110,21 @@ int bmu_prepare(som_ctx* ctx, const float* W, int32_t K, int32_t D, BmuPrep* out
     long long elems = (long long)kpad * nch * stride;
     if (elems < (long long)kpad * 16) elems = (long long)kpad * 16;
     if (elems < (long long)kpad * D) elems = (long long)kpad * D;
-    hipLaunchKernelGGL(bmu_prep_kernel, dim3((unsigned)((elems + 255) / 256)), dim3(256), 0, ctx->stream, W, K, D, kpad,
-                       stride, nch, stage_floats_for(stride), out->centre, out->stage, out->wt, out->scal, qe, small);
-    if (int rc = check_hip(ctx, hipGetLastError(), "bmu_prep launch")) return rc;
+    SplitPrep sp{};
     if (split) {
+        sp.stage16 = (char*)out->stage16;
+        sp.wwin = out->wwin;
+        sp.kb_count = kb;
+        sp.tail_r = tail_r;
+        sp.nch16 = nch16;
+        sp.row_bytes = split_row_bytes(kb, tail_r > 0);
+        sp.stage16_bytes = (int)stage16_one;
         const long long slots = (long long)kpad * nch16 * (kb * 16 + (tail_r ? 16 : 0));
-        hipLaunchKernelGGL(bmu_prep_split_kernel, dim3((unsigned)((slots + 255) / 256)),
-                           dim3(256), 0, ctx->stream, W, K, D, kpad, kb, tail_r, nch16, out->centre, out->stage, stride,
-                           stage_floats_for(stride), nch, (char*)out->stage16, split_row_bytes(kb, tail_r > 0),
-                           (int)stage16_one, out->wwin);
-        return check_hip(ctx, hipGetLastError(), "bmu_prep_split launch");
+        if (elems < slots) elems = slots;
     }
-    return SOM_OK;
+    hipLaunchKernelGGL(bmu_prep_kernel, dim3((unsigned)((elems + 255) / 256)), dim3(256), 0, ctx->stream, W, K, D, kpad,
+                       stride, nch, stage_floats_for(stride), out->centre, out->stage, out->wt, out->scal, qe, small, sp);
+    return check_hip(ctx, hipGetLastError(), "bmu_prep launch");
 }
 
 template <int STEPS>
