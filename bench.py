@@ -1,8 +1,8 @@
 """Benchmark of the batch-SOM epoch on one MI355X.
 
-A step is one whole epoch (weight preparation, fused BMU search + per-BMU accumulation, exact re-decision of
-near-ties, neighbourhood update) over the full sample matrix, which is resident in HBM before the timed region
-starts.  Prints ONE JSON line; `value` is presented samples per second.
+A step is one whole epoch (weight preparation, BMU search, exact re-decision of near-ties, per-BMU accumulation in a
+second pass over the samples, neighbourhood update) over the full sample matrix, which is resident in HBM before the
+timed region starts.  Prints ONE JSON line; `value` is presented samples per second.
 """
 from __future__ import annotations
 
@@ -67,7 +67,9 @@ def stream_bench(args, wl, X, W0, sig, som, pkg, torch) -> int:
         "metric": METRIC + " (host-resident samples, chunked loading path)", "value": wl.n * args.steps / dt,
         "unit": "samples/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": 1e3 * dt / max(args.steps, 1), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f32", "data": "synthetic",
+        "dtype": "bf16x2-split MFMA scores (float32 accumulate), f32 re-decision and distances, f64 sums and update" if args.search == "auto" and wl.d >= 4 and wl.k > 384
+                 else "f32 MFMA scores, f32 re-decision and distances, f64 sums and update",
+        "data": "synthetic",
         "config": {"workload": f"{wl.name}: {wl.k}-node {wl.topology} map, {wl.n} x {wl.d} float32 samples in {args.stream} "
                                f"host memory, chunks of {args.chunk_rows} rows", "samples": wl.n, "chunk_rows": args.chunk_rows},
         "host_link": {"bytes_per_epoch": nbytes, "copy_stream_GBps": nbytes * args.steps / (h2d_ms * 1e-3) / 1e9 if h2d_ms else None,
@@ -259,22 +261,54 @@ def main() -> int:
     # which matrix pipe the dominant kernel runs on decides the peak it is priced against
     split = args.search == "auto" and wl.d >= 4 and wl.k > 384     # (the library keeps small maps on float32)
     if split:
-        # padded shape: 16-feature blocks up to D = 64, chunks of 64 features above; 128-node stages
-        dpad, kpad = ((wl.d + 15) // 16 * 16) if wl.d <= 64 else ((wl.d + 63) // 64 * 64), (wl.k + 127) // 128 * 128
-        issued = 3 * 2.0 * m * kpad * dpad                 # three bf16 MFMA products per float32 product, padded shape
-        roof = {"bound": "mfma", "kernel": ("bmu_split_kernel" if wl.d <= 64 else "bmu_split_convert_kernel + bmu_split_wide_kernel") +
-                          " (scores from bf16 parts on the bf16 matrix pipe + arg-max)",
+        # MFMAs of 32 nodes x 32 samples x 16 slots the kernel issues per 32 x 32 block: three per whole 16-feature block
+        # (hi.hi, lo.hi, hi.lo), one packed block for a remainder of 1..4 features (D <= 64); chunks of 64 features above
+        if wl.d <= 64:
+            tail = 1 <= wl.d % 16 <= 4
+            n_mfma = 3 * (wl.d // 16) + 1 if tail else 3 * ((wl.d + 15) // 16)
+        else:
+            n_mfma = 12 * ((wl.d + 63) // 64)
+        kpad = (wl.k + 127) // 128 * 128
+        issued = 2.0 * m * kpad * 16 * n_mfma
+        roof = {"bound": "mfma", "kernel": ("bmu_split_kernel + bmu_list_kernel" if wl.d <= 64 else "bmu_split_convert_kernel + bmu_split_wide_kernel + bmu_list_kernel") +
+                          " (scores from bf16 parts on the bf16 matrix pipe + arg-max; the marks of the samples to re-decide compacted into a list)",
                 "achieved": achieved, "peak": PEAK_BF16_MFMA_TFLOPS, "unit": "TFLOP/s",
                 "frac": achieved / PEAK_BF16_MFMA_TFLOPS if kernel_ms else None,
                 "issued": issued / (avg_kernel_ms * 1e-3) / 1e12 if kernel_ms else None,
                 "issued_frac": issued / (avg_kernel_ms * 1e-3) / 1e12 / PEAK_BF16_MFMA_TFLOPS if kernel_ms else None,
+                "mfma_per_block": n_mfma,
                 "note": "achieved = algorithmic 2 m K D float32 flops per launch; issued = the bf16 MFMA flops the kernel "
-                        "executes for them (3 products of bf16 parts per float32 product, K and D padded to 128 and 16)"}
+                        "executes for them (mfma_per_block instructions of 32 x 32 x 16 per 32 nodes x 32 samples, K padded to 128); "
+                        "under this kernel the chip holds its power limit at a shader clock of about 1.9 GHz, the peak assumes 2.4"}
     else:
         roof = {"bound": "mfma", "kernel": "bmu_kernel (fused float32 score contraction + arg-max)",
                 "achieved": achieved, "peak": PEAK_FP32_MFMA_TFLOPS, "unit": "TFLOP/s",
                 "frac": achieved / PEAK_FP32_MFMA_TFLOPS if kernel_ms else None}
     roof.update({"avg_kernel_ms": avg_kernel_ms, "launches": len(kernel_ms)})
+    if split and kernel_ms:
+        # What the bf16 pipe sustains on this machine under its power limit (random operands, two wavefronts per SIMD): MFMAs
+        # alone, and with six vector instructions beside each (the search's fold has four to five).  Each loop runs for
+        # about 0.6 s; the last launches count.  The published peak is one MFMA per 13.3 ns and SIMD (2.4 GHz).
+        def sustained(fold_steps):
+            iters, last = 20000, []
+            t_end = time.perf_counter() + 0.6
+            while time.perf_counter() < t_end:
+                a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                a.record()
+                som.som_mfma_rate_probe(fold_steps, 2, iters)
+                b.record()
+                torch.cuda.synchronize()
+                last.append(a.elapsed_time(b))
+            return float(np.median(last[-5:])) * 1e6 / (8.0 * iters * 2)
+        simds = 4 * torch.cuda.get_device_properties(0).multi_processor_count
+        ns_alone, ns_valu = sustained(0), sustained(2)
+        ns_kernel = avg_kernel_ms * 1e6 / (issued / (2.0 * 32 * 32 * 16) / simds)
+        roof["power_limit"] = {"mfma_alone_ns": ns_alone, "mfma_with_6_vector_instructions_ns": ns_valu, "peak_ns": 13.333,
+                               "mfma_alone_frac_of_peak": 13.333 / ns_alone, "with_6_vector_instructions_frac_of_peak": 13.333 / ns_valu,
+                               "search_kernel_ns_per_mfma": ns_kernel,
+                               "note": "nanoseconds per v_mfma_f32_32x32x16_bf16 and SIMD: sustained by som_mfma_rate_probe on random "
+                                       "operands for 0.6 s each, and averaged over the whole search kernel (its prologue and epilogue "
+                                       "included)"}
     # the float32 search on the same workload, for reference (same results; its own kernel, its own peak)
     if split and not args.no_float32_reference and flops * (args.warmup + args.steps) < 2e15:
         som.som_set_search("float32")
@@ -339,16 +373,24 @@ def main() -> int:
 
     acc_ms = event_ms(lambda: som.som_accumulate(Xd, b_final, wl.k, S_t, n_t, zero_first=True))
     upd_ms = event_ms(lambda: som.som_neighborhood_update(S_t, n_t, Gd, float(sig[-1]), W_t))
+    read_ms = event_ms(lambda: som.som_read_probe(Xd))
     acc_bytes = wl.n * (wl.d * 4 + 4)
+    read_GBps = Xd.numel() * 4 / (read_ms * 1e-3) / 1e9
     stages = {"accumulate_ms": acc_ms, "accumulate_GBps": acc_bytes / (acc_ms * 1e-3) / 1e9,
               "accumulate_frac_of_hbm_peak": acc_bytes / (acc_ms * 1e-3) / 8e12, "update_ms": upd_ms,
+              "plain_read_of_X_ms": read_ms, "plain_read_GBps": read_GBps, "plain_read_frac_of_hbm_peak": read_GBps / 8e3,
+              "accumulate_frac_of_plain_read": acc_bytes / (acc_ms * 1e-3) / 1e9 / read_GBps,
               "note": "stand-alone som_accumulate over all rows with the final BMUs (algorithmic bytes: one row + "
-                      "one int32 per sample) and som_neighborhood_update, HIP events, median of 5"}
+                      "one int32 per sample) and som_neighborhood_update, HIP events, median of 5; plain_read = a kernel "
+                      "that only streams X through 16-byte loads (som_read_probe), the rate this GPU's memory system delivers"}
 
     out = {
         "metric": METRIC, "value": value, "unit": "samples/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
-        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "vs_baseline": None,
+        "dtype": ("bf16x2-split MFMA scores (float32 accumulate), f32 re-decision and distances, f64 sums and update" if split
+                  else "f32 MFMA scores, f32 re-decision and distances, f64 sums and update"),
+        "data": "synthetic",
         "config": {"workload": f"{wl.name}: {wl.k}-node {wl.topology} map, {wl.n} x {wl.d} float32 samples resident in HBM"
                                f"{'' if m_sel == wl.n else f' ({m_sel} drawn per epoch)'}, "
                                f"sigma {wl.sigma[0]}->{wl.sigma[1]} over {args.steps} epochs",

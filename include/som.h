@@ -91,6 +91,23 @@ int som_profile_read(som_ctx* ctx, float* ms, int32_t capacity, int32_t* count);
 int som_matrix_pipe_probe(som_ctx* ctx, const uint16_t* A, const uint16_t* Bt, const float* C, float* Dout, int64_t n);
 
 /*
+ * Measurement support (not an operation of the paper): a loop of v_mfma_f32_32x32x16_bf16 on pseudo-random operands,
+ * eight per trip on two accumulators, with fold_steps (0..2) fold steps of three vector instructions beside each, on one
+ * workgroup of four wavefronts per compute unit and waves_per_simd (1 or 2) of them resident.  It executes
+ * 8 * iters MFMAs per wavefront; timed by the caller over a second or more it gives the MFMA rate the chip sustains under
+ * its power limit for that instruction mix, the practical ceiling of the default BMU search's stage loop.
+ */
+int som_mfma_rate_probe(som_ctx* ctx, int fold_steps, int waves_per_simd, int iters);
+
+/*
+ * Measurement support (not an operation of the paper): one plain streaming read of `bytes` bytes at p [device] (16-byte
+ * loads, nothing else), enqueued on the context's stream.  Timed by the caller, it gives the read bandwidth the memory
+ * system delivers to a kernel on this GPU, the yardstick for the HBM-bound accumulation pass.  p and bytes must be
+ * multiples of 16.
+ */
+int som_read_probe(som_ctx* ctx, const void* p, int64_t bytes);
+
+/*
  * Best-matching-unit search (Section 3.3.1, definition of b(x)).
  *   X [device] N x D, ldx;  idx [device] m row numbers or NULL;  W [device] K x D
  *   bmu [device] int32[m], required: bmu[i] = b(x_{idx[i]})

@@ -30,7 +30,7 @@ EXPORTS = [
     "som_create", "som_destroy", "som_strerror", "som_last_error", "som_sync", "som_bmu", "som_accumulate",
     "som_neighborhood_update", "som_epoch", "som_epoch_host", "som_profile", "som_profile_read",
     "som_set_update_rule", "som_topology", "som_set_safeguard", "som_set_reproducible", "som_set_search",
-    "som_matrix_pipe_probe", "som_neighborhood_update_static", "som_epoch_file",
+    "som_matrix_pipe_probe", "som_neighborhood_update_static", "som_epoch_file", "som_read_probe", "som_mfma_rate_probe",
 ]
 
 
@@ -99,6 +99,10 @@ def load_library(path: str = LIB_PATH) -> C.CDLL:
     lib.som_epoch_host.argtypes = [vp, vp, i64, i32, i64, C.c_int, vp, i32, vp, f64, C.c_int, f64,
                                    C.POINTER(SomStats)]
     lib.som_epoch_host.restype = C.c_int
+    lib.som_mfma_rate_probe.argtypes = [vp, C.c_int, C.c_int, C.c_int]
+    lib.som_mfma_rate_probe.restype = C.c_int
+    lib.som_read_probe.argtypes = [vp, vp, i64]
+    lib.som_read_probe.restype = C.c_int
     lib.som_epoch_file.argtypes = [vp, C.c_int, i64, i64, i32, i64, vp, i32, vp, f64, C.c_int, f64, C.POINTER(SomStats)]
     lib.som_epoch_file.restype = C.c_int
     _lib = lib
@@ -214,6 +218,15 @@ class Som:
         count = C.c_int32(0)
         self._check(self.lib.som_profile_read(self._h, buf, capacity, C.byref(count)), "som_profile_read")
         return [buf[i] for i in range(min(capacity, count.value))]
+
+    def som_mfma_rate_probe(self, fold_steps=0, waves_per_simd=2, iters=20000):
+        """Enqueue a loop of 8 * iters bf16 MFMAs per wavefront on random operands (time it from outside)."""
+        self._check(self.lib.som_mfma_rate_probe(self._h, int(fold_steps), int(waves_per_simd), int(iters)), "som_mfma_rate_probe")
+
+    def som_read_probe(self, t):
+        """One plain streaming read of tensor t's bytes on the context's stream (time it from outside)."""
+        nbytes = t.numel() * t.element_size() // 16 * 16
+        self._check(self.lib.som_read_probe(self._h, C.c_void_p(t.data_ptr()), nbytes), "som_read_probe")
 
     def som_matrix_pipe_probe(self, A, Bt, Cm, Dout=None):
         """One bf16 MFMA per problem: Dout = Cm + A @ Bt^T.  A, Bt: (n, 32, 16) bf16; Cm: (n, 32, 32) float32."""

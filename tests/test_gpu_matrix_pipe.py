@@ -151,3 +151,19 @@ def test_bf16_mfma_accumulation_error_on_structured_worst_cases(som):
     worst = max(r[1] for r in report)
     print(f"largest error over {sum(r[4] for r in report)} outputs: {worst:.3f} units; charged {UNITS_CHARGED}", flush=True)
     assert worst <= UNITS_CHARGED
+
+
+def test_measurement_probes_run(som):
+    """The two rate probes (sustained MFMA loop, plain streaming read) run and give plausible figures."""
+    t = torch.ones(1 << 24, dtype=torch.float32, device="cuda")
+    for fn in (lambda: som.som_read_probe(t), lambda: som.som_mfma_rate_probe(2, 2, 2000), lambda: som.som_mfma_rate_probe(0, 1, 2000)):
+        fn()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        fn()
+        b.record()
+        torch.cuda.synchronize()
+        assert 0.0 < a.elapsed_time(b) < 50.0
+    from paper_2604_26555_amd import SomError
+    with pytest.raises(SomError):
+        som.som_mfma_rate_probe(3, 2, 10)
