@@ -17,7 +17,8 @@
  *          RNG topologies of Sections 3.2.1-3.2.2; +inf = no influence)
  *   sigma  neighbourhood radius of this epoch;  h(g) = exp(-g^2 / (2 sigma^2))
  *
- * One epoch (Eq. 3 with learning rate 1 and no momentum, then "U_j / H_j up to numerical safeguards"):
+ * One epoch (Eq. 3 with learning rate 1 and no momentum; the new weight is the ratio U_j / H_j of the paragraph
+ * after Eq. 4, guarded where H_j vanishes):
  *   Num_j = sum_k h(G[k][j]) S_k,   Den_j = sum_k h(G[k][j]) n_k,
  *   w_j  <- Num_j / Den_j   if Den_j >= eps_h,   otherwise w_j is left unchanged.
  * Grouping the per-sample sums of Eq. 3 by BMU gives exactly this form.
@@ -69,7 +70,8 @@ int som_sync(som_ctx* ctx);
 
 /*
  * Measurement support (not an operation of the paper).  While profiling is enabled the library brackets every
- * launch of its main BMU kernel with a pair of HIP events on the context's stream; som_profile_read waits for the
+ * launch of its BMU search kernel (in the default search together with the small kernel that compacts the
+ * search's per-sample marks into the re-decision list) with a pair of HIP events on the context's stream; som_profile_read waits for the
  * stream, writes up to `capacity` kernel durations in milliseconds (launch order) to ms [host], stores the number
  * of launches recorded since the last read in *count [host], and starts a new record.  A call over more rows than one
  * pass holds (2^27; fewer for D > 64 in the default search, whose pass must fit the samples' bf16 parts into 8 GB)
@@ -111,7 +113,9 @@ int som_read_probe(som_ctx* ctx, const void* p, int64_t bytes);
  * Best-matching-unit search (Section 3.3.1, definition of b(x)).
  *   X [device] N x D, ldx;  idx [device] m row numbers or NULL;  W [device] K x D
  *   bmu [device] int32[m], required: bmu[i] = b(x_{idx[i]})
- *   d2  [device] float[m] or NULL: squared distance to the BMU, recomputed by direct differences
+ *   d2  [device] float[m] or NULL: squared distance to the BMU by float32 direct differences: on the values as
+ *       given for re-decided samples, on values centred by the column means of W for the others (relative
+ *       error up to 6e-5 from the two centring roundings; samples that close to their node are re-decided)
  *   qe  [device] double[2] or NULL, OVERWRITTEN with { sum_i sqrt(d2_i), sum_i d2_i }  (the quantisation
  *       error of Section 4.1.2 is qe[0] / m)
  * The N x K distance matrix is never formed in memory.  m == 0 is allowed (qe becomes {0, 0}).
@@ -187,7 +191,7 @@ int som_set_update_rule(som_ctx* ctx, double eta, double mu, float* velocity);
 int som_topology(som_ctx* ctx, const float* W, int32_t K, int32_t D, int kind, float* G);
 
 /*
- * How the update keeps U_j / H_j finite (the "numerical safeguards" of the paragraph after Eq. 4), for every later
+ * How the update keeps U_j / H_j finite (the paragraph after Eq. 4 asks for a guard and names none), for every later
  * update on this context:
  *   SOM_SAFEGUARD_THRESHOLD (default)  w_j is left unchanged where Den_j < eps_h;
  *   SOM_SAFEGUARD_SHIFT                the exponents of updated node j are shifted by m_j = min over occupied nodes k
@@ -214,8 +218,8 @@ int som_set_reproducible(som_ctx* ctx, int on);
  * the paper).  The results are the same either way: every sample whose best two scores lie inside the worst-case
  * rounding bound of the arithmetic in use is re-decided by direct float32 differences.
  *   SOM_SEARCH_AUTO (default)  for D >= 4 and K > 384 the samples and weights are cut into two bf16 parts each
- *                              and a score is the sum of three bf16 MFMA products (error below 2^-15 of
- *                              |x||w| + |w|^2/2 for a difference of two scores); for D > 64 the samples' parts
+ *                              and a score is the sum of three bf16 MFMA products (worst-case error of a
+ *                              difference of two scores: below 2^-14 of |x||w| + |w|^2/2); for D > 64 the samples' parts
  *                              are written once per call into a library-owned workspace of up to 8 GB (rows go
  *                              through in passes that fit it); other shapes use the float32 MFMA search;
  *   SOM_SEARCH_FLOAT32         float32 MFMA for every shape.

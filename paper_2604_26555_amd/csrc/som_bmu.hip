@@ -2390,7 +2390,7 @@ static int dispatch_bmu(som_ctx* ctx, int steps, const BmuArgs& a)
 
 static int bmu_run_pass(som_ctx* ctx, BmuPrep& prep, BmuArgs a);
 
-// The rows go through in passes of at most 2^27: the re-decision workspace then stays near 1.7 GB whatever m is,
+// The rows go through in passes of at most 2^27: the re-decision workspace then stays near 2.2 GB whatever m is,
 // and a pass's list stays within what the candidate pass can hold (2^24 entries, an eighth of a pass) — one call over
 // 10^9 rows listed more than that and fell back to direct differences over all nodes for every listed sample.
 int bmu_run(som_ctx* ctx, BmuPrep& prep, BmuArgs a)
