@@ -54,5 +54,47 @@ def build(verbose: bool = True, extra_flags=()) -> str:
     return LIB
 
 
+HOST_CHECKED_DIR = os.path.join(HERE, "_build", "hostsan")
+HOST_CHECKED_LIB = os.path.join(HOST_CHECKED_DIR, "libsom_hostsan.so")
+HOST_CHECKED_DRIVER = os.path.join(HOST_CHECKED_DIR, "host_shell_check")
+# the sanitizers instrument HOST code only: every -fsanitize option rides on -Xarch_host
+HOST_SANITIZE = ["-Xarch_host", "-fsanitize=address", "-Xarch_host", "-fsanitize=undefined",
+                 "-Xarch_host", "-fno-sanitize-recover=undefined", "-Xarch_host", "-fno-omit-frame-pointer"]
+
+
+def build_host_checked(verbose: bool = True) -> str:
+    """The library's host shell (som_api.hip: argument checks, workspaces, events, chunked loaders) compiled with
+    AddressSanitizer and UndefinedBehaviorSanitizer on the host side, linked with the ordinary objects of build()
+    into libsom_hostsan.so, and the driver tests/host_shell_check.cpp linked against it.  Returns the driver's path.
+    Call build() first."""
+    os.makedirs(HOST_CHECKED_DIR, exist_ok=True)
+    cc = _hipcc()
+    out_dir = os.path.join(HERE, "_build")
+    api_obj = os.path.join(HOST_CHECKED_DIR, "som_api.o")
+    objs = [api_obj] + [os.path.join(out_dir, s.replace(".hip", ".o")) for s in SOURCES if s != "som_api.hip"]
+    missing = [o for o in objs[1:] if not os.path.exists(o)]
+    if missing:
+        raise RuntimeError(f"build() has not been run: {missing[0]} is missing")
+    clang = os.path.join(os.path.dirname(os.path.realpath(cc)), "amdclang++")
+    if not os.path.exists(clang):
+        clang = "/opt/rocm/bin/amdclang++"
+    steps = [
+        [cc, *FLAGS, "-O1", "-g", *HOST_SANITIZE, "-c", os.path.join(CSRC, "som_api.hip"), "-o", api_obj],
+        [cc, "-shared", "-fPIC", "--offload-arch=gfx950", "-fno-gpu-sanitize", *objs, "-o", HOST_CHECKED_LIB],
+        # the driver is plain host C++ (the HIP runtime API only); its link brings the sanitizer runtimes
+        [clang, "-O1", "-g", "-std=c++17", "-fno-gpu-sanitize", "-fsanitize=address", "-fsanitize=undefined",
+         "-fno-sanitize-recover=undefined", "-fno-omit-frame-pointer", "-D__HIP_PLATFORM_AMD__",
+         "-I", os.path.join(ROOT, "include"), "-I", "/opt/rocm/include", os.path.join(ROOT, "tests", "host_shell_check.cpp"),
+         "-o", HOST_CHECKED_DRIVER, "-L", HOST_CHECKED_DIR, "-lsom_hostsan", "-L", "/opt/rocm/lib", "-lamdhip64",
+         "-Wl,-rpath," + HOST_CHECKED_DIR, "-Wl,-rpath,/opt/rocm/lib"],
+    ]
+    for cmd in steps:
+        if verbose:
+            print(" ".join(cmd), flush=True)
+        subprocess.run(cmd, check=True)
+    return HOST_CHECKED_DRIVER
+
+
 if __name__ == "__main__":
     build(extra_flags=sys.argv[1:])
+    build_host_checked()

@@ -245,7 +245,8 @@ int accumulate_run(som_ctx* ctx, const float* X, int32_t D, int64_t ldx, const u
     unsigned int* part_n = (unsigned int*)((char*)ctx->acc_blob + slices_bytes);
     const int total = K * D + K;
     const dim3 rgrid((total + 63) / 64), grid((unsigned)groups);
-    static bool attr_set[2] = {false, false};
+    static bool attr_set_dev[kMaxDevices][2] = {};    // the attribute belongs to the device, not to the process
+    bool* attr_set = attr_set_dev[ctx->device];
     auto launch = [&](auto kern, auto* part_S, int slot) -> int {
         if (!attr_set[slot]) {
             if (int rc = check_hip(ctx,

@@ -255,7 +255,8 @@ static int launch_mfma(som_ctx* ctx, const float* X, int32_t D, int64_t ldx, con
                        const int32_t* bmu, int32_t K, int64_t ranges, int64_t rows_per_range, SliceT* part)
 {
     constexpr size_t lds = (size_t)kMTile * (FB * 32 + 1) * 4 + kMTile * 4 + (size_t)kMWaves * NBW * kMTile * 2;
-    static bool attr_set = false;
+    static bool attr_set_dev[kMaxDevices] = {};       // the attribute belongs to the device, not to the process
+    bool& attr_set = attr_set_dev[ctx->device];
     auto kern = accumulate_mfma_kernel<SliceT, NBW, FB>;
     if (!attr_set) {
         if (int rc = check_hip(ctx,

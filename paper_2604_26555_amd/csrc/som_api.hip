@@ -110,6 +110,7 @@ int som_create(som_ctx** out, int device, void* hip_stream)
         (void)hipGetLastError();
         return SOM_ESTATE;
     }
+    if (device >= kMaxDevices) return SOM_EINVAL;         // per-device tables of the launchers
     hipDeviceProp_t prop;
     if (hipGetDeviceProperties(&prop, device) != hipSuccess) return SOM_ESTATE;
     if (strncmp(prop.gcnArchName, "gfx950", 6) != 0) return SOM_ESTATE; // kernels are built for gfx950 only

@@ -2131,7 +2131,8 @@ template <int STEPS>
 static int launch_bmu_wide(som_ctx* ctx, const BmuArgs& a)
 {
     constexpr size_t lds_bytes = 2 * (size_t)stage_floats_for(2 * STEPS + 1) * sizeof(float);
-    static bool attr_set = false;
+    static bool attr_set_dev[kMaxDevices] = {};       // the attribute belongs to the device, not to the process
+    bool& attr_set = attr_set_dev[ctx->device];
     auto kern = bmu_wide_kernel<STEPS>;
     if (!attr_set) {
         if (int rc = check_hip(ctx,
@@ -2150,7 +2151,8 @@ static int launch_bmu_wide(som_ctx* ctx, const BmuArgs& a)
 static int launch_bmu_split_wide(som_ctx* ctx, const BmuArgs& a, int nch16)
 {
     constexpr size_t lds_bytes = 2 * (size_t)split_stage_f4(4) * 16;
-    static bool attr_set = false;
+    static bool attr_set_dev[kMaxDevices] = {};       // the attribute belongs to the device, not to the process
+    bool& attr_set = attr_set_dev[ctx->device];
     if (!attr_set) {
         if (int rc = check_hip(ctx,
                                hipFuncSetAttribute(reinterpret_cast<const void*>(bmu_split_wide_kernel),
@@ -2181,7 +2183,8 @@ template <int STEPS>
 static int launch_bmu_wide_cand(som_ctx* ctx, const BmuArgs& a)
 {
     constexpr size_t lds_bytes = 2 * (size_t)stage_floats_for(2 * STEPS + 1) * sizeof(float);
-    static bool attr_set = false;
+    static bool attr_set_dev[kMaxDevices] = {};       // the attribute belongs to the device, not to the process
+    bool& attr_set = attr_set_dev[ctx->device];
     auto kern = bmu_wide_cand_kernel<STEPS>;
     if (!attr_set) {
         if (int rc = check_hip(ctx,
@@ -2198,7 +2201,8 @@ static int launch_bmu_wide_cand(som_ctx* ctx, const BmuArgs& a)
 static int launch_bmu_split_wide_cand(som_ctx* ctx, const BmuArgs& a)
 {
     constexpr size_t lds_bytes = 2 * (size_t)split_stage_f4(4) * 16;
-    static bool attr_set = false;
+    static bool attr_set_dev[kMaxDevices] = {};       // the attribute belongs to the device, not to the process
+    bool& attr_set = attr_set_dev[ctx->device];
     if (!attr_set) {
         if (int rc = check_hip(ctx,
                                hipFuncSetAttribute(reinterpret_cast<const void*>(bmu_split_wide_cand_kernel),
@@ -2216,7 +2220,8 @@ template <int STEPS, int MS>
 static int launch_bmu_cand(som_ctx* ctx, const BmuArgs& a)
 {
     constexpr size_t lds_bytes = 2 * (size_t)stage_floats_for(2 * STEPS + 1) * sizeof(float);
-    static bool attr_set = false;
+    static bool attr_set_dev[kMaxDevices] = {};       // the attribute belongs to the device, not to the process
+    bool& attr_set = attr_set_dev[ctx->device];
     auto kern = bmu_cand_kernel<STEPS, MS>;
     if (!attr_set) {
         if (int rc = check_hip(ctx,
@@ -2292,7 +2297,8 @@ template <int KB, bool TAIL, int MS>
 static int launch_bmu_split(som_ctx* ctx, const BmuArgs& a)
 {
     constexpr size_t lds_bytes = 2 * (size_t)split_stage_f4(KB, TAIL) * 16;
-    static bool attr_set = false;
+    static bool attr_set_dev[kMaxDevices] = {};       // the attribute belongs to the device, not to the process
+    bool& attr_set = attr_set_dev[ctx->device];
     auto kern = bmu_split_kernel<KB, TAIL, MS>;
     if (!attr_set) {
         if (int rc = check_hip(ctx,
@@ -2328,7 +2334,8 @@ template <int KB, bool TAIL, int MS>
 static int launch_bmu_split_cand(som_ctx* ctx, const BmuArgs& a)
 {
     constexpr size_t lds_bytes = 2 * (size_t)split_stage_f4(KB, TAIL) * 16;
-    static bool attr_set = false;
+    static bool attr_set_dev[kMaxDevices] = {};       // the attribute belongs to the device, not to the process
+    bool& attr_set = attr_set_dev[ctx->device];
     auto kern = bmu_split_cand_kernel<KB, TAIL, MS>;
     if (!attr_set) {
         if (int rc = check_hip(ctx,
