@@ -54,7 +54,8 @@ def build(verbose: bool = True, extra_flags=()) -> str:
     return LIB
 
 
-HOST_CHECKED_DIR = os.path.join(HERE, "_build", "hostsan")
+# (beside the library, not under _build/: the driver and its library travel to the GPU machine with the tree)
+HOST_CHECKED_DIR = os.path.join(HERE, "hostsan")
 HOST_CHECKED_LIB = os.path.join(HOST_CHECKED_DIR, "libsom_hostsan.so")
 HOST_CHECKED_DRIVER = os.path.join(HOST_CHECKED_DIR, "host_shell_check")
 # the sanitizers instrument HOST code only: every -fsanitize option rides on -Xarch_host
@@ -86,7 +87,7 @@ def build_host_checked(verbose: bool = True) -> str:
          "-fno-sanitize-recover=undefined", "-fno-omit-frame-pointer", "-D__HIP_PLATFORM_AMD__",
          "-I", os.path.join(ROOT, "include"), "-I", "/opt/rocm/include", os.path.join(ROOT, "tests", "host_shell_check.cpp"),
          "-o", HOST_CHECKED_DRIVER, "-L", HOST_CHECKED_DIR, "-lsom_hostsan", "-L", "/opt/rocm/lib", "-lamdhip64",
-         "-Wl,-rpath," + HOST_CHECKED_DIR, "-Wl,-rpath,/opt/rocm/lib"],
+         "-Wl,-rpath,$ORIGIN", "-Wl,-rpath,/opt/rocm/lib"],
     ]
     for cmd in steps:
         if verbose:

@@ -392,6 +392,29 @@ def test_accumulate_matches_oracle(som, m, K, D):
             som.som_set_reproducible(False)
 
 
+@pytest.mark.parametrize("m,K,D,crowd", [(70_000, 4096, 50, None), (33_333, 2304, 50, None), (150_001, 1600, 50, 7),
+                                         (20_000, 2500, 100, None), (9000, 4096, 50, 4000), (64, 4096, 50, None)])
+def test_accumulate_on_large_maps(som, m, K, D, crowd):
+    """Maps whose per-node sums take five to twelve slabs of LDS (the paper's grid axis up to 64 x 64): ragged ends, slabs
+    that get no sample at all, one crowded node, rows wider than one feature window, fewer rows than lanes."""
+    X, _ = problem(900 + m + K, m, 64, D)
+    rng = np.random.default_rng(m + K)
+    b = rng.integers(0, K, size=m).astype(np.int32)
+    if crowd is not None:
+        b[rng.random(m) < 0.6] = crowd                              # most samples on one node; its slab holds the lot
+        b[b < K // 3] = crowd                                       # and the first slabs stay empty
+    S_or, n_or = oracle.accumulate(X, None, b, K)
+    scale = np.abs(X).max() * np.maximum(n_or, 1)[:, None]
+    S = torch.full((K, D), 7.0, dtype=torch.float64, device="cuda")
+    n = torch.full((K,), 7, dtype=torch.int64, device="cuda")
+    som.som_accumulate(dev(X), dev(b), K, S, n, zero_first=True)
+    assert (n.cpu().numpy() == n_or).all()
+    assert (np.abs(S.cpu().numpy() - S_or) <= 1e-6 * scale).all()
+    som.som_accumulate(dev(X), dev(b), K, S, n, zero_first=False)
+    assert (n.cpu().numpy() == 2 * n_or).all()
+    assert (np.abs(S.cpu().numpy() - 2 * S_or) <= 2e-6 * scale).all()
+
+
 def test_accumulate_fixed_order_is_bit_reproducible(som):
     X, _ = problem(31, 200_000, 1024, 50)
     b = np.random.default_rng(31).integers(0, 1024, size=200_000).astype(np.int32)
