@@ -218,7 +218,7 @@ def neighborhood_update_momentum(S, n, G, sigma, W, V, eta: float = 1.0, mu: flo
 
 
 def neighborhood_update_shifted(S, n, G, sigma, W):
-    """The update with the other possible reading of the "numerical safeguards" on U_j / H_j (paragraph after Eq. 4):
+    """The update with the other possible reading of the guard that the paragraph after Eq. 4 asks for on U_j / H_j:
     instead of a threshold on the denominator, every updated node j has its exponents shifted by the smallest
     squared distance to an occupied node,
 
