@@ -67,7 +67,7 @@ def stream_bench(args, wl, X, W0, sig, som, pkg, torch) -> int:
         "metric": METRIC + " (host-resident samples, chunked loading path)", "value": wl.n * args.steps / dt,
         "unit": "samples/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": 1e3 * dt / max(args.steps, 1), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "bf16x2-split MFMA scores (float32 accumulate), f32 re-decision and distances, f64 sums and update" if args.search == "auto" and wl.d >= 4 and wl.k > 384
+        "dtype": "bf16x2-split MFMA scores (float32 accumulate), f32 re-decision and distances, f64 sums and update" if args.search == "auto" and wl.d >= 4 and wl.k > 1
                  else "f32 MFMA scores, f32 re-decision and distances, f64 sums and update",
         "data": "synthetic",
         "config": {"workload": f"{wl.name}: {wl.k}-node {wl.topology} map, {wl.n} x {wl.d} float32 samples in {args.stream} "
@@ -259,7 +259,7 @@ def main() -> int:
     flops = 2.0 * m * wl.k * wl.d                          # algorithmic: 2 K D per presented sample
     achieved = flops / (avg_kernel_ms * 1e-3) / 1e12 if kernel_ms else float("nan")
     # which matrix pipe the dominant kernel runs on decides the peak it is priced against
-    split = args.search == "auto" and wl.d >= 4 and wl.k > 384     # (the library keeps small maps on float32)
+    split = args.search == "auto" and wl.d >= 4 and wl.k > 1       # (what SOM_SEARCH_AUTO means in the library)
     if split:
         # MFMAs of 32 nodes x 32 samples x 16 slots the kernel issues per 32 x 32 block: three per whole 16-feature block
         # (hi.hi, lo.hi, hi.lo), one packed block for a remainder of 1..4 features (D <= 64); chunks of 64 features above

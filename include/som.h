@@ -217,7 +217,7 @@ int som_set_reproducible(som_ctx* ctx, int on);
  * Which matrix pipe forms the scores of the best-matching-unit search (Section 3.3.1: b(x); not an operation of
  * the paper).  The results are the same either way: every sample whose best two scores lie inside the worst-case
  * rounding bound of the arithmetic in use is re-decided by direct float32 differences.
- *   SOM_SEARCH_AUTO (default)  for D >= 4 and K > 384 the samples and weights are cut into two bf16 parts each
+ *   SOM_SEARCH_AUTO (default)  for D >= 4 and K > 1 the samples and weights are cut into two bf16 parts each
  *                              and a score is the sum of three bf16 MFMA products (worst-case error of a
  *                              difference of two scores: below 2^-14 of |x||w| + |w|^2/2); for D > 64 the samples' parts
  *                              are written once per call into a library-owned workspace of up to 8 GB (rows go

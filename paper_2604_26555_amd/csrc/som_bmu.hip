@@ -741,7 +741,7 @@ __global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2
 
 // ---------------------------------------------------------------------------------------------------------
 // The same search with the contraction on the bf16 matrix pipe (this kernel: 4 <= D <= 64, bmu_split_wide_kernel
-// below: D > 64; chosen for maps above 384 nodes).
+// below: D > 64; the default for every map of more than one node).
 //
 // A float32 value v is cut into two bf16 parts, hi = bf16(v) and lo = bf16(v - hi) (both rounded to nearest, the
 // difference is exact in float32), so that |v - hi - lo| <= 2^-18 |v|.  A score then takes three bf16 MFMAs per 16
@@ -771,7 +771,8 @@ constexpr int split_stage_f4(int kb, bool tail = false)
 {
     return ((kNodesPerStage * split_row_bytes(kb, tail) + kNodesPerStage * 4) / 16 + kThreads - 1) / kThreads * kThreads;
 }
-constexpr int kSplitMinNodes = 384;            // SOM_SEARCH_AUTO: smaller maps use the float32 search
+constexpr int kSplitMinNodes = 1;              // SOM_SEARCH_AUTO: every map of more than this many nodes (measured faster than the
+                                               // float32 search from 2 x 2 nodes and from D = 4 on)
 constexpr size_t kPartsBytes = (size_t)8 << 30;    // workspace of the samples' bf16 parts (D > 64), per pass
 constexpr int kSplitMS = 2;
 

@@ -79,7 +79,7 @@ def check_bmu(b_gpu, d2_gpu, X, W, idx=None):
     (700, 150, 128), (900, 260, 111), (333, 129, 500),                         # chunks of 50, 56 and 64 features
     (900, 70, 4), (900, 70, 5), (1200, 130, 7), (800, 200, 15), (800, 200, 16), (700, 300, 31), (700, 129, 32),
     (600, 260, 47), (600, 260, 48), (500, 100, 49), (500, 100, 63),            # 16-feature blocks, shifted windows
-    (1500, 400, 4), (1500, 450, 17), (1200, 500, 33), (1100, 640, 49), (1000, 385, 64),   # the same above 384 nodes
+    (1500, 400, 4), (1500, 450, 17), (1200, 500, 33), (1100, 640, 49), (1000, 385, 64),   # more node stages
     (1200, 400, 65), (900, 500, 67), (700, 390, 127), (800, 450, 129), (600, 1024, 257), (500, 400, 1000),  # chunks of 64
 ])
 def test_bmu_matches_oracle(som, search, m, K, D):
