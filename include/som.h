@@ -119,6 +119,8 @@ int som_read_probe(som_ctx* ctx, const void* p, int64_t bytes);
  *   qe  [device] double[2] or NULL, OVERWRITTEN with { sum_i sqrt(d2_i), sum_i d2_i }  (the quantisation
  *       error of Section 4.1.2 is qe[0] / m)
  * The N x K distance matrix is never formed in memory.  m == 0 is allowed (qe becomes {0, 0}).
+ * With d2 and qe both NULL no distance is formed for samples that are not re-decided: for 4 <= D <= 64 the default
+ * search then reads every row once instead of twice.
  */
 int som_bmu(som_ctx* ctx, const float* X, int64_t N, int32_t D, int64_t ldx,
             const uint32_t* idx, int64_t m, const float* W, int32_t K,
@@ -245,7 +247,8 @@ typedef struct {
  * One whole epoch on device-resident samples: best-matching-unit search over the presented rows (the BMU indices go
  * to a library-owned buffer), per-BMU accumulation in a second pass over the same rows, then the neighbourhood update
  * of W in place.  Arguments as above.  stats is [host] or NULL; a non-NULL stats makes the call wait for the epoch
- * to finish.  m == 0 leaves W unchanged.
+ * to finish, and only then are the distances to the BMUs and their sums formed at all (they are statistics of the
+ * epoch, Section 4.1.2, not part of the update of Eq. 3-4).  m == 0 leaves W unchanged.
  */
 int som_epoch(som_ctx* ctx, const float* X, int64_t N, int32_t D, int64_t ldx,
               const uint32_t* idx, int64_t m, float* W, int32_t K,

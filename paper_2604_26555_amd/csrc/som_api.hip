@@ -386,7 +386,7 @@ int som_epoch(som_ctx* ctx, const float* X, int64_t N, int32_t D, int64_t ldx, c
     a.D = D;
     a.K = K;
     a.W = W;
-    a.qe = ctx->qe;
+    a.qe = stats ? ctx->qe : nullptr;       // no statistics asked for: the search forms no distances
     a.bmu = ctx->bmu_ws;
     if (int rc = bmu_run(ctx, prep, a)) return rc;
     if (int rc = accumulate_run(ctx, X, D, ldx, idx, m, ctx->bmu_ws, K, ctx->S, ctx->n, true)) return rc;
@@ -555,7 +555,7 @@ static int stream_epoch(som_ctx* ctx, const ChunkSource& src, int64_t N, int32_t
         a.D = D;
         a.K = K;
         a.W = W;
-        a.qe = ctx->qe;
+        a.qe = stats ? ctx->qe : nullptr;
         a.bmu = ctx->bmu_ws;
         if (int rc = bmu_run(ctx, prep, a)) return bail(rc);
         if (int rc = accumulate_run(ctx, ctx->dchunk[b], D, D, nullptr, rows, ctx->bmu_ws, K, ctx->S, ctx->n, c == 0)) return bail(rc);

@@ -884,6 +884,7 @@ __device__ __forceinline__ void bmu_split_tile(const BmuArgs& a, int64_t first, 
     bf16x8 xh[MS][KBA], xl[MS][KBA], xt[MS];
     bool valid[MS];
     const float* xrow[MS];
+    float xnorm2[MS];       // search: squared norm of the centred sample (both lane halves hold the whole row's)
     float cut[MS];          // CAND
     CandSet noted[MS];      // CAND
 #pragma unroll
@@ -898,17 +899,28 @@ __device__ __forceinline__ void bmu_split_tile(const BmuArgs& a, int64_t first, 
         }
         const int64_t row = a.idx ? (int64_t)a.idx[ii] : ii;
         xrow[mb] = a.X + row * a.ldx;
-        if constexpr (KB > 0) {
-            float v[KBA][8];
-            centred_slots(xrow[mb], a.D, v);
-#pragma unroll
-            for (int kb = 0; kb < KB; ++kb) split8(v[kb], xh[mb][kb], xl[mb][kb]);
-        }
+        float xs = 0.0f;     // this lane's slots, in the order the end of the tile adds them up
         if constexpr (TAIL) {
             float vt[4];
             tail_values(xrow[mb], a.D, vt);
             xt[mb] = tail_pack(vt);
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                const float xv = g == 0 ? vt[t] : 0.0f;      // the packed block's features once each
+                xs = fmaf(xv, xv, xs);
+            }
         }
+        if constexpr (KB > 0) {
+            float v[KBA][8];
+            centred_slots(xrow[mb], a.D, v);
+#pragma unroll
+            for (int kb = 0; kb < KB; ++kb) {
+                split8(v[kb], xh[mb][kb], xl[mb][kb]);
+#pragma unroll
+                for (int t = 0; t < 8; ++t) xs = fmaf(v[kb][t], v[kb][t], xs);
+            }
+        }
+        xnorm2[mb] = CAND ? 0.0f : xs + __shfl_xor(xs, 32);
     }
 
     // running best / runner-up scores of this lane's half of the rows (position in the block in the low four bits
@@ -1119,6 +1131,10 @@ __device__ __forceinline__ void bmu_split_tile(const BmuArgs& a, int64_t first, 
     // (the window offsets are worked out again rather than carried through the stage loop in registers)
     int d_again = a.D;
     asm volatile("" : "+s"(d_again));
+    // Squared distances (d2, the quantisation-error sums) only where the caller wants them: without them the rows are
+    // not read a second time, the sample's norm comes from the start of the tile and the winner's from the stage
+    // blob (-|w|^2 / 2 in float32 behind the rows of its stage).
+    const bool distances = a.d2 != nullptr || a.qe != nullptr;
     double qs = 0.0, qs2 = 0.0;
 #pragma unroll
     for (int mp = 0; mp < MS; mp += 2) {
@@ -1143,7 +1159,12 @@ __device__ __forceinline__ void bmu_split_tile(const BmuArgs& a, int64_t first, 
             // float32 values, this lane's slots (the row is read again: it is still in the cache; the winner's
             // centred weights come from the float32 copy of the stage rows, in the same slot order)
             float xn = 0.f, part = 0.f, wn = 0.f;
-            if constexpr (TAIL) {
+            if (!distances) {
+                xn = xnorm2[mb];
+                const char* blob = reinterpret_cast<const char*>(a.stage16) + (size_t)(node / kNodesPerStage) * STAGE_F4 * 16;
+                wn = -2.0f * reinterpret_cast<const float*>(blob + (size_t)kNodesPerStage * RS)[node % kNodesPerStage];
+            }
+            if constexpr (TAIL) if (distances) {
                 // the packed block's features once each: lane half 0 takes them (its first slots of wwin hold the weights)
                 float vt[4];
                 tail_values(xrow[mb], d_again, vt);
@@ -1158,7 +1179,7 @@ __device__ __forceinline__ void bmu_split_tile(const BmuArgs& a, int64_t first, 
                     wn = fmaf(wv, wv, wn);
                 }
             }
-            if constexpr (KB > 0) {
+            if constexpr (KB > 0) if (distances) {
                 float v[KBA][8];
                 centred_slots(xrow[mb], d_again, v);
                 const float* wr = a.wwin + (size_t)node * WROW + g * 8;
@@ -1176,9 +1197,11 @@ __device__ __forceinline__ void bmu_split_tile(const BmuArgs& a, int64_t first, 
                     }
                 }
             }
-            xn += __shfl_xor(xn, 32);
-            part += __shfl_xor(part, 32);
-            wn += __shfl_xor(wn, 32);
+            if (distances) {
+                xn += __shfl_xor(xn, 32);
+                part += __shfl_xor(part, 32);
+                wn += __shfl_xor(wn, 32);
+            }
             if (q == g) {
                 r_best = bst;
                 r_second = sec;
@@ -1195,8 +1218,9 @@ __device__ __forceinline__ void bmu_split_tile(const BmuArgs& a, int64_t first, 
         // winner's own norm; any other node's by at most rel / 2 of the bound with the largest norm.
         const float wb = fminf(sqrtf(r_wn) * 1.00001f, wmax);
         const float bound = 0.5f * rel * ((xl2 * wb + 0.5f * wb * wb) + (xl2 * wmax + 0.5f * wmax2));
+        // (a sample that close to its node is re-decided for the sake of its distance: the centring roundings)
         const float tiny = (xl2 + wmax) * (xl2 + wmax) * 3.8146973e-06f;
-        const bool close = r_valid && a.K > 1 && (!((r_best - r_second) > bound) || r_part < tiny);
+        const bool close = r_valid && a.K > 1 && (!((r_best - r_second) > bound) || (distances && r_part < tiny));
         if (r_valid) {
             a.bmu[i] = r_node;
             if (a.d2) a.d2[i] = r_part;

@@ -92,6 +92,8 @@ def test_bmu_matches_oracle(som, search, m, K, D):
     q = qe.cpu().numpy()
     assert abs(q[0] - np.sqrt(best).sum()) <= REL * max(np.sqrt(best).sum(), 1e-30)
     assert abs(q[1] - best.sum()) <= REL * max(best.sum(), 1e-30)
+    # without d2 and qe the search forms no distances (the rows are read once): the units must not care
+    check_bmu(som.som_bmu(dev(X), dev(W))[0].cpu().numpy(), None, X, W)
 
 
 def test_bmu_exact_ties_and_duplicates(som, search):
@@ -241,6 +243,9 @@ def test_bmu_at_the_edge_of_the_recheck_band(som, search, regime):
     assert not bad.any(), f"{int(bad.sum())} wrong units outside the mask, at band ratios {np.sort(ratio[bad])[:8]}"
     same = b_gpu == b
     np.testing.assert_allclose(d2.cpu().numpy()[same], best[same], rtol=REL, atol=0.0)
+    b_plain = som.som_bmu(Xd, Wd)[0].cpu().numpy()                 # the same search without distances
+    bad = (b_plain != b) & ~mask
+    assert not bad.any(), f"{int(bad.sum())} wrong units outside the mask without distances, at band ratios {np.sort(ratio[bad])[:8]}"
     st = som.som_epoch(Xd, Wd.clone(), dev(oracle.rect_lattice_distances(32, 32).astype(np.float32)), 1.0)
     print(f"{regime}/{search}: n_recheck / m = {st.n_recheck / m:.4f}", flush=True)
     # every sample inside the band must have been listed: the list is at least as long as the count inside 0.9 x bound
@@ -748,6 +753,28 @@ def test_epochs_cfg0_teacher_forced(som):
 def test_epochs_cfg1_shape_teacher_forced(som):
     wl = make_workload("cfg1", n=40_000)
     run_teacher_forced(som, wl, wl.n, [0, 1, 10, 19])
+
+
+def test_epoch_without_statistics_gives_the_same_weights(som, search):
+    """stats = NULL: the epoch forms no distances at all (one read of the rows less in the default search); the
+    weights must be those of the epoch with statistics, and of the oracle."""
+    wl = make_workload("cfg1", n=60_000)
+    X = wl.data().rows(0, wl.n)
+    W = X[draw_initial_rows(wl.seed, wl.n, wl.k)].copy()
+    G = oracle.graph_distances(wl.topology, lattice=wl.lattice)
+    Xd, Gd = dev(X), dev(G.astype(np.float32))
+    for sigma in (8.0, 1.0):
+        b_gpu = som.som_bmu(Xd, dev(W))[0].cpu().numpy()
+        b, _, mask = check_bmu(b_gpu, None, X, W)
+        ref = oracle.epoch_grouped(X, None, W, G, sigma, b=np.where(mask, b_gpu, b))
+        W_with, W_without = dev(W), dev(W)
+        st = som.som_epoch(Xd, W_with, Gd, sigma)
+        assert som.som_epoch(Xd, W_without, Gd, sigma, want_stats=False) is None
+        som.som_sync()
+        weights_close(W_with.cpu().numpy(), ref["W"], ref["den"])
+        weights_close(W_without.cpu().numpy(), ref["W"], ref["den"])
+        assert st.m == wl.n
+        W = ref["W"].astype(np.float32)
 
 
 def test_epochs_mst_and_rng_teacher_forced(som):
