@@ -2,7 +2,9 @@
 
 A step is one whole epoch (weight preparation, BMU search, exact re-decision of near-ties, per-BMU accumulation in a
 second pass over the samples, neighbourhood update) over the full sample matrix, which is resident in HBM before the
-timed region starts.  Prints ONE JSON line; `value` is presented samples per second.
+timed region starts.  Prints ONE JSON line; `value` is presented samples per second.  The timed epochs ask the library
+for no statistics (`som_epoch` with stats = NULL: the distances to the BMUs, which only the quantisation error needs, are
+then not formed); `final_qe` comes from one separate search after the timed region.
 """
 from __future__ import annotations
 
