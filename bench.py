@@ -376,15 +376,24 @@ def main() -> int:
     acc_ms = event_ms(lambda: som.som_accumulate(Xd, b_final, wl.k, S_t, n_t, zero_first=True))
     upd_ms = event_ms(lambda: som.som_neighborhood_update(S_t, n_t, Gd, float(sig[-1]), W_t))
     read_ms = event_ms(lambda: som.som_read_probe(Xd))
+    # the whole search (weight preparation, search kernel, re-decision) with and without the distances to the BMUs, which
+    # only statistics need: the timed epochs run without them
+    d2_t = torch.empty(b_final.numel(), dtype=torch.float32, device="cuda")
+    search_plain_ms = event_ms(lambda: som.som_bmu(Xd, Wd, idx=subsets[0] if subsets else None, bmu=b_final[:m_sel]))
+    search_dist_ms = event_ms(lambda: som.som_bmu(Xd, Wd, idx=subsets[0] if subsets else None, bmu=b_final[:m_sel], d2=d2_t[:m_sel], qe=qe))
+    del d2_t
     acc_bytes = wl.n * (wl.d * 4 + 4)
     read_GBps = Xd.numel() * 4 / (read_ms * 1e-3) / 1e9
     stages = {"accumulate_ms": acc_ms, "accumulate_GBps": acc_bytes / (acc_ms * 1e-3) / 1e9,
               "accumulate_frac_of_hbm_peak": acc_bytes / (acc_ms * 1e-3) / 8e12, "update_ms": upd_ms,
+              "search_ms": search_plain_ms, "search_with_distances_ms": search_dist_ms,
               "plain_read_of_X_ms": read_ms, "plain_read_GBps": read_GBps, "plain_read_frac_of_hbm_peak": read_GBps / 8e3,
               "accumulate_frac_of_plain_read": acc_bytes / (acc_ms * 1e-3) / 1e9 / read_GBps,
               "note": "stand-alone som_accumulate over all rows with the final BMUs (algorithmic bytes: one row + "
                       "one int32 per sample) and som_neighborhood_update, HIP events, median of 5; plain_read = a kernel "
-                      "that only streams X through 16-byte loads (som_read_probe), the rate this GPU's memory system delivers"}
+                      "that only streams X through 16-byte loads (som_read_probe), the rate this GPU's memory system delivers; "
+                      "search_ms = som_bmu on the final weights (preparation, search, re-decision) as the timed epochs run it, "
+                      "search_with_distances_ms = the same with d2 and the quantisation-error sums asked for"}
 
     out = {
         "metric": METRIC, "value": value, "unit": "samples/s", "n_gpus": 1, "steps": args.steps,
