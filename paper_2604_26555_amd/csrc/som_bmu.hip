@@ -1110,9 +1110,78 @@ __device__ __forceinline__ void bmu_split_tile(const BmuArgs& a, int64_t first, 
     for (int sidx = 0; sidx < STEPS_ALL; ++sidx) fold_step(accB, sidx, nstages * (kNodesPerStage / 32) - 1);
 
     if constexpr (CAND) {
+        // Direct float32 differences over the nodes this lane noted for its sample (the true winner is among the two
+        // lane halves' candidates: its score lies within the rounding bound of the best one found), features in order,
+        // lowest distance, then lowest node index; the halves are joined at the end.  An entry whose set overflowed
+        // in either half (more than seven candidates) or that noted nothing goes to the second list, which the
+        // all-nodes kernel serves.  The row stays in registers across the candidates: D <= 64.
+        double qs = 0.0, qs2 = 0.0;
 #pragma unroll
-        for (int mb = 0; mb < MS; ++mb)
-            if (valid[mb]) a.cand[(size_t)(wave0 + mb * 32 + j) * 2 + g] = noted[mb].packed();
+        for (int mb = 0; mb < MS; ++mb) {
+            const int n = noted[mb].n;
+            const bool over = n >= kCandSlots;
+            const int mine = (valid[mb] && !over) ? n : 0;
+            const float* xr = xrow[mb];
+            const int D = a.D, whole = D / 4, rest = D - 4 * whole;
+            float4 xv[16];
+#pragma unroll
+            for (int q = 0; q < 16; ++q) xv[q] = (mine > 0 && q < whole) ? load4(xr + 4 * q) : float4{0.f, 0.f, 0.f, 0.f};
+            // the last one to three features: the window [D - 4, D), its leading elements already counted
+            const float4 xt4 = (mine > 0 && rest > 0) ? load4(xr + D - 4) : float4{0.f, 0.f, 0.f, 0.f};
+            float bd = INFINITY;
+            int bk = 0x7fffffff;
+            for (int t = 0; t < kCandSlots - 1; ++t) {
+                if (__ballot(t < mine) == 0ull) break;
+                if (t < mine) {
+                    const unsigned long long word = t < 4 ? noted[mb].lo >> (16 * t) : noted[mb].hi >> (16 * (t - 4));
+                    const int id = (int)(word & 0xffffull);
+                    if (id < a.K) {
+                        const float* wr = a.W + (size_t)id * D;
+                        float d = 0.0f;
+#pragma unroll
+                        for (int q = 0; q < 16; ++q) {
+                            if (q < whole) {
+                                const float4 w4 = load4(wr + 4 * q);
+                                const float d0 = xv[q].x - w4.x, d1 = xv[q].y - w4.y, d2 = xv[q].z - w4.z, d3 = xv[q].w - w4.w;
+                                d = fmaf(d0, d0, d);
+                                d = fmaf(d1, d1, d);
+                                d = fmaf(d2, d2, d);
+                                d = fmaf(d3, d3, d);
+                            }
+                        }
+                        if (rest > 0) {
+                            const float4 w4 = load4(wr + D - 4);
+                            const float d1 = xt4.y - w4.y, d2 = xt4.z - w4.z, d3 = xt4.w - w4.w;
+                            if (rest > 2) d = fmaf(d1, d1, d);
+                            if (rest > 1) d = fmaf(d2, d2, d);
+                            d = fmaf(d3, d3, d);
+                        }
+                        if (d < bd || (d == bd && id < bk)) {
+                            bd = d;
+                            bk = id;
+                        }
+                    }
+                }
+            }
+            const float od = __shfl_xor(bd, 32);
+            const int ok = __shfl_xor(bk, 32);
+            const bool oover = __shfl_xor(over ? 1 : 0, 32) != 0;
+            if (od < bd || (od == bd && ok < bk)) {
+                bd = od;
+                bk = ok;
+            }
+            const bool served = !over && !oover && bk < a.K;
+            const bool writer = valid[mb] && g == 0;
+            const int64_t i = writer ? (int64_t)a.recheck[wave0 + mb * 32 + j] : 0;
+            if (writer && served) {
+                a.bmu[i] = bk;
+                if (a.d2) a.d2[i] = bd;
+                qs += sqrt((double)bd);
+                qs2 += (double)bd;
+            }
+            list_push(&a.scal[a.slot2], a.recheck2, nullptr, writer && !served, i, 0.0f);
+        }
+        if (a.qe) group_qe_add(a.qe_part, qs, qs2);
         return;
     }
     // ---- join the two half-wavefronts, then lane (j, g) finishes block mp + g
@@ -2544,8 +2613,12 @@ static int bmu_run_pass(som_ctx* ctx, BmuPrep& prep, BmuArgs a)
                                                 : launch_bmu_wide_cand<32>(ctx, a))
                           : (prep.stage16 ? dispatch_bmu_split_cand(ctx, prep.kb, prep.tail_r > 0, a) : dispatch_bmu_cand(ctx, prep.steps, a));
         if (rc) return rc;
-        hipLaunchKernelGGL(bmu_cand_exact_kernel, dim3(2048), dim3(256), 0, ctx->stream, a);
-        if ((rc = check_hip(ctx, hipGetLastError(), "bmu candidate-distance launch"))) return rc;
+        // (the split search for D <= 64 takes the direct differences over its candidates at the end of the candidate
+        // tile itself; the others hand their candidate sets to a kernel of their own)
+        if (!(prep.stage16 && prep.nch == 1)) {
+            hipLaunchKernelGGL(bmu_cand_exact_kernel, dim3(2048), dim3(256), 0, ctx->stream, a);
+            if ((rc = check_hip(ctx, hipGetLastError(), "bmu candidate-distance launch"))) return rc;
+        }
     }
     if (a.K > 1) {
         hipLaunchKernelGGL(bmu_exact_kernel, dim3(1024), dim3(256), 0, ctx->stream, a);
