@@ -19,9 +19,13 @@
 // (roundings) * 2^-24 * (|x - c| max|w - c| + max|w - c|^2 / 2) in a score, so a sample whose best two scores are
 // closer than that worst-case bound is put on a list and re-decided by direct differences sum_d (x_d - w_kd)^2 on
 // the values as given (lowest index wins ties): over every node (bmu_exact_kernel), or, for long lists, over the
-// few nodes whose score lies inside the bound, which a second pass of the search collects (bmu_cand_kernel,
-// bmu_cand_exact_kernel).  For all other samples the winner's squared distance is recomputed by direct differences
-// as well, so the reported distances never carry the cancellation error of the score form.
+// few nodes whose score lies inside the bound, which a second pass of the search collects (bmu_cand_kernel +
+// bmu_cand_exact_kernel; the bf16 search for D <= 64 takes the differences at the end of its candidate tile).
+// Where the caller asks for distances, the winner's squared distance of all other samples is recomputed by direct
+// differences as well, so the reported distances never carry the cancellation error of the score form.
+//
+// The default search (bmu_split_kernel and bmu_split_wide_kernel further down) is the same scheme with the
+// contraction on the bf16 matrix pipe, samples and weights cut into two bf16 parts each.
 #include "som_internal.hpp"
 
 #include <hip/amd_detail/amd_hip_unsafe_atomics.h>
