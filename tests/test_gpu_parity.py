@@ -112,6 +112,8 @@ def test_bmu_index_list_and_leading_dimension(som, search):
     Xd = dev(pad)[:, :10]
     b_gpu, _, _ = som.som_bmu(Xd, dev(W), idx=dev(idx.astype(np.int32)), d2=d2)
     check_bmu(b_gpu.cpu().numpy(), d2.cpu().numpy(), X, W, idx)
+    b_plain, _, _ = som.som_bmu(Xd, dev(W), idx=dev(idx.astype(np.int32)))       # no distances asked for
+    check_bmu(b_plain.cpu().numpy(), None, X, W, idx)
 
 
 def test_bmu_large_norm_small_gap(som, search):
