@@ -68,6 +68,7 @@ def test_full_size_bmu_sampled_against_brute_force(som, cfg1, epochs, search):
     d2 = torch.empty(wl.n, dtype=torch.float32, device="cuda")
     qe = torch.zeros(2, dtype=torch.float64, device="cuda")
     b_gpu, _, _ = som.som_bmu(Xd, Wd, d2=d2, qe=qe)
+    b_plain = som.som_bmu(Xd, Wd)[0].cpu().numpy()      # as the benchmark's epochs run it: no distances asked for
     som.som_set_search("auto")
     b_gpu, d2 = b_gpu.cpu().numpy(), d2.cpu().numpy()
     rows = np.sort(np.random.default_rng(77 + epochs).choice(wl.n, 4000, replace=False))
@@ -75,6 +76,9 @@ def test_full_size_bmu_sampled_against_brute_force(som, cfg1, epochs, search):
     b, best, second = oracle.bmu(X[rows], W)
     mask = oracle.near_tie_mask(best, second)
     assert ((b_gpu[rows] == b) | mask).all()
+    assert ((b_plain[rows] == b) | mask).all()
+    assert b_plain.min() >= 0 and b_plain.max() < wl.k
+    print(f"units with and without distances differ on {int((b_plain != b_gpu).sum())} of {wl.n} samples", flush=True)
     same = b_gpu[rows] == b
     np.testing.assert_allclose(d2[rows][same], best[same], rtol=1e-4, atol=1e-12)
     # properties at full size
