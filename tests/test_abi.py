@@ -58,3 +58,24 @@ def test_product_never_imports_the_oracle():
             if f.endswith((".py", ".hip", ".hpp", ".h")):
                 src = open(os.path.join(dirpath, f)).read()
                 assert "oracle" not in src, os.path.join(dirpath, f)
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """bench.py measures one GPU; asked for more it says so and exits instead of printing a number."""
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
+    assert r.returncode != 0 and "one GPU" in (r.stdout + r.stderr) and "{" not in r.stdout
+
+
+def test_nothing_committed_points_at_the_working_folder():
+    """Probes and helper scripts live in a git-ignored working folder; no committed source may import, read or run them."""
+    import subprocess
+    tracked = subprocess.run(["git", "ls-files"], cwd=ROOT, capture_output=True, text=True).stdout.split()
+    if not tracked:
+        pytest.skip("not a git checkout")
+    needle = "_" + "work/"
+    for f in tracked:
+        reviews = ("VERDICT.md", "ADVICE.md", "SURVEY.md", "BASELINE.md", "BASELINE.json")      # not this build's own files
+        if f.endswith((".py", ".hip", ".hpp", ".h", ".cpp", ".md", ".json")) and f not in reviews:
+            assert needle not in open(os.path.join(ROOT, f), errors="ignore").read(), f
